@@ -1,0 +1,113 @@
+/*
+ * CPU oracle for the mixed-precision integer (MIP) GEMM.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the checker the GPU library is
+ * compared against; the product never calls it, links it or falls back to it.
+ * It shares no code, header, table or helper with the HIP path.
+ *
+ * What it computes (paper, abstract and Section 5 "Micro-kernel for
+ * DOT-oriented SIMD units and MIP": inputs multiplied in INT8, result
+ * accumulated in INT32; Section 3, Figure "Reference GEMM algorithm":
+ * C += A * B):
+ *
+ *     for 0 <= i < m, 0 <= j < n:
+ *         S(i,j) = sum_{p=0}^{k-1} (int32) A(i,p) * (int32) B(p,j)
+ *         C(i,j) = S(i,j)            (overwrite)
+ *         C(i,j) = C(i,j) + S(i,j)   (accumulate)
+ *
+ * The paper's blocked algorithm is a reordering of this sum, and integer
+ * addition is associative, so the method reaches exactly this definition; the
+ * oracle is therefore the definition written out as three plain loops, with no
+ * blocking, packing or reordering.
+ *
+ * Readings where the paper is silent:
+ *   - int32 overflow: two's-complement wraparound (arithmetic modulo 2^32),
+ *     done here in uint32_t so that C leaves no behaviour undefined.
+ *   - every int8 product is exact in int32 (no int16 intermediate as in the
+ *     ARMv8.0 kernel of Section 5.1, which is an artefact of that ISA).
+ *   - a uint8 operand is taken at face value, 0..255 (Section 7.3 describes a
+ *     scale-only quantization scheme: no zero point is subtracted).
+ *   - m == 0 or n == 0: nothing is touched.  k == 0: the sum is empty, so
+ *     overwrite stores 0 and accumulate leaves C as it is.
+ *
+ * Storage (Section 3, last paragraph: row- or column-major for all three
+ * operands, explicit leading dimension as in the ldC of Section 4):
+ *     row-major    X(r,c) = X[r*ld + c]
+ *     column-major X(r,c) = X[r + c*ld]
+ * ld is counted in elements.  Elements of C outside the m x n matrix (the
+ * leading-dimension padding) are never written.
+ *
+ * Parity pins (tests/test_oracle_pins.py): brute-force int64 dot products,
+ * exhaustive 1x1x1 over all byte pairs, constant-matrix closed forms,
+ * identity / permutation matrices, row and column sums, linearity and k-split,
+ * layout identities, the u8 <-> s8 identity, numpy int64 matmul, the
+ * instruction-tile definitions the paper prints (sdot, vmadot, AMX tile) and a
+ * hand-worked example stored under tests/golden/.
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+enum { ORACLE_ROW_MAJOR = 0, ORACLE_COL_MAJOR = 1 };
+enum { ORACLE_OVERWRITE = 0, ORACLE_ACCUMULATE = 1 };
+
+/* position of X(r,c) in its buffer */
+static size_t at(int64_t r, int64_t c, int64_t ld, int order)
+{
+    if (order == ORACLE_ROW_MAJOR)
+        return (size_t)r * (size_t)ld + (size_t)c;
+    return (size_t)r + (size_t)c * (size_t)ld;
+}
+
+/* one byte read as int8 or as uint8, widened to 32 bits before any multiply */
+static uint32_t widen(const void *X, size_t pos, int is_unsigned)
+{
+    if (is_unsigned)
+        return (uint32_t)((const uint8_t *)X)[pos];
+    return (uint32_t)(int32_t)((const int8_t *)X)[pos];
+}
+
+/*
+ * Returns 0, or -1 when an argument is malformed (negative size, leading
+ * dimension too small, unknown order or mode).  Host pointers only.
+ */
+int oracle_mip_gemm(int a_unsigned, int b_unsigned,
+                    int64_t m, int64_t n, int64_t k,
+                    const void *A, int64_t lda, int orderA,
+                    const void *B, int64_t ldb, int orderB,
+                    int32_t *C, int64_t ldc, int orderC,
+                    int mode)
+{
+    if (m < 0 || n < 0 || k < 0) return -1;
+    if (orderA != ORACLE_ROW_MAJOR && orderA != ORACLE_COL_MAJOR) return -1;
+    if (orderB != ORACLE_ROW_MAJOR && orderB != ORACLE_COL_MAJOR) return -1;
+    if (orderC != ORACLE_ROW_MAJOR && orderC != ORACLE_COL_MAJOR) return -1;
+    if (mode != ORACLE_OVERWRITE && mode != ORACLE_ACCUMULATE) return -1;
+    if (lda < (orderA == ORACLE_ROW_MAJOR ? k : m)) return -1;
+    if (ldb < (orderB == ORACLE_ROW_MAJOR ? n : k)) return -1;
+    if (ldc < (orderC == ORACLE_ROW_MAJOR ? n : m)) return -1;
+
+    uint32_t *Cu = (uint32_t *)C;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        if (mode == ORACLE_OVERWRITE)
+            for (int64_t j = 0; j < n; ++j)
+                Cu[at(i, j, ldc, orderC)] = 0u;
+        for (int64_t p = 0; p < k; ++p) {
+            uint32_t a = widen(A, at(i, p, lda, orderA), a_unsigned);
+            for (int64_t j = 0; j < n; ++j) {
+                uint32_t b = widen(B, at(p, j, ldb, orderB), b_unsigned);
+                Cu[at(i, j, ldc, orderC)] += a * b;
+            }
+        }
+    }
+    return 0;
+}
+
+/* number of threads the parallel loop above runs with (for the bench report) */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
