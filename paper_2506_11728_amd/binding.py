@@ -1,0 +1,133 @@
+"""Thin ctypes binding of the C ABI declared in ``include/mipgemm.h``.
+
+Argument marshalling only: every step of the GEMM runs in the HIP kernels of
+``libmipgemm.so``.  Operands are device pointers: pass torch CUDA tensors (their
+``data_ptr()`` is taken) or plain integer addresses.  PyTorch appears here only
+as the owner of device memory and streams.
+
+There is no fallback: if the shared library has not been built
+(``python -m paper_2506_11728_amd.build``) loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+ROW_MAJOR, COL_MAJOR = 0, 1
+OVERWRITE, ACCUMULATE = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmipgemm.so")
+_lock = threading.Lock()
+_lib = None
+
+_GEMM_ARGTYPES = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                  ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                  ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                  ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                  ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+
+
+class MipGemmError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("mipgemm error %d: %s" % (code, text))
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def exported_symbols():
+    """Names include/mipgemm.h declares; the library must export every one."""
+    return ["mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32",
+            "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name"]
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    with _lock:
+        if _lib is None:
+            if not os.path.exists(_LIB_PATH):
+                raise ImportError(
+                    "libmipgemm.so is not built (%s); run `python -m paper_2506_11728_amd.build`. "
+                    "There is no CPU fallback." % _LIB_PATH)
+            lib = ctypes.CDLL(_LIB_PATH)
+            for name in ("mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32"):
+                fn = getattr(lib, name)
+                fn.restype = ctypes.c_int
+                fn.argtypes = _GEMM_ARGTYPES
+            lib.mipgemm_workspace_size.restype = ctypes.c_size_t
+            lib.mipgemm_workspace_size.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+            lib.mipgemm_strerror.restype = ctypes.c_char_p
+            lib.mipgemm_strerror.argtypes = [ctypes.c_int]
+            lib.mipgemm_variant_name.restype = ctypes.c_char_p
+            lib.mipgemm_variant_name.argtypes = ([ctypes.c_int64] * 3
+                                                 + [ctypes.c_int64, ctypes.c_int] * 3
+                                                 + [ctypes.c_int] * 3)
+            _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x or None
+    return x.data_ptr() or None          # torch tensor (device memory)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None    # torch.cuda.Stream
+
+
+def _call(name, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+          workspace, workspace_bytes, stream, check):
+    rc = getattr(load_library(), name)(
+        m, n, k, _ptr(A), lda, orderA, _ptr(B), ldb, orderB, _ptr(C), ldc, orderC, mode,
+        _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_s8s8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, check=True):
+    """C = [C +] A * B, int8 x int8 -> int32 (see include/mipgemm.h)."""
+    return _call("mipgemm_s8s8s32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check)
+
+
+def mipgemm_u8s8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, check=True):
+    """Same with an unsigned A."""
+    return _call("mipgemm_u8s8s32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check)
+
+
+def mipgemm_s8u8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, check=True):
+    """Same with an unsigned B."""
+    return _call("mipgemm_s8u8s32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check)
+
+
+def mipgemm_workspace_size(m, n, k, orderA, orderB, orderC) -> int:
+    return int(load_library().mipgemm_workspace_size(m, n, k, orderA, orderB, orderC))
+
+
+def mipgemm_strerror(code: int) -> str:
+    return load_library().mipgemm_strerror(code).decode()
+
+
+def mipgemm_variant_name(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+                         a_unsigned=False, b_unsigned=False, aligned16=True) -> str:
+    return load_library().mipgemm_variant_name(
+        m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+        int(a_unsigned), int(b_unsigned), int(aligned16)).decode()

@@ -1,0 +1,348 @@
+// MFMA tile kernels for the MIP GEMM on gfx950.
+//
+// Roles taken from the paper's algorithm (Section 3, figure "Reference GEMM
+// algorithm", and Section 4.1), re-cast for a GPU:
+//   loops L1/L3 (jc, ic over n, m)  ->  the grid: one workgroup per BM x BN tile of C
+//   loop  L2    (pc over k)         ->  the K loop of a workgroup, BK = 64 per step
+//   Pack A / Pack B                 ->  staging of a BM x BK block of A and a BK x BN block
+//                                       of B into LDS, in an order from which every lane
+//                                       fetches 16 consecutive k per operand register;
+//                                       storage order, leading dimension and the
+//                                       unsigned-operand bias are absorbed here
+//   loops L4/L5 (jr, ir)            ->  the 2 x 2 waves of a workgroup and the 32 x 32 blocks
+//                                       of each wave's sub-tile
+//   micro-kernel, loop L6           ->  v_mfma_i32_32x32x32_i8 on register-resident int32
+//                                       accumulators (C_r), written back once after the K loop
+//
+// v_mfma_i32_32x32x32_i8 lane layout (measured on the device):
+//   operand a: lane l holds row (l % 32), 16 consecutive k starting at 16 * (l / 32)
+//   operand b: lane l holds column (l % 32), same 16 k
+//   result   : lane l holds column (l % 32); register v holds row 8*(v/4) + 4*(l/32) + v%4
+//
+// Unsigned operands: the matrix instruction multiplies signed bytes only.  An
+// unsigned x is staged as the signed byte x - 128 (x ^ 0x80), and the epilogue
+// adds 128 * sum_p y(p) of the other (signed) operand, which the waves
+// accumulate from the fragments they already hold.  Exact modulo 2^32.
+#include "mip_internal.h"
+
+namespace mip {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+struct __attribute__((packed, aligned(1))) unaligned_v4i { v4i v; };
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+constexpr int BK = 64;        // k per staged block
+constexpr int NTHREADS = 256; // 4 waves, arranged 2 x 2 over the tile
+
+// 16 bytes, of which only the first nvalid are read; the rest are zero.
+__device__ __forceinline__ v4i load16_partial(const uint8_t *p, int nvalid) {
+  v4i r = {0, 0, 0, 0};
+#pragma unroll
+  for (int b = 0; b < 16; ++b) {
+    uint32_t x = b < nvalid ? p[b] : 0u;
+    r[b >> 2] |= (int)(x << (8 * (b & 3)));
+  }
+  return r;
+}
+
+__device__ __forceinline__ v4i load16(const uint8_t *p) {
+  return reinterpret_cast<const unaligned_v4i *>(p)->v;
+}
+
+// One operand block in LDS.
+//   KC (k contiguous in memory: row-major A, column-major B):
+//     R rows of 64 bytes; 16-byte chunk c of row r sits at r*64 + 16*(c ^ ((r>>2)&3)).
+//   strided (the index runs contiguously: column-major A, row-major B):
+//     64 k-rows of R bytes; chunk c of k-row q sits at q*R + 16*(c ^ swz(q)).
+// Both XOR patterns spread the 16 lanes of one LDS access over all banks.
+template <int R, bool KC>
+struct Stage {
+  static constexpr int CHUNKS = R * BK / 16;
+  static constexpr int PER_THREAD = CHUNKS / NTHREADS;
+  static constexpr int ROW_CHUNKS = R / 16;  // strided: chunks per k-row
+
+  __device__ static __forceinline__ int swz(int q) { return 2 * ((q / (256 / R)) % (R / 32)); }
+
+  // chunk handled by this thread: (row, chunk-in-row) for KC, (k-row, chunk) for strided
+  __device__ static __forceinline__ void chunk_of(int i, int tid, int &a, int &c) {
+    int q = tid + NTHREADS * i;
+    if (KC) { a = q >> 2; c = q & 3; }
+    else { a = q / ROW_CHUNKS; c = q % ROW_CHUNKS; }
+  }
+
+  __device__ static __forceinline__ int lds_offset(int a, int c) {
+    if (KC) return a * 64 + ((c ^ ((a >> 2) & 3)) << 4);
+    return a * R + ((c ^ swz(a)) << 4);
+  }
+
+  // Global -> registers.  r0: first row (m or n index) of the block, k0: first k.
+  // ext: number of valid rows, kext: number of valid k.  sr / sk: byte strides.
+  template <bool CHECKED>
+  __device__ static __forceinline__ void load(v4i (&reg)[PER_THREAD], const uint8_t *base,
+                                             int64_t sr, int64_t sk, int64_t r0, int64_t k0,
+                                             int64_t ext, int64_t kext, int tid, int flip) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      int a, c;
+      chunk_of(i, tid, a, c);
+      v4i v;
+      if (KC) {
+        int64_t row = r0 + a, kk = k0 + c * 16;
+        if (!CHECKED) {
+          v = load16(base + row * sr + kk);
+        } else {
+          if (row > ext - 1) row = ext - 1;  // rows past the edge: any valid row, never stored
+          int64_t left = kext - kk;
+          const uint8_t *p = base + row * sr + kk;
+          if (left >= 16) v = load16(p);
+          else v = load16_partial(p, left > 0 ? (int)left : 0);
+        }
+      } else {
+        int64_t kq = k0 + a, col = r0 + c * 16;
+        if (!CHECKED) {
+          v = load16(base + kq * sk + col);
+        } else {
+          int64_t left = kq < kext ? ext - col : 0;
+          const uint8_t *p = base + kq * sk + col;
+          if (left >= 16) v = load16(p);
+          else v = load16_partial(p, left > 0 ? (int)left : 0);
+        }
+      }
+      v ^= flip;  // 0x80808080 turns unsigned bytes into signed ones minus 128
+      reg[i] = v;
+    }
+  }
+
+  __device__ static __forceinline__ void store(const v4i (&reg)[PER_THREAD], uint8_t *lds,
+                                              int tid) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      int a, c;
+      chunk_of(i, tid, a, c);
+      *reinterpret_cast<v4i *>(lds + lds_offset(a, c)) = reg[i];
+    }
+  }
+
+  // Fragment for one MFMA operand: lane l gets, for row (row0 + l%32), the 16
+  // bytes k = 32*ks + 16*(l/32) .. +15 of the staged block.
+  __device__ static __forceinline__ v4i fragment(const uint8_t *lds, int row0, int ks, int lane) {
+    if (KC) {
+      int r = row0 + (lane & 31);
+      int c = ks * 2 + (lane >> 5);
+      return *reinterpret_cast<const v4i *>(lds + lds_offset(r, c));
+    } else {
+      // ds_read_b64_tr_b8 (measured): inside each group of 16 lanes, lane 2t+h
+      // supplies the address of 8 bytes: half h of a 16-byte row t; lane i
+      // receives byte i of rows t = 0..7.  Rows are k, bytes are the index.
+      int s = lane & 15;
+      int col = row0 + ((lane >> 4) & 1) * 16 + (s & 1) * 8;
+      int kbase = ks * 32 + (lane >> 5) * 16 + (s >> 1);
+      v4i f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        int q = kbase + t * 8;
+        int off = q * R + (((col >> 4) ^ swz(q)) << 4) + (col & 15);
+        v2i h = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, lds + off));
+        f[2 * t] = h[0];
+        f[2 * t + 1] = h[1];
+      }
+      return f;
+    }
+  }
+};
+
+struct TileParams {
+  Problem p;
+  int tiles_m, tiles_n;
+};
+
+template <int BM, int BN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
+  constexpr int FM = BM / 64, FN = BN / 64;  // 32 x 32 blocks per wave, down and across
+  using SA = Stage<BM, A_KC>;
+  using SB = Stage<BN, B_KC>;
+  constexpr int STAGE_BYTES = (BM + BN) * BK;
+  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE_BYTES];
+
+  const Problem &p = tp.p;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of
+  // them, each with its own L2), so give every XCD a contiguous run of tiles,
+  // and walk the tiles in groups of 8 tile-rows so that the workgroups resident
+  // on one XCD share A row-panels and B column-panels.
+  const int ntiles = tp.tiles_m * tp.tiles_n;
+  const int per_xcd = (ntiles + 7) / 8;
+  int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (lid >= ntiles) return;
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tp.tiles_n;
+  const int first_m = (lid / per_group) * GROUP;
+  const int gsz = tp.tiles_m - first_m < GROUP ? tp.tiles_m - first_m : GROUP;
+  const int tm = first_m + (lid % per_group) % gsz;
+  const int tn = (lid % per_group) / gsz;
+
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const uint8_t *A = static_cast<const uint8_t *>(p.A);
+  const uint8_t *B = static_cast<const uint8_t *>(p.B);
+  const int flipA = p.a_unsigned ? (int)0x80808080u : 0;
+  const int flipB = p.b_unsigned ? (int)0x80808080u : 0;
+
+  const int64_t nkt = (p.k + BK - 1) / BK;
+  const bool edge_tile = m0 + BM > p.m || n0 + BN > p.n;
+  const bool k_tail = (p.k % BK) != 0;
+
+  v16i acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+  int sumA[FM], sumB[FN];  // per lane: partial sum over k of its row of A / column of B
+#pragma unroll
+  for (int i = 0; i < FM; ++i) sumA[i] = 0;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) sumB[j] = 0;
+
+  v4i ra[SA::PER_THREAD], rb[SB::PER_THREAD];
+
+  auto load_block = [&](int64_t kt) {
+    const bool checked = edge_tile || (k_tail && kt == nkt - 1);
+    if (!checked) {
+      SA::template load<false>(ra, A, p.a_sm, p.a_sk, m0, kt * BK, p.m, p.k, tid, flipA);
+      SB::template load<false>(rb, B, p.b_sn, p.b_sk, n0, kt * BK, p.n, p.k, tid, flipB);
+    } else {
+      SA::template load<true>(ra, A, p.a_sm, p.a_sk, m0, kt * BK, p.m, p.k, tid, flipA);
+      SB::template load<true>(rb, B, p.b_sn, p.b_sk, n0, kt * BK, p.n, p.k, tid, flipB);
+    }
+  };
+  auto store_block = [&](int stage) {
+    uint8_t *sa = smem + stage * STAGE_BYTES;
+    SA::store(ra, sa, tid);
+    SB::store(rb, sa + BM * BK, tid);
+  };
+
+  load_block(0);
+  store_block(0);
+  __syncthreads();
+
+  for (int64_t kt = 0; kt < nkt; ++kt) {
+    const int stage = (int)(kt & 1);
+    if (kt + 1 < nkt) load_block(kt + 1);
+
+    const uint8_t *sa = smem + stage * STAGE_BYTES;
+    const uint8_t *sb = sa + BM * BK;
+#pragma unroll
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      v4i fa[FM], fb[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa[i] = SA::fragment(sa, wm * (BM / 2) + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb[j] = SB::fragment(sb, wn * (BN / 2) + j * 32, ks, lane);
+      if (flipA) {  // A unsigned: need sum over k of B's columns
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            sumB[j] = __builtin_amdgcn_sdot4(fb[j][r], 0x01010101, sumB[j], false);
+      }
+      if (flipB) {  // B unsigned: need sum over k of A's rows
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            sumA[i] = __builtin_amdgcn_sdot4(fa[i][r], 0x01010101, sumA[i], false);
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+
+    if (kt + 1 < nkt) store_block(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: unsigned-operand correction, then C = acc or C += acc ----
+  if (flipA) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      // lanes l and l^32 hold the two k-halves of the same column
+      int other = __shfl_xor(sumB[j], 32);
+      int corr = 128 * (sumB[j] + other);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += corr;
+    }
+  }
+  if (flipB) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      int total = sumA[i] + __shfl_xor(sumA[i], 32);  // lane l: row (l % 32) of block i
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        int corr = 128 * __shfl(total, row);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j][v] += corr;
+      }
+    }
+  }
+
+  int32_t *C = p.C;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t row = m0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (row < p.m) {
+        int32_t *crow = C + row * p.ldc;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int64_t col = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+          if (col < p.n) {
+            uint32_t val = (uint32_t)acc[i][j][v];
+            if (p.accumulate) val += (uint32_t)crow[col];
+            crow[col] = (int32_t)val;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN>
+static hipError_t launch_cfg(const Problem &p, hipStream_t s) {
+  TileParams tp;
+  tp.p = p;
+  int64_t tiles_m = (p.m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
+  if (tiles_m * tiles_n > (int64_t)1 << 30) return hipErrorInvalidValue;
+  tp.tiles_m = (int)tiles_m;
+  tp.tiles_n = (int)tiles_n;
+  int ntiles = tp.tiles_m * tp.tiles_n;
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
+  const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  if (a_kc && b_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, true>), grid, dim3(NTHREADS), 0, s, tp);
+  else if (a_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, false>), grid, dim3(NTHREADS), 0, s, tp);
+  else if (b_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, false, true>), grid, dim3(NTHREADS), 0, s, tp);
+  else hipLaunchKernelGGL((tile_kernel<BM, BN, false, false>), grid, dim3(NTHREADS), 0, s, tp);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile(const Problem &p, Variant v, hipStream_t s) {
+  switch (v) {
+    case VARIANT_TILE256: return launch_cfg<256, 256>(p, s);
+    case VARIANT_TILE128: return launch_cfg<128, 128>(p, s);
+    case VARIANT_TILE64: return launch_cfg<64, 64>(p, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace mip

@@ -1,0 +1,99 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/mipgemm.h declares,
+validates arguments before touching the GPU, and picks kernel variants as documented."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2506_11728_amd as M
+    if not os.path.exists(M.library_path()):
+        from paper_2506_11728_amd.build import build_library
+        build_library()
+    M.load_library()
+    return M
+
+
+def test_header_symbols_are_exported(M):
+    header = open(os.path.join(ROOT, "include", "mipgemm.h")).read()
+    declared = set(re.findall(r"\b(mipgemm_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(M.exported_symbols())
+    lib = M.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_header_constants_match_binding(M):
+    header = open(os.path.join(ROOT, "include", "mipgemm.h")).read()
+    consts = dict(re.findall(r"#define\s+MIPGEMM_(\w+)\s+(\d+)\b", header))
+    assert int(consts["ROW_MAJOR"]) == M.ROW_MAJOR and int(consts["COL_MAJOR"]) == M.COL_MAJOR
+    assert int(consts["OVERWRITE"]) == M.OVERWRITE and int(consts["ACCUMULATE"]) == M.ACCUMULATE
+
+
+def call(M, name="mipgemm_s8s8s32", m=4, n=5, k=6, A=4096, lda=6, oa=0, B=4096, ldb=5, ob=0,
+         C=4096, ldc=5, oc=0, mode=0, ws=None, wsb=0):
+    # stream=0 keeps torch out of it; every call below must fail validation, so nothing launches
+    return getattr(M, name)(m, n, k, A, lda, oa, B, ldb, ob, C, ldc, oc, mode, ws, wsb, 0,
+                            check=False)
+
+
+@pytest.mark.parametrize("entry", ["mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32"])
+def test_argument_validation_codes(M, entry):
+    assert call(M, entry, m=-1) == -1
+    assert call(M, entry, n=-1) == -2
+    assert call(M, entry, k=-1) == -3
+    assert call(M, entry, m=2**31) == -1
+    assert call(M, entry, A=0) == -4
+    assert call(M, entry, lda=5) == -5               # row-major A needs lda >= k
+    assert call(M, entry, oa=1, lda=3) == -5         # column-major A needs lda >= m
+    assert call(M, entry, oa=2) == -6
+    assert call(M, entry, B=0) == -7
+    assert call(M, entry, ldb=4) == -8
+    assert call(M, entry, ob=1, ldb=5) == -8         # column-major B needs ldb >= k
+    assert call(M, entry, ob=-1) == -9
+    assert call(M, entry, C=0) == -10
+    assert call(M, entry, ldc=4) == -11
+    assert call(M, entry, oc=1, ldc=3) == -11        # column-major C needs ldc >= m
+    assert call(M, entry, oc=5) == -12
+    assert call(M, entry, mode=2) == -13
+    assert call(M, entry, lda=0, k=0) == -5          # leading dimensions are at least 1
+
+
+def test_first_bad_argument_wins(M):
+    assert call(M, m=-1, n=-1, mode=9) == -1
+    assert call(M, lda=1, ldb=1, ldc=1) == -5
+
+
+def test_empty_problems_need_no_pointers(M):
+    assert call(M, m=0, A=0, C=0) == 0
+    assert call(M, n=0, B=0, C=0, ldb=1, ldc=1) == 0
+    assert call(M, k=0, A=0, B=0, lda=1, mode=1) == 0     # accumulate of an empty sum: no-op
+
+
+def test_strerror_and_workspace(M):
+    assert M.mipgemm_strerror(0) == "success"
+    for code in range(-16, 0):
+        assert str(-code) in M.mipgemm_strerror(code)
+    assert "unknown" in M.mipgemm_strerror(-99)
+    assert M.mipgemm_workspace_size(8192, 8192, 8192, 0, 0, 0) == 0
+
+
+def test_variant_choice(M):
+    name = M.mipgemm_variant_name
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
+    assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
+    assert name(0, 4, 4, 4, 0, 4, 0, 4, 0) == "none"
+    assert name(4, 4, 4, 1, 0, 4, 0, 4, 0) == "invalid"
+    assert name(256, 256, 256, 256, 0, 256, 0, 256, 0).startswith("mfma_tile")
+
+
+def test_binding_fails_loudly_without_library(M, monkeypatch):
+    import paper_2506_11728_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libmipgemm.so")
+    with pytest.raises(ImportError):
+        b.load_library()

@@ -1,0 +1,204 @@
+"""GPU parity: the HIP library against the CPU oracle, bit for bit, through the C ABI.
+
+Every comparison is on the whole flat C buffer, leading-dimension padding
+included, so a store outside the m x n matrix fails too.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = ["auto", "simple", "tile256", "tile128", "tile64"]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2506_11728_amd as M
+    M.load_library()                       # raises if the HIP library is not built
+    return M
+
+
+class VariantEnv:
+    def __init__(self, variant):
+        self.variant = variant
+
+    def __enter__(self):
+        self.old = os.environ.pop("MIPGEMM_VARIANT", None)
+        if self.variant != "auto":
+            os.environ["MIPGEMM_VARIANT"] = self.variant
+
+    def __exit__(self, *a):
+        os.environ.pop("MIPGEMM_VARIANT", None)
+        if self.old is not None:
+            os.environ["MIPGEMM_VARIANT"] = self.old
+
+
+def gpu_gemm(M, case, A, B, C, variant="auto"):
+    """Run the library on host buffers A, B, C (flat numpy); returns the flat C it produced."""
+    import torch
+    dA = torch.from_numpy(A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(C).cuda()
+    fn = getattr(M, "mipgemm_" + case.entry)
+    with VariantEnv(variant):
+        fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+           dC, case.ldc, case.orderC, case.mode)
+    torch.cuda.synchronize()
+    return dC.cpu().numpy()
+
+
+_expected = {}
+
+
+def oracle_result(oracle, case, ops):
+    if case.name not in _expected:
+        C = ops.C.copy()
+        oracle.gemm(case.a_unsigned, case.b_unsigned, case.m, case.n, case.k, ops.A, case.lda,
+                    case.orderA, ops.B, case.ldb, case.orderB, C, case.ldc, case.orderC, case.mode)
+        _expected[case.name] = C
+    return _expected[case.name]
+
+
+def check_case(M, oracle, case, variant):
+    print("case", case.name, "variant", variant, flush=True)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    got = gpu_gemm(M, case, ops.A, ops.B, ops.C, variant)
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        pytest.fail("%s [%s]: %d of %d words differ, first at %d: got %d want %d" % (
+            case.name, variant, bad.size, got.size, bad[0], got[bad[0]], want[bad[0]]))
+
+
+def _ops_count(c):
+    return c.m * c.n * c.k
+
+
+SMALL = [c for c in W.all_cases() if _ops_count(c) <= 2.5e9]
+LARGE = [c for c in W.all_cases() if 2.5e9 < _ops_count(c) <= 7e10]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: c.name)
+def test_small_cases_every_variant(gpu, oracle, case, variant):
+    check_case(gpu, oracle, case, variant)
+
+
+@pytest.mark.parametrize("variant", ["auto", "tile256"])
+@pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
+def test_large_cases(gpu, oracle, case, variant):
+    check_case(gpu, oracle, case, variant)
+
+
+@pytest.mark.parametrize("case", W.config3(), ids=lambda c: c.name)
+def test_conv_cases_through_swapped_u8s8(gpu, oracle, case):
+    """The same buffers through mipgemm_u8s8s32 with A and B swapped (C^T = B^T A^T)."""
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    sw = W.swapped(case)
+    assert sw.entry == "u8s8s32"
+    got = gpu_gemm(gpu, sw, ops.B, ops.A, ops.C)
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------------------
+# the headline size: sampled rows through the oracle, closed form, Freivalds
+# ---------------------------------------------------------------------------
+
+def test_headline_8192_sampled_rows_and_freivalds(gpu, oracle):
+    case = W.headline_case()
+    ops = W.materialize(case)
+    got = gpu_gemm(gpu, case, ops.A, ops.B, ops.C).reshape(case.m, case.ldc)
+    rng = np.random.default_rng(99)
+    rows = np.unique(np.concatenate([rng.integers(0, case.m, size=48),
+                                     [0, 1, 31, 32, 127, 128, 255, 256, 4095, 4096, 8190, 8191]]))
+    # the oracle computes the sampled rows one block at a time: A restricted to those rows
+    A_rows = np.ascontiguousarray(ops.A.reshape(case.m, case.lda)[rows]).reshape(-1)
+    C_rows = np.zeros(rows.size * case.n, dtype=np.int32)
+    oracle.gemm_s8s8s32(rows.size, case.n, case.k, A_rows, case.lda, W.ROW_MAJOR,
+                        ops.B, case.ldb, W.ROW_MAJOR, C_rows, case.n, W.ROW_MAJOR, W.OVERWRITE)
+    assert np.array_equal(got[rows], C_rows.reshape(rows.size, case.n))
+    # every element, through an exact integer identity: C x == A (B x)
+    for _ in range(3):
+        x = rng.integers(-2, 2, size=case.n, endpoint=True).astype(np.int64)
+        lhs = got.astype(np.int64) @ x
+        rhs = ops.A2d.astype(np.int64) @ (ops.B2d.astype(np.int64) @ x)
+        assert np.array_equal(lhs, rhs)
+
+
+def test_headline_8192_extreme_values(gpu):
+    case = next(c for c in W.config2() if c.name == "c2_8192_min")
+    ops = W.materialize(case)
+    got = gpu_gemm(gpu, case, ops.A, ops.B, ops.C)
+    assert (got == 16384 * 8192).all()      # (-128) * (-128) * k = 2^27
+
+
+# ---------------------------------------------------------------------------
+# degenerate sizes, wraparound, error handling on the device
+# ---------------------------------------------------------------------------
+
+def test_wraparound_on_device(gpu, oracle):
+    k = 131072 + 64 + 5
+    case = W.Case("wrap", 9, 0, 40, 33, k, a_dist=("const", -128), b_dist=("const", -128))
+    check_case(gpu, oracle, case, "auto")
+    check_case(gpu, oracle, case, "tile128")
+
+
+def test_empty_problems(gpu):
+    import torch
+    C0 = np.arange(12, dtype=np.int32) + 5
+    dA = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    dC = torch.from_numpy(C0).cuda()
+    R, OVW, ACC = W.ROW_MAJOR, W.OVERWRITE, W.ACCUMULATE
+    gpu.mipgemm_s8s8s32(0, 4, 5, dA, 5, R, dA, 4, R, dC, 4, R, OVW)
+    gpu.mipgemm_s8s8s32(3, 0, 5, dA, 5, R, dA, 1, R, dC, 1, R, OVW)
+    gpu.mipgemm_s8s8s32(3, 3, 0, dA, 1, R, dA, 3, R, dC, 4, R, ACC)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), C0)
+    gpu.mipgemm_s8s8s32(3, 3, 0, dA, 1, R, dA, 3, R, dC, 4, R, OVW)      # k == 0: C := 0
+    torch.cuda.synchronize()
+    want = C0.reshape(3, 4).copy()
+    want[:, :3] = 0
+    assert np.array_equal(dC.cpu().numpy().reshape(3, 4), want)
+    # column-major C, k == 0
+    dC = torch.from_numpy(C0).cuda()
+    gpu.mipgemm_s8s8s32(3, 3, 0, dA, 1, R, dA, 3, R, dC, 4, W.COL_MAJOR, OVW)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy().reshape(3, 4), want)
+
+
+def test_errors_touch_nothing(gpu):
+    import torch
+    C0 = np.full(16, 123, dtype=np.int32)
+    dA = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    dC = torch.from_numpy(C0).cuda()
+    R = W.ROW_MAJOR
+    assert gpu.mipgemm_s8s8s32(4, 4, 4, dA, 3, R, dA, 4, R, dC, 4, R, 0, check=False) == -5
+    assert gpu.mipgemm_s8s8s32(4, 4, 4, dA, 4, R, dA, 4, R, dC, 4, R, 7, check=False) == -13
+    with pytest.raises(gpu.MipGemmError):
+        gpu.mipgemm_u8s8s32(4, 4, 4, dA, 4, R, dA, 4, 3, dC, 4, R, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), C0)
+
+
+def test_runs_on_a_side_stream(gpu, oracle):
+    import torch
+    case = W.config1()[0]
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    s = torch.cuda.Stream()
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+    torch.cuda.synchronize()
+    gpu.mipgemm_s8s8s32(case.m, case.n, case.k, dA, case.lda, 0, dB, case.ldb, 0, dC, case.ldc, 0,
+                        case.mode, stream=s)
+    s.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
