@@ -1,0 +1,250 @@
+// The large-problem kernel: 256 x 256 tile of C per workgroup, operands streamed
+// global -> LDS without passing through registers (global_load_lds_dwordx4),
+// four LDS stages, one workgroup barrier per 64-deep k block.
+//
+// In the paper's terms (Section 3 and Section 4.1): the 256 x 64 block of A and
+// the 64 x 256 block of B that a workgroup holds in LDS are the packed buffers
+// A_c and B_c; "packing" is done by the choice of which 16-byte piece each lane
+// fetches, so that the piece lands where the fragment reads expect it.  The
+// micro-kernel is v_mfma_i32_32x32x32_i8 on a 128 x 128 register-resident
+// accumulator block per wave (C_r), stored once after the k loop.
+//
+// Preconditions, checked on the host (dma_eligible): m and n multiples of 256,
+// k a multiple of 64, 16-byte aligned operand bases and leading dimensions,
+// 256 * ld below 2^31.  Everything else takes the generic tile kernel.
+#include <type_traits>
+
+#include "lds_layout.h"
+#include "mip_internal.h"
+
+namespace mip {
+
+namespace {
+
+constexpr int DM = 256, DN = 256;        // workgroup tile
+constexpr int STAGES = 4;
+constexpr int STAGE_BYTES = (DM + DN) * BK;  // 32 KiB
+constexpr int LOADS = DM * BK / 16 / NTHREADS;  // 16-byte pieces per thread, per operand, per k block
+
+struct DmaParams {
+  const uint8_t *A, *B;
+  int32_t *C;
+  int64_t lda, ldb, ldc;  // the one stride of each operand that is not 1
+  int tiles_m, tiles_n;
+  int nkt;                // k / 64
+};
+
+// One wave-wide direct load: lane l's 16 bytes from sbase + voff land in LDS at
+// lds_addr + 16 * l.  Written as inline assembly so that the compiler's
+// automatic wait-count insertion, which would drain every outstanding load
+// before any LDS read, stays out of the pipeline; the kernel places its own
+// s_waitcnt vmcnt before the barrier that publishes a stage.  M0 carries the
+// LDS base and needs one wait state before the load reads it.
+__device__ __forceinline__ void dma16(uint32_t voff, const uint8_t *sbase, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(voff), "s"(sbase), "s"(lds_addr)
+      :);  // M0 is reserved: the compiler keeps nothing live in it across statements
+}
+
+// "my loads of the next block have landed (N newer loads may still fly), my LDS
+// reads are complete; meet the other waves": after this the next stage is
+// visible to the whole workgroup and the stage read two steps ago may be refilled.
+template <int N>
+__device__ __forceinline__ void publish_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const uint8_t *p) {
+  return (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const uint8_t *)p);
+}
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(NTHREADS) void dma_kernel(DmaParams P) {
+  using SA = Stage<DM, A_KC>;
+  using SB = Stage<DN, B_KC>;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // workgroup -> tile: contiguous run of tiles per XCD, tiles walked in groups of 8 tile-rows
+  const int ntiles = P.tiles_m * P.tiles_n;
+  const int per_xcd = (ntiles + 7) / 8;
+  const int lid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (lid >= ntiles) return;
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * P.tiles_n;
+  const int first_m = (lid / per_group) * GROUP;
+  const int gsz = P.tiles_m - first_m < GROUP ? P.tiles_m - first_m : GROUP;
+  const int tm = first_m + (lid % per_group) % gsz;
+  const int tn = (lid % per_group) / gsz;
+  const int64_t m0 = (int64_t)tm * DM, n0 = (int64_t)tn * DN;
+
+  // Per-lane source offsets.  LDS piece Q = i*256 + tid of an operand block holds the
+  // logical piece whose swizzled position is Q (the XOR is its own inverse).
+  uint32_t offA[LOADS], offB[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    int a, c;
+    SA::chunk_of(i, tid, a, c);
+    offA[i] = A_KC ? (uint32_t)(a * P.lda + ((c ^ ((a >> 2) & 3)) << 4))
+                   : (uint32_t)(a * P.lda + ((c ^ SA::swz(a)) << 4));
+    SB::chunk_of(i, tid, a, c);
+    offB[i] = B_KC ? (uint32_t)(a * P.ldb + ((c ^ ((a >> 2) & 3)) << 4))
+                   : (uint32_t)(a * P.ldb + ((c ^ SB::swz(a)) << 4));
+  }
+  const uint8_t *gA = P.A + (A_KC ? m0 * P.lda : m0);
+  const uint8_t *gB = P.B + (B_KC ? n0 * P.ldb : n0);
+  const int64_t stepA = A_KC ? BK : BK * P.lda;
+  const int64_t stepB = B_KC ? BK : BK * P.ldb;
+
+  const uint32_t lds0 = lds_address(smem) + wave * 1024;
+  // one of the 8 direct loads of a k block (0..3: A, 4..7: B)
+  auto issue_one = [&](int stage, int q) {
+    const uint32_t sa = lds0 + stage * STAGE_BYTES;
+    if (q < LOADS) dma16(offA[q], gA, sa + q * 4096);
+    else dma16(offB[q - LOADS], gB, sa + DM * BK + (q - LOADS) * 4096);
+  };
+  auto advance = [&]() {
+    gA += stepA;
+    gB += stepB;
+  };
+  auto issue = [&](int stage) {
+#pragma unroll
+    for (int q = 0; q < 2 * LOADS; ++q) issue_one(stage, q);
+    advance();
+  };
+
+  v16i acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int nkt = P.nkt;
+  // prologue: blocks 0 .. STAGES-2 in flight
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < nkt) issue(s);
+
+  v4i fa[2][4], fb[2][4];
+  // fragment f of a k sub-block: 0..3 rows of A, 4..7 columns of B
+  auto read_frag = [&](int stage, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
+    const uint8_t *sa = smem + stage * STAGE_BYTES;
+    if (f < 4) a[f] = SA::fragment(sa, wm * 128 + f * 32, ks, lane);
+    else b[f - 4] = SB::fragment(sa + DM * BK, wn * 128 + (f - 4) * 32, ks, lane);
+  };
+  auto read_frags = [&](int stage, int ks, v4i (&a)[4], v4i (&b)[4]) {
+#pragma unroll
+    for (int f = 0; f < 8; ++f) read_frag(stage, ks, f, a, b);
+  };
+
+  constexpr int PER_BLOCK = 2 * LOADS;  // direct loads per thread per k block
+
+  // block 0 visible to everyone, its first fragments on their way
+  if (nkt > 2) publish_barrier<2 * PER_BLOCK>();
+  else if (nkt > 1) publish_barrier<PER_BLOCK>();
+  else publish_barrier<0>();
+  read_frags(0, 0, fa[0], fb[0]);
+
+  // One k block of 64 = two sub-blocks of 32, 16 MFMAs each.  The instruction
+  // order is pinned (sched_barrier after every slot) so that LDS reads and direct
+  // loads sit between MFMAs and their latency hides behind the matrix pipe:
+  //   sub-block 0 MFMAs, with the fragment reads of sub-block 1 and, if ISSUE, the
+  //                      direct loads of block t+3 (into the stage read in step t-1)
+  //   publish barrier    block t+1 becomes visible
+  //   sub-block 1 MFMAs, with the fragment reads of block t+1, sub-block 0
+  // NEWER: whole blocks that may still be in flight when block t+1 must be
+  // complete; -1 marks the last block (nothing to publish).
+  auto step = [&](int t, auto issue_tag, auto newer_tag) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;
+    constexpr int NEWER = decltype(newer_tag)::value;
+    const int stage = t & (STAGES - 1);
+    const int fill = (t + STAGES - 1) & (STAGES - 1);
+    const int next = (t + 1) & (STAGES - 1);
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][s >> 2], fb[0][s & 3],
+                                                                 acc[s >> 2][s & 3], 0, 0, 0);
+      if (s < 8) read_frag(stage, 1, s, fa[1], fb[1]);
+      else if (ISSUE) issue_one(fill, s - 8);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (ISSUE) advance();
+    if (NEWER >= 0) publish_barrier<(NEWER > 0 ? NEWER : 0) * PER_BLOCK>();
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][s >> 2], fb[1][s & 3],
+                                                                 acc[s >> 2][s & 3], 0, 0, 0);
+      if (NEWER >= 0 && s < 8) read_frag(next, 0, s, fa[0], fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  using std::integral_constant;
+  int t = 0;
+  for (; t + STAGES - 1 < nkt; ++t)  // blocks t+1, t+2, t+3 exist; t+2 and t+3 may fly
+    step(t, integral_constant<bool, true>{}, integral_constant<int, 2>{});
+  // the last (up to) three blocks: nothing left to issue
+  if (t + 2 < nkt) { step(t, integral_constant<bool, false>{}, integral_constant<int, 1>{}); ++t; }
+  if (t + 1 < nkt) { step(t, integral_constant<bool, false>{}, integral_constant<int, 0>{}); ++t; }
+  step(t, integral_constant<bool, false>{}, integral_constant<int, -1>{});
+
+  // epilogue: lane l holds column l % 32; register v holds row 8*(v/4) + 4*(l/32) + v%4
+  int32_t *C = P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128 + (lane & 31);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      int32_t *crow = C + (int64_t)(i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * P.ldc;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) crow[j * 32] = acc[i][j][v];
+    }
+}
+
+}  // namespace
+
+bool dma_eligible(const Problem &p) {
+  if (p.a_unsigned || p.b_unsigned || p.accumulate) return false;
+  if (p.m % DM || p.n % DN || p.k % BK || p.k < BK) return false;
+  const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
+  const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
+  if (lda % 16 || ldb % 16) return false;
+  if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
+  if (256 * lda >= ((int64_t)1 << 31) || 256 * ldb >= ((int64_t)1 << 31)) return false;
+  if ((p.m / DM) * (p.n / DN) > ((int64_t)1 << 30)) return false;
+  return true;
+}
+
+hipError_t launch_dma(const Problem &p, hipStream_t s) {
+  DmaParams P;
+  P.A = static_cast<const uint8_t *>(p.A);
+  P.B = static_cast<const uint8_t *>(p.B);
+  P.C = p.C;
+  P.lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
+  P.ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
+  P.ldc = p.ldc;
+  P.tiles_m = (int)(p.m / DM);
+  P.tiles_n = (int)(p.n / DN);
+  P.nkt = (int)(p.k / BK);
+  const int ntiles = P.tiles_m * P.tiles_n;
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
+  const size_t lds = (size_t)STAGES * STAGE_BYTES;
+  const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  void (*kern)(DmaParams) =
+      a_kc ? (b_kc ? dma_kernel<true, true> : dma_kernel<true, false>)
+           : (b_kc ? dma_kernel<false, true> : dma_kernel<false, false>);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);
+  return hipGetLastError();
+}
+
+}  // namespace mip
