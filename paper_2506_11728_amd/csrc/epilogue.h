@@ -1,0 +1,90 @@
+// Write-back of the register-resident accumulator blocks (the paper's C_r,
+// Section 4.1: loaded or zeroed before loop L6, stored once after it), shared
+// by the MFMA kernels.
+//
+// The kernels issue v_mfma_i32_32x32x32_i8 with the B fragment as first operand
+// and the A fragment as second, so each 32 x 32 block comes out transposed in
+// the register file: lane l owns C row (l % 32) of the block and register v
+// owns column 8*(v/4) + 4*(l/32) + v%4.  Four consecutive registers are four
+// consecutive int32 of one row of C: one 16-byte store per lane.
+#pragma once
+#include "lds_layout.h"
+
+namespace mip {
+
+struct __attribute__((packed, aligned(4))) c_quad { v4i v; };
+
+// Unsigned-operand correction (exact modulo 2^32).  sumB[j]: this lane's partial
+// sum over k of column (32*j + l%32) of the staged B; sumA[i]: same for row
+// (32*i + l%32) of A; lanes l and l^32 hold the two k halves.
+template <int FM, int FN>
+__device__ __forceinline__ void unsigned_correction(v16i (&acc)[FM][FN], const int (&sumA)[FM],
+                                                    const int (&sumB)[FN], bool a_unsigned,
+                                                    bool b_unsigned, int lane) {
+  if (a_unsigned) {  // sum_p (a - 128) b + 128 sum_p b: needs B's column sums
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int total = sumB[j] + __shfl_xor(sumB[j], 32);  // lane l: column l % 32
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int corr = 128 * __shfl(total, col);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) acc[i][j][v] += corr;
+      }
+    }
+  }
+  if (b_unsigned) {  // needs A's row sums, which already sit in the owning lane
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int corr = 128 * (sumA[i] + __shfl_xor(sumA[i], 32));
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += corr;
+    }
+  }
+}
+
+// C points at the first element of the wave's sub-tile; rows / cols are how
+// many of its 32*FM x 32*FN elements lie inside the matrix.
+template <int FM, int FN, bool FULL>
+__device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t *C, int64_t ldc,
+                                             int64_t rows, int64_t cols, bool accumulate,
+                                             int lane) {
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = i * 32 + (lane & 31);
+    if (!FULL && row >= rows) continue;
+    int32_t *crow = C + row * ldc + 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = j * 32 + 8 * q;  // plus 4 * (lane / 32), already in crow
+        v4i val = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                   acc[i][j][4 * q + 3]};
+        if (FULL || col + 4 * (lane >> 5) + 3 < cols) {
+          c_quad *dst = reinterpret_cast<c_quad *>(crow + col);
+          if (accumulate) {
+            v4i old = dst->v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) val[e] = (int)((uint32_t)val[e] + (uint32_t)old[e]);
+          }
+          dst->v = val;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (col + 4 * (lane >> 5) + e < cols) {
+              uint32_t x = (uint32_t)val[e];
+              if (accumulate) x += (uint32_t)crow[col + e];
+              crow[col + e] = (int32_t)x;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace mip

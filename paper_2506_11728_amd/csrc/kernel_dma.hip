@@ -14,6 +14,7 @@
 // 256 * ld below 2^31.  Everything else takes the generic tile kernel.
 #include <type_traits>
 
+#include "epilogue.h"
 #include "lds_layout.h"
 #include "mip_internal.h"
 
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(NTHREADS) void dma_kernel(DmaParams P) {
     const int next = (t + 1) & (STAGES - 1);
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
-      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][s >> 2], fb[0][s & 3],
+      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][s & 3], fa[0][s >> 2],
                                                                  acc[s >> 2][s & 3], 0, 0, 0);
       if (s < 8) read_frag(stage, 1, s, fa[1], fb[1]);
       else if (ISSUE) issue_one(fill, s - 8);
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(NTHREADS) void dma_kernel(DmaParams P) {
     if (NEWER >= 0) publish_barrier<(NEWER > 0 ? NEWER : 0) * PER_BLOCK>();
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
-      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][s >> 2], fb[1][s & 3],
+      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[1][s & 3], fa[1][s >> 2],
                                                                  acc[s >> 2][s & 3], 0, 0, 0);
       if (NEWER >= 0 && s < 8) read_frag(next, 0, s, fa[0], fb[0]);
       __builtin_amdgcn_sched_barrier(0);
@@ -196,16 +197,9 @@ __global__ __launch_bounds__(NTHREADS) void dma_kernel(DmaParams P) {
   if (t + 1 < nkt) { step(t, integral_constant<bool, false>{}, integral_constant<int, 0>{}); ++t; }
   step(t, integral_constant<bool, false>{}, integral_constant<int, -1>{});
 
-  // epilogue: lane l holds column l % 32; register v holds row 8*(v/4) + 4*(l/32) + v%4
-  int32_t *C = P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128 + (lane & 31);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      int32_t *crow = C + (int64_t)(i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * P.ldc;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) crow[j * 32] = acc[i][j][v];
-    }
+  // write-back: C_r -> C, one 16-byte store per lane and register quad
+  store_blocks<4, 4, true>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc, 128, 128,
+                           false, lane);
 }
 
 }  // namespace

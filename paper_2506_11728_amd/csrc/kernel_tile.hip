@@ -18,11 +18,15 @@
 //   operand a: lane l holds row (l % 32), 16 consecutive k starting at 16 * (l / 32)
 //   operand b: lane l holds column (l % 32), same 16 k
 //   result   : lane l holds column (l % 32); register v holds row 8*(v/4) + 4*(l/32) + v%4
+// The kernels pass the B fragment as operand a and the A fragment as operand b, so the
+// block comes out transposed: lane = row of C, four consecutive registers = four
+// consecutive columns, which makes the write-back one 16-byte store per lane.
 //
 // Unsigned operands: the matrix instruction multiplies signed bytes only.  An
 // unsigned x is staged as the signed byte x - 128 (x ^ 0x80), and the epilogue
 // adds 128 * sum_p y(p) of the other (signed) operand, which the waves
 // accumulate from the fragments they already hold.  Exact modulo 2^32.
+#include "epilogue.h"
 #include "lds_layout.h"
 #include "mip_internal.h"
 
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
 
     if (kt + 1 < nkt) store_block(stage ^ 1);
@@ -144,51 +148,12 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   }
 
   // ---- epilogue: unsigned-operand correction, then C = acc or C += acc ----
-  if (flipA) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      // lanes l and l^32 hold the two k-halves of the same column
-      int other = __shfl_xor(sumB[j], 32);
-      int corr = 128 * (sumB[j] + other);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] += corr;
-    }
-  }
-  if (flipB) {
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      int total = sumA[i] + __shfl_xor(sumA[i], 32);  // lane l: row (l % 32) of block i
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int row = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        int corr = 128 * __shfl(total, row);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j][v] += corr;
-      }
-    }
-  }
-
-  int32_t *C = p.C;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int64_t row = m0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (row < p.m) {
-        int32_t *crow = C + row * p.ldc;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int64_t col = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
-          if (col < p.n) {
-            uint32_t val = (uint32_t)acc[i][j][v];
-            if (p.accumulate) val += (uint32_t)crow[col];
-            crow[col] = (int32_t)val;
-          }
-        }
-      }
-    }
+  unsigned_correction<FM, FN>(acc, sumA, sumB, flipA != 0, flipB != 0, lane);
+  const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
+  if (mw < p.m && nw < p.n) {
+    int32_t *C = p.C + mw * p.ldc + nw;
+    if (!edge_tile) store_blocks<FM, FN, true>(acc, C, p.ldc, BM / 2, BN / 2, p.accumulate, lane);
+    else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane);
   }
 }
 
