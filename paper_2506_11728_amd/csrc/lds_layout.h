@@ -32,28 +32,34 @@ __device__ __forceinline__ v4i load16(const uint8_t *p) {
 }
 
 // One operand block in LDS.
+// KD is the depth of the block along k (64 or 128).
 //   KC (k contiguous in memory: row-major A, column-major B):
-//     R rows of 64 bytes; 16-byte chunk c of row r sits at r*64 + 16*(c ^ ((r>>2)&3)).
+//     R rows of KD bytes; 16-byte chunk c of row r sits at r*KD + 16*(c ^ kswz(r)).
 //   strided (the index runs contiguously: column-major A, row-major B):
-//     64 k-rows of R bytes; chunk c of k-row q sits at q*R + 16*(c ^ swz(q)).
-// Both XOR patterns spread the 16 lanes of one LDS access over all banks.
-template <int R, bool KC>
+//     KD k-rows of R bytes; chunk c of k-row q sits at q*R + 16*(c ^ swz(q)).
+// Both XOR patterns spread the 16 lanes of one LDS access over all banks
+// (no bank conflicts measured).
+template <int R, bool KC, int KD = BK>
 struct Stage {
-  static constexpr int CHUNKS = R * BK / 16;
+  static constexpr int CHUNKS = R * KD / 16;
   static constexpr int PER_THREAD = CHUNKS / NTHREADS;
   static constexpr int ROW_CHUNKS = R / 16;  // strided: chunks per k-row
+  static constexpr int K_CHUNKS = KD / 16;   // KC: chunks per row
+
+  // rows 256 bytes apart share banks: rotate their chunks against each other
+  __device__ static __forceinline__ int kswz(int r) { return (r / (256 / KD)) % K_CHUNKS; }
 
   __device__ static __forceinline__ int swz(int q) { return 2 * ((q / (256 / R)) % (R / 32)); }
 
   // chunk handled by this thread: (row, chunk-in-row) for KC, (k-row, chunk) for strided
   __device__ static __forceinline__ void chunk_of(int i, int tid, int &a, int &c) {
     int q = tid + NTHREADS * i;
-    if (KC) { a = q >> 2; c = q & 3; }
+    if (KC) { a = q / K_CHUNKS; c = q % K_CHUNKS; }
     else { a = q / ROW_CHUNKS; c = q % ROW_CHUNKS; }
   }
 
   __device__ static __forceinline__ int lds_offset(int a, int c) {
-    if (KC) return a * 64 + ((c ^ ((a >> 2) & 3)) << 4);
+    if (KC) return a * KD + ((c ^ kswz(a)) << 4);
     return a * R + ((c ^ swz(a)) << 4);
   }
 

@@ -27,6 +27,7 @@ enum Variant {
   VARIANT_FILL,       // k == 0, overwrite: C := 0
   VARIANT_SIMPLE,     // one thread per C element, any layout
   VARIANT_DMA256,     // MFMA, 256 x 256 tile, global->LDS direct loads, aligned full tiles only
+  VARIANT_DMA256K128, // same, k blocks of 128 in two LDS stages
   VARIANT_TILE256,    // MFMA, 256 x 256 workgroup tile
   VARIANT_TILE128,    // MFMA, 128 x 128 workgroup tile
   VARIANT_TILE64,     // MFMA, 64 x 64 workgroup tile
@@ -39,7 +40,7 @@ Variant choose_variant(const Problem &p);
 hipError_t launch_fill_zero(const Problem &p, hipStream_t s);
 hipError_t launch_simple(const Problem &p, hipStream_t s);
 hipError_t launch_tile(const Problem &p, Variant v, hipStream_t s);
-bool dma_eligible(const Problem &p);
-hipError_t launch_dma(const Problem &p, hipStream_t s);
+bool dma_eligible(const Problem &p, bool deep);  // deep: k blocks of 128 instead of 64
+hipError_t launch_dma(const Problem &p, bool deep, hipStream_t s);
 
 }  // namespace mip

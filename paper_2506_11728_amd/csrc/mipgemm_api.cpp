@@ -15,6 +15,7 @@ const char *variant_name(Variant v) {
     case VARIANT_FILL: return "fill_zero";
     case VARIANT_SIMPLE: return "simple";
     case VARIANT_DMA256: return "mfma_dma256";
+    case VARIANT_DMA256K128: return "mfma_dma256_k128";
     case VARIANT_TILE256: return "mfma_tile256";
     case VARIANT_TILE128: return "mfma_tile128";
     case VARIANT_TILE64: return "mfma_tile64";
@@ -29,6 +30,7 @@ static Variant forced_variant() {
   if (!e || !*e) return VARIANT_NONE;
   if (!std::strcmp(e, "simple")) return VARIANT_SIMPLE;
   if (!std::strcmp(e, "dma256")) return VARIANT_DMA256;
+  if (!std::strcmp(e, "dma256k128")) return VARIANT_DMA256K128;
   if (!std::strcmp(e, "tile256")) return VARIANT_TILE256;
   if (!std::strcmp(e, "tile128")) return VARIANT_TILE128;
   if (!std::strcmp(e, "tile64")) return VARIANT_TILE64;
@@ -39,12 +41,13 @@ Variant choose_variant(const Problem &p) {
   if (p.m == 0 || p.n == 0) return VARIANT_NONE;
   if (p.k == 0) return p.accumulate ? VARIANT_NONE : VARIANT_FILL;
   Variant f = forced_variant();
-  if (f == VARIANT_DMA256 && !dma_eligible(p)) f = VARIANT_NONE;
+  if (f == VARIANT_DMA256 && !dma_eligible(p, false)) f = VARIANT_NONE;
+  if (f == VARIANT_DMA256K128 && !dma_eligible(p, true)) f = VARIANT_NONE;
   if (f != VARIANT_NONE) return f;
   // Tile choice: the largest tile that still yields about one workgroup per
   // compute unit (256 of them); small problems take small tiles.
   auto tiles = [&](int64_t t) { return ((p.m + t - 1) / t) * ((p.n + t - 1) / t); };
-  if (tiles(256) >= 192) return dma_eligible(p) ? VARIANT_DMA256 : VARIANT_TILE256;
+  if (tiles(256) >= 192) return dma_eligible(p, false) ? VARIANT_DMA256 : VARIANT_TILE256;
   if (tiles(128) >= 192) return VARIANT_TILE128;
   return VARIANT_TILE64;
 }
@@ -125,7 +128,8 @@ int run(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const v
     case mip::VARIANT_NONE: break;
     case mip::VARIANT_FILL: e = mip::launch_fill_zero(p, s); break;
     case mip::VARIANT_SIMPLE: e = mip::launch_simple(p, s); break;
-    case mip::VARIANT_DMA256: e = mip::launch_dma(p, s); break;
+    case mip::VARIANT_DMA256: e = mip::launch_dma(p, false, s); break;
+    case mip::VARIANT_DMA256K128: e = mip::launch_dma(p, true, s); break;
     default: e = mip::launch_tile(p, v, s); break;
   }
   return static_cast<int>(e);

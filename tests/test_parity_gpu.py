@@ -91,7 +91,7 @@ def test_small_cases_every_variant(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
 
 
-@pytest.mark.parametrize("variant", ["auto", "tile256"])
+@pytest.mark.parametrize("variant", ["auto", "tile256", "dma256", "dma256k128"])
 @pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
 def test_large_cases(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
