@@ -87,4 +87,25 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
   }
 }
 
+// Split-k write-back: every workgroup adds its partial sums into C with integer
+// atomics (order-independent, so still bit-exact).
+template <int FM, int FN>
+__device__ __forceinline__ void add_blocks_atomic(const v16i (&acc)[FM][FN], int32_t *C,
+                                                  int64_t ldc, int64_t rows, int64_t cols,
+                                                  int lane) {
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = i * 32 + (lane & 31);
+    if (row >= rows) continue;
+    int32_t *crow = C + row * ldc + 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = j * 32 + 8 * (v >> 2) + (v & 3);
+        if (col + 4 * (lane >> 5) < cols) atomicAdd(crow + col, acc[i][j][v]);
+      }
+  }
+}
+
 }  // namespace mip

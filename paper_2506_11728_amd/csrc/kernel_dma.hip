@@ -170,23 +170,28 @@ __global__ __launch_bounds__(NTHREADS) void dma_kernel(DmaParams P) {
     const int stage = t & (STAGES - 1);
     const int fill = (t + STAGES - 1) & (STAGES - 1);
     const int next = (t + 1) & (STAGES - 1);
+    // Direct loads go out one every other MFMA slot, spread over the whole step:
+    // the four waves run in lockstep, and the address unit takes about 16 cycles
+    // per wave-wide load, so bunching them stalls the MFMA stream.
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[0][s & 3], fa[0][s >> 2],
                                                                  acc[s >> 2][s & 3], 0, 0, 0);
       if (s < 8) read_frag(stage, 1, s, fa[1], fb[1]);
-      else if (ISSUE) issue_one(fill, s - 8);
+      else if (ISSUE && (s & 1)) issue_one(fill, (s - 8) >> 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (ISSUE) advance();
-    if (NEWER >= 0) publish_barrier<(NEWER > 0 ? NEWER : 0) * PER_BLOCK>();
+    // block t+2 and, if issuing, the first half of block t+3 may still be in flight
+    if (NEWER >= 0) publish_barrier<ISSUE ? PER_BLOCK + PER_BLOCK / 2 : (NEWER > 0 ? NEWER : 0) * PER_BLOCK>();
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[1][s & 3], fa[1][s >> 2],
                                                                  acc[s >> 2][s & 3], 0, 0, 0);
       if (NEWER >= 0 && s < 8) read_frag(next, 0, s, fa[0], fb[0]);
+      else if (ISSUE && (s & 1)) issue_one(fill, LOADS + ((s - 8) >> 1));
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (ISSUE) advance();
   };
   using std::integral_constant;
   int t = 0;

@@ -35,6 +35,8 @@ namespace mip {
 struct TileParams {
   Problem p;
   int tiles_m, tiles_n;
+  int kt_per_split;  // k blocks of 64 handled by one workgroup (blockIdx.y picks the range)
+  int atomic;        // several workgroups add into the same tile of C (split k)
 };
 
 template <int BM, int BN, bool A_KC, bool B_KC>
@@ -70,7 +72,12 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   const int flipA = p.a_unsigned ? (int)0x80808080u : 0;
   const int flipB = p.b_unsigned ? (int)0x80808080u : 0;
 
-  const int64_t nkt = (p.k + BK - 1) / BK;
+  // Split k: integer addition is associative, so partial sums added into C in
+  // any order give the same bits as one pass.
+  const int64_t nkt = (p.k + BK - 1) / BK;  // k blocks in the whole problem
+  const int64_t kt_begin = (int64_t)blockIdx.y * tp.kt_per_split;
+  const int64_t kt_end = kt_begin + tp.kt_per_split < nkt ? kt_begin + tp.kt_per_split : nkt;
+  if (kt_begin >= kt_end) return;
   const bool edge_tile = m0 + BM > p.m || n0 + BN > p.n;
   const bool k_tail = (p.k % BK) != 0;
 
@@ -105,13 +112,13 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
     SB::store(rb, sa + BM * BK, tid);
   };
 
-  load_block(0);
+  load_block(kt_begin);
   store_block(0);
   __syncthreads();
 
-  for (int64_t kt = 0; kt < nkt; ++kt) {
-    const int stage = (int)(kt & 1);
-    if (kt + 1 < nkt) load_block(kt + 1);
+  for (int64_t kt = kt_begin; kt < kt_end; ++kt) {
+    const int stage = (int)((kt - kt_begin) & 1);
+    if (kt + 1 < kt_end) load_block(kt + 1);
 
     const uint8_t *sa = smem + stage * STAGE_BYTES;
     const uint8_t *sb = sa + BM * BK;
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
 
-    if (kt + 1 < nkt) store_block(stage ^ 1);
+    if (kt + 1 < kt_end) store_block(stage ^ 1);
     __syncthreads();
   }
 
@@ -152,21 +159,34 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < p.m && nw < p.n) {
     int32_t *C = p.C + mw * p.ldc + nw;
-    if (!edge_tile) store_blocks<FM, FN, true>(acc, C, p.ldc, BM / 2, BN / 2, p.accumulate, lane);
+    if (tp.atomic) add_blocks_atomic<FM, FN>(acc, C, p.ldc, p.m - mw, p.n - nw, lane);
+    else if (!edge_tile) store_blocks<FM, FN, true>(acc, C, p.ldc, BM / 2, BN / 2, p.accumulate, lane);
     else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane);
   }
 }
 
 template <int BM, int BN>
-static hipError_t launch_cfg(const Problem &p, hipStream_t s) {
+static hipError_t launch_cfg(const Problem &p, int splits, hipStream_t s) {
   TileParams tp;
   tp.p = p;
   int64_t tiles_m = (p.m + BM - 1) / BM, tiles_n = (p.n + BN - 1) / BN;
   if (tiles_m * tiles_n > (int64_t)1 << 30) return hipErrorInvalidValue;
   tp.tiles_m = (int)tiles_m;
   tp.tiles_n = (int)tiles_n;
+  const int64_t nkt = (p.k + BK - 1) / BK;
+  if (splits < 1) splits = 1;
+  if (splits > nkt) splits = (int)nkt;
+  if (splits > 65535) splits = 65535;
+  tp.kt_per_split = (int)((nkt + splits - 1) / splits);
+  splits = (int)((nkt + tp.kt_per_split - 1) / tp.kt_per_split);  // no empty ranges
+  tp.atomic = splits > 1;
+  if (tp.atomic && !p.accumulate) {
+    // partial sums are added into C: start it from zero
+    hipError_t e = launch_fill_zero(p, s);
+    if (e != hipSuccess) return e;
+  }
   int ntiles = tp.tiles_m * tp.tiles_n;
-  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits);
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   if (a_kc && b_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, true>), grid, dim3(NTHREADS), 0, s, tp);
   else if (a_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, false>), grid, dim3(NTHREADS), 0, s, tp);
@@ -175,11 +195,13 @@ static hipError_t launch_cfg(const Problem &p, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_tile(const Problem &p, Variant v, hipStream_t s) {
+hipError_t launch_tile(const Problem &p, Variant v, int splits, hipStream_t s) {
   switch (v) {
-    case VARIANT_TILE256: return launch_cfg<256, 256>(p, s);
-    case VARIANT_TILE128: return launch_cfg<128, 128>(p, s);
-    case VARIANT_TILE64: return launch_cfg<64, 64>(p, s);
+    case VARIANT_TILE256: return launch_cfg<256, 256>(p, splits, s);
+    case VARIANT_TILE128: return launch_cfg<128, 128>(p, splits, s);
+    case VARIANT_TILE64: return launch_cfg<64, 64>(p, splits, s);
+    case VARIANT_TILE64X256: return launch_cfg<64, 256>(p, splits, s);
+    case VARIANT_TILE256X64: return launch_cfg<256, 64>(p, splits, s);
     default: return hipErrorInvalidValue;
   }
 }

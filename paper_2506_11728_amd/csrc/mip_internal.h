@@ -31,15 +31,23 @@ enum Variant {
   VARIANT_TILE256,    // MFMA, 256 x 256 workgroup tile
   VARIANT_TILE128,    // MFMA, 128 x 128 workgroup tile
   VARIANT_TILE64,     // MFMA, 64 x 64 workgroup tile
+  VARIANT_TILE64X256, // MFMA, 64 x 256 tile: few rows, many columns
+  VARIANT_TILE256X64, // MFMA, 256 x 64 tile: many rows, few columns
   VARIANT_COUNT
 };
 
 const char *variant_name(Variant v);
-Variant choose_variant(const Problem &p);
+// Kernel and, for the tile kernels, the number of k ranges worked on by separate
+// workgroups (1 = no split).
+struct Plan {
+  Variant variant;
+  int splits;
+};
+Plan choose_plan(const Problem &p);
 
 hipError_t launch_fill_zero(const Problem &p, hipStream_t s);
 hipError_t launch_simple(const Problem &p, hipStream_t s);
-hipError_t launch_tile(const Problem &p, Variant v, hipStream_t s);
+hipError_t launch_tile(const Problem &p, Variant v, int splits, hipStream_t s);
 bool dma_eligible(const Problem &p, bool deep);  // deep: k blocks of 128 instead of 64
 hipError_t launch_dma(const Problem &p, bool deep, hipStream_t s);
 

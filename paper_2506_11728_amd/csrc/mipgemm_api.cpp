@@ -19,37 +19,94 @@ const char *variant_name(Variant v) {
     case VARIANT_TILE256: return "mfma_tile256";
     case VARIANT_TILE128: return "mfma_tile128";
     case VARIANT_TILE64: return "mfma_tile64";
+    case VARIANT_TILE64X256: return "mfma_tile64x256";
+    case VARIANT_TILE256X64: return "mfma_tile256x64";
     default: return "?";
   }
 }
 
-// MIPGEMM_VARIANT=simple|dma256|tile256|tile128|tile64 pins the kernel (tuning and tests).
-// dma256 only applies to problems it is eligible for; others keep the automatic choice.
+// MIPGEMM_VARIANT pins the kernel (tuning and tests): simple, dma256, dma256k128,
+// tile256, tile128, tile64, tile64x256, tile256x64.  The two dma variants only apply
+// to problems they are eligible for; others keep the automatic choice.
+// MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
 static Variant forced_variant() {
   const char *e = std::getenv("MIPGEMM_VARIANT");
   if (!e || !*e) return VARIANT_NONE;
-  if (!std::strcmp(e, "simple")) return VARIANT_SIMPLE;
-  if (!std::strcmp(e, "dma256")) return VARIANT_DMA256;
-  if (!std::strcmp(e, "dma256k128")) return VARIANT_DMA256K128;
-  if (!std::strcmp(e, "tile256")) return VARIANT_TILE256;
-  if (!std::strcmp(e, "tile128")) return VARIANT_TILE128;
-  if (!std::strcmp(e, "tile64")) return VARIANT_TILE64;
+  static const struct { const char *name; Variant v; } table[] = {
+      {"simple", VARIANT_SIMPLE},         {"dma256", VARIANT_DMA256},
+      {"dma256k128", VARIANT_DMA256K128}, {"tile256", VARIANT_TILE256},
+      {"tile128", VARIANT_TILE128},       {"tile64", VARIANT_TILE64},
+      {"tile64x256", VARIANT_TILE64X256}, {"tile256x64", VARIANT_TILE256X64}};
+  for (const auto &t : table)
+    if (!std::strcmp(e, t.name)) return t.v;
   return VARIANT_NONE;
 }
 
-Variant choose_variant(const Problem &p) {
-  if (p.m == 0 || p.n == 0) return VARIANT_NONE;
-  if (p.k == 0) return p.accumulate ? VARIANT_NONE : VARIANT_FILL;
-  Variant f = forced_variant();
-  if (f == VARIANT_DMA256 && !dma_eligible(p, false)) f = VARIANT_NONE;
-  if (f == VARIANT_DMA256K128 && !dma_eligible(p, true)) f = VARIANT_NONE;
-  if (f != VARIANT_NONE) return f;
-  // Tile choice: the largest tile that still yields about one workgroup per
-  // compute unit (256 of them); small problems take small tiles.
-  auto tiles = [&](int64_t t) { return ((p.m + t - 1) / t) * ((p.n + t - 1) / t); };
-  if (tiles(256) >= 192) return dma_eligible(p, false) ? VARIANT_DMA256 : VARIANT_TILE256;
-  if (tiles(128) >= 192) return VARIANT_TILE128;
-  return VARIANT_TILE64;
+static int forced_splits() {
+  const char *e = std::getenv("MIPGEMM_SPLITK");
+  if (!e || !*e) return 0;
+  int v = std::atoi(e);
+  return v > 0 ? v : 0;
+}
+
+static int64_t tile_count(const Problem &p, int64_t bm, int64_t bn) {
+  return ((p.m + bm - 1) / bm) * ((p.n + bn - 1) / bn);
+}
+
+static void tile_shape(Variant v, int64_t *bm, int64_t *bn) {
+  switch (v) {
+    case VARIANT_TILE256: *bm = 256; *bn = 256; break;
+    case VARIANT_TILE128: *bm = 128; *bn = 128; break;
+    case VARIANT_TILE64X256: *bm = 64; *bn = 256; break;
+    case VARIANT_TILE256X64: *bm = 256; *bn = 64; break;
+    default: *bm = 64; *bn = 64; break;
+  }
+}
+
+Plan choose_plan(const Problem &p) {
+  constexpr int64_t kComputeUnits = 256;
+  if (p.m == 0 || p.n == 0) return {VARIANT_NONE, 1};
+  if (p.k == 0) return {p.accumulate ? VARIANT_NONE : VARIANT_FILL, 1};
+  Variant v = forced_variant();
+  if (v == VARIANT_DMA256 && !dma_eligible(p, false)) v = VARIANT_NONE;
+  if (v == VARIANT_DMA256K128 && !dma_eligible(p, true)) v = VARIANT_NONE;
+  if (v == VARIANT_NONE) {
+    // The largest tile that still gives most compute units a workgroup; a
+    // matrix that is short in one dimension takes a tile that is short there too.
+    if (tile_count(p, 256, 256) >= 192) {
+      // deep k blocks pay off once the k loop is long enough to amortise their prologue
+      if (p.k >= 6144 && dma_eligible(p, true)) v = VARIANT_DMA256K128;
+      else if (dma_eligible(p, false)) v = VARIANT_DMA256;
+      else v = VARIANT_TILE256;
+    } else if (p.m <= 64 && p.n > 128) {
+      v = VARIANT_TILE64X256;
+    } else if (p.n <= 64 && p.m > 128) {
+      v = VARIANT_TILE256X64;
+    } else if (tile_count(p, 128, 128) >= 192) {
+      v = VARIANT_TILE128;
+    } else {
+      v = VARIANT_TILE64;
+    }
+  }
+  int splits = 1;
+  if (v >= VARIANT_TILE256) {
+    splits = forced_splits();
+    if (splits == 0) {
+      // Too few tiles to fill the chip: cut k into ranges, at least 256 deep each,
+      // until there are about two workgroups per compute unit.
+      int64_t bm, bn;
+      tile_shape(v, &bm, &bn);
+      const int64_t tiles = tile_count(p, bm, bn);
+      const int64_t nkt = (p.k + 63) / 64;
+      splits = 1;
+      if (tiles < kComputeUnits / 2) {
+        int64_t want = (2 * kComputeUnits + tiles - 1) / tiles;
+        int64_t most = nkt / 4 > 1 ? nkt / 4 : 1;
+        splits = (int)(want < most ? want : most);
+      }
+    }
+  }
+  return {v, splits};
 }
 
 }  // namespace mip
@@ -123,14 +180,15 @@ int run(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const v
   if (rc != 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  mip::Variant v = mip::choose_variant(p);
+  const mip::Plan plan = mip::choose_plan(p);
+  const mip::Variant v = plan.variant;
   switch (v) {
     case mip::VARIANT_NONE: break;
     case mip::VARIANT_FILL: e = mip::launch_fill_zero(p, s); break;
     case mip::VARIANT_SIMPLE: e = mip::launch_simple(p, s); break;
     case mip::VARIANT_DMA256: e = mip::launch_dma(p, false, s); break;
     case mip::VARIANT_DMA256K128: e = mip::launch_dma(p, true, s); break;
-    default: e = mip::launch_tile(p, v, s); break;
+    default: e = mip::launch_tile(p, v, plan.splits, s); break;
   }
   return static_cast<int>(e);
 }
@@ -192,7 +250,7 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, i
                                   orderB, reinterpret_cast<int32_t *>(uintptr_t(4096)), ldc,
                                   orderC, MIPGEMM_OVERWRITE, nullptr, 0, &p);
   if (rc != 0) return "invalid";
-  return mip::variant_name(mip::choose_variant(p));
+  return mip::variant_name(mip::choose_plan(p).variant);
 }
 
 }  // extern "C"

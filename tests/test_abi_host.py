@@ -84,7 +84,17 @@ def test_strerror_and_workspace(M):
 
 def test_variant_choice(M):
     name = M.mipgemm_variant_name
-    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256_k128"
+    assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256"
+    # unaligned operands or odd sizes cannot use the direct-to-LDS kernels
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile256"
+    assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_tile256"
+    # short in one dimension: a tile that is short there too
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_tile64x256"
+    assert name(4095, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"
+    # column-major C swaps the operand roles
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 16, 1) == "mfma_tile256x64"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
     assert name(0, 4, 4, 4, 0, 4, 0, 4, 0) == "none"
     assert name(4, 4, 4, 1, 0, 4, 0, 4, 0) == "invalid"

@@ -12,7 +12,7 @@ import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = ["auto", "simple", "tile256", "tile128", "tile64"]
+VARIANTS = ["auto", "simple", "tile256", "tile128", "tile64", "tile64x256", "tile256x64"]
 
 
 @pytest.fixture(scope="module")
@@ -26,28 +26,33 @@ def gpu():
 
 
 class VariantEnv:
-    def __init__(self, variant):
-        self.variant = variant
+    """Pins the kernel variant (and optionally the split-k factor) for the calls inside."""
+
+    def __init__(self, variant, splits=None):
+        self.want = {"MIPGEMM_VARIANT": None if variant == "auto" else variant,
+                     "MIPGEMM_SPLITK": None if splits is None else str(splits)}
 
     def __enter__(self):
-        self.old = os.environ.pop("MIPGEMM_VARIANT", None)
-        if self.variant != "auto":
-            os.environ["MIPGEMM_VARIANT"] = self.variant
+        self.old = {k: os.environ.pop(k, None) for k in self.want}
+        for k, v in self.want.items():
+            if v is not None:
+                os.environ[k] = v
 
     def __exit__(self, *a):
-        os.environ.pop("MIPGEMM_VARIANT", None)
-        if self.old is not None:
-            os.environ["MIPGEMM_VARIANT"] = self.old
+        for k, v in self.old.items():
+            os.environ.pop(k, None)
+            if v is not None:
+                os.environ[k] = v
 
 
-def gpu_gemm(M, case, A, B, C, variant="auto"):
+def gpu_gemm(M, case, A, B, C, variant="auto", splits=None):
     """Run the library on host buffers A, B, C (flat numpy); returns the flat C it produced."""
     import torch
     dA = torch.from_numpy(A.view(np.uint8)).cuda()
     dB = torch.from_numpy(B.view(np.uint8)).cuda()
     dC = torch.from_numpy(C).cuda()
     fn = getattr(M, "mipgemm_" + case.entry)
-    with VariantEnv(variant):
+    with VariantEnv(variant, splits):
         fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
            dC, case.ldc, case.orderC, case.mode)
     torch.cuda.synchronize()
@@ -66,11 +71,11 @@ def oracle_result(oracle, case, ops):
     return _expected[case.name]
 
 
-def check_case(M, oracle, case, variant):
-    print("case", case.name, "variant", variant, flush=True)
+def check_case(M, oracle, case, variant, splits=None):
+    print("case", case.name, "variant", variant, "splits", splits, flush=True)
     ops = W.materialize(case)
     want = oracle_result(oracle, case, ops)
-    got = gpu_gemm(M, case, ops.A, ops.B, ops.C, variant)
+    got = gpu_gemm(M, case, ops.A, ops.B, ops.C, variant, splits)
     if not np.array_equal(got, want):
         bad = np.flatnonzero(got != want)
         pytest.fail("%s [%s]: %d of %d words differ, first at %d: got %d want %d" % (
@@ -95,6 +100,17 @@ def test_small_cases_every_variant(gpu, oracle, case, variant):
 @pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
 def test_large_cases(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
+
+
+SPLIT_CASES = [c for c in W.all_cases() if c.k >= 513 and _ops_count(c) <= 2.5e9]
+
+
+@pytest.mark.parametrize("variant,splits", [("tile64", 3), ("tile64x256", 7), ("tile256x64", 2),
+                                            ("tile128", 5), ("tile64", 1000)])
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: c.name)
+def test_split_k_is_exact(gpu, oracle, case, variant, splits):
+    """k cut into ranges added into C with integer atomics: same bits as one pass."""
+    check_case(gpu, oracle, case, variant, splits)
 
 
 @pytest.mark.parametrize("case", W.config3(), ids=lambda c: c.name)
