@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--suite", action="store_true",
+                    help="time every workload case once and print a table instead of the JSON line")
     return ap.parse_args()
 
 
@@ -73,6 +75,53 @@ def cpu_baseline(case: W.Case, ops: W.Operands, rows: int):
     }, C
 
 
+def time_case(M, case, steps, warmup):
+    """Average milliseconds per call, operands resident, events on the launch stream."""
+    import torch
+    ops = W.materialize(case)
+    fn = getattr(M, "mipgemm_" + case.entry)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+           dC, case.ldc, case.orderC, case.mode, stream=stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+           dC, case.ldc, case.orderC, case.mode, stream=stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / steps
+
+
+def run_suite(M, args):
+    """One line per workload case: time, TOPS, GB/s of algorithmic bytes, and the
+    fraction of the roofline max(ops / int8 MFMA peak, bytes / HBM peak)."""
+    print("| case | entry | m | n | k | kernel | us | TOPS | GB/s | bound | frac of roofline |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    seen = set()
+    for case in W.all_cases():
+        key = (case.entry, case.m, case.n, case.k, case.orderA, case.orderB, case.orderC,
+               case.pad, case.mode, case.a_dist[0])
+        if key in seen:
+            continue
+        seen.add(key)
+        ms = time_case(M, case, args.steps, args.warmup)
+        t_mfma = case.ops / (INT8_MFMA_PEAK_TOPS * 1e12)
+        t_hbm = case.algorithmic_bytes / (HBM_PEAK_GBS * 1e9)
+        variant = M.mipgemm_variant_name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
+                                         case.orderB, case.ldc, case.orderC, case.a_unsigned,
+                                         case.b_unsigned, True)
+        print("| %s | %s | %d | %d | %d | %s | %.1f | %.1f | %.1f | %s | %.3f |" % (
+            case.name, case.entry, case.m, case.n, case.k, variant, ms * 1e3,
+            case.ops / ms / 1e9, case.algorithmic_bytes / ms / 1e6,
+            "mfma" if t_mfma >= t_hbm else "hbm", max(t_mfma, t_hbm) / (ms * 1e-3)), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -85,6 +134,10 @@ def main():
         raise SystemExit("no GPU visible: bench.py needs an MI355X")
     import paper_2506_11728_amd as M
     M.load_library()
+
+    if args.suite:
+        run_suite(M, args)
+        return
 
     case = pick_case(args)
     ops = W.materialize(case)

@@ -21,22 +21,40 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every kernel and the C-ABI layer into one shared library."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-x", "hip"] + sources() + ["-o", tmp]
-    if verbose:
-        print(" ".join(cmd), flush=True)
+def _compile(args):
+    hipcc, src, obj = args
+    cmd = [hipcc] + [f for f in HIPCC_FLAGS if f != "-shared"] + ["-c", "-x", "hip", src, "-o", obj]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass does not know the packed-fp32 feature and says so: harmless
     out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
+    return src, proc.returncode, out
+
+
+def build_library(verbose: bool = False, jobs: int = 0) -> str:
+    """Compile every kernel and the C-ABI layer (one object per source, in parallel) and link."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    work = [(hipcc, src, os.path.join(objdir, os.path.basename(src) + ".o")) for src in sources()]
+    jobs = jobs or min(len(work), max(1, min(16, os.cpu_count() or 1)))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(_compile, work))
+    failed = [(src, out) for src, rc, out in results if rc != 0]
+    if failed:
+        raise RuntimeError("hipcc failed:\n" + "\n".join("%s:\n%s" % f for f in failed))
+    if verbose:
+        for src, _, out in results:
+            print("compiled", os.path.relpath(src, HERE), flush=True)
+            if out.strip():
+                print(out, flush=True)
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [w[2] for w in work] + ["-o", tmp]
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
         if os.path.exists(tmp):
             os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out, flush=True)
+        raise RuntimeError("link failed:\n" + proc.stdout)
     os.replace(tmp, LIB)
     return LIB
 

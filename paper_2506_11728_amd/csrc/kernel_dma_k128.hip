@@ -1,0 +1,185 @@
+// The kernel for large, aligned, signed problems (the m = n = k = 8192 class):
+// 256 x 256 tile of C per workgroup, operands streamed global -> LDS directly.
+// See dma_tile.h for the general form; this one trades generality for a deeper
+// k block.
+//
+// Preconditions, checked on the host (dma_k128_eligible): signed operands,
+// overwrite mode, m and n multiples of 256, k a multiple of 128, 16-byte aligned
+// operand bases and leading dimensions, 256 * ld below 2^31.
+#include "dma_common.h"
+
+namespace mip {
+
+namespace {
+
+constexpr int DM = 256, DN = 256;  // workgroup tile
+
+struct DmaParams {
+  const uint8_t *A, *B;
+  int32_t *C;
+  int64_t lda, ldb, ldc;  // the one stride of each operand that is not 1
+  int tiles_m, tiles_n;
+  int nkt;                // k / 128
+};
+
+// ---------------------------------------------------------------------------
+// 256 x 256 tile, k blocks of 128 in two LDS stages: half as many barriers per unit
+// of work as the 64-deep kernel, and every row of a k-contiguous operand is fetched as one full
+// 128-byte line.  A block is four sub-blocks of 32; the barrier that publishes
+// block t+1 sits before the last sub-block of block t, whose fragments are
+// already in registers, so the refill of the stage just read starts there.
+// ---------------------------------------------------------------------------
+constexpr int KD2 = 128;
+constexpr int STAGE2_BYTES = (DM + DN) * KD2;          // 64 KiB
+constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
+  using SA = Stage<DM, A_KC, KD2>;
+  using SB = Stage<DN, B_KC, KD2>;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int tm, tn;
+  if (!tile_of_workgroup(P.tiles_m, P.tiles_n, &tm, &tn)) return;
+  const int64_t m0 = (int64_t)tm * DM, n0 = (int64_t)tn * DN;
+
+  uint32_t offA[LOADS2], offB[LOADS2];
+#pragma unroll
+  for (int i = 0; i < LOADS2; ++i) {
+    int a, c;
+    SA::chunk_of(i, tid, a, c);
+    offA[i] = A_KC ? (uint32_t)(a * P.lda + ((c ^ SA::kswz(a)) << 4))
+                   : (uint32_t)(a * P.lda + ((c ^ SA::swz(a)) << 4));
+    SB::chunk_of(i, tid, a, c);
+    offB[i] = B_KC ? (uint32_t)(a * P.ldb + ((c ^ SB::kswz(a)) << 4))
+                   : (uint32_t)(a * P.ldb + ((c ^ SB::swz(a)) << 4));
+  }
+  const uint8_t *gA = P.A + (A_KC ? m0 * P.lda : m0);
+  const uint8_t *gB = P.B + (B_KC ? n0 * P.ldb : n0);
+  const int64_t stepA = A_KC ? KD2 : KD2 * P.lda;
+  const int64_t stepB = B_KC ? KD2 : KD2 * P.ldb;
+
+  const uint32_t lds0 = lds_address(smem) + wave * 1024;
+  // direct load q of a block: 0..7 A, 8..15 B
+  auto issue_one = [&](int stage, int q) {
+    const uint32_t sa = lds0 + stage * STAGE2_BYTES;
+    if (q < LOADS2) dma16(offA[q], gA, sa + q * 4096);
+    else dma16(offB[q - LOADS2], gB, sa + DM * KD2 + (q - LOADS2) * 4096);
+  };
+  auto advance = [&]() {
+    gA += stepA;
+    gB += stepB;
+  };
+
+  v16i acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  v4i fa[2][4], fb[2][4];
+  auto read_frag = [&](int stage, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
+    const uint8_t *sa = smem + stage * STAGE2_BYTES;
+    if (f < 4) a[f] = SA::fragment(sa, wm * 128 + f * 32, ks, lane);
+    else b[f - 4] = SB::fragment(sa + DM * KD2, wn * 128 + (f - 4) * 32, ks, lane);
+  };
+
+  const int nkt = P.nkt;  // k / 128
+  // prologue: block 0 whole, published; then the first half of block 1
+#pragma unroll
+  for (int q = 0; q < 2 * LOADS2; ++q) issue_one(0, q);
+  advance();
+  publish_barrier<0>();
+#pragma unroll
+  for (int f = 0; f < 8; ++f) read_frag(0, 0, f, fa[0], fb[0]);
+  if (nkt > 1) {
+#pragma unroll
+    for (int q = 0; q < LOADS2; ++q) issue_one(1, q);
+  }
+
+  // 16 MFMAs of one sub-block, with up to 8 fragment reads and 8 direct loads between them
+  auto phase = [&](int set, auto reader, auto loader) {
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+          fb[set][s & 3], fa[set][s >> 2], acc[s >> 2][s & 3], 0, 0, 0);
+      if (s < 8) reader(s);
+      else loader(s - 8);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto nothing = [](int) {};
+
+  // NEXT: block t+1 exists.  NEXT2: block t+2 exists.
+  auto step = [&](int t, auto next_tag, auto next2_tag) {
+    constexpr bool NEXT = decltype(next_tag)::value;
+    constexpr bool NEXT2 = decltype(next2_tag)::value;
+    const int cur = t & 1, oth = cur ^ 1;
+    // sub-block 0; fetch sub-block 1; second half of block t+1 (first half went out in step t-1)
+    phase(0, [&](int f) { read_frag(cur, 1, f, fa[1], fb[1]); },
+          [&](int q) { if (NEXT) issue_one(oth, LOADS2 + q); });
+    if (NEXT) advance();
+    phase(1, [&](int f) { read_frag(cur, 2, f, fa[0], fb[0]); }, nothing);
+    phase(0, [&](int f) { read_frag(cur, 3, f, fa[1], fb[1]); }, nothing);
+    if (NEXT) publish_barrier<0>();  // block t+1 visible; stage `cur` may be refilled
+    phase(1, [&](int f) { if (NEXT) read_frag(oth, 0, f, fa[0], fb[0]); },
+          [&](int q) { if (NEXT2) issue_one(cur, q); });
+  };
+  using std::integral_constant;
+  using T = integral_constant<bool, true>;
+  using F = integral_constant<bool, false>;
+  int t = 0;
+  for (; t + 2 < nkt; ++t) step(t, T{}, T{});
+  if (t + 1 < nkt) { step(t, T{}, F{}); ++t; }
+  step(t, F{}, F{});
+
+  store_blocks<4, 4, true>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc, 128, 128,
+                           false, lane);
+}
+
+}  // namespace
+
+bool dma_k128_eligible(const Problem &p) {
+  if (p.a_unsigned || p.b_unsigned || p.accumulate) return false;
+  if (p.m % DM || p.n % DN || p.k % KD2 || p.k < KD2) return false;
+  const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
+  const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
+  if (lda % 16 || ldb % 16) return false;
+  if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
+  if (256 * lda >= ((int64_t)1 << 31) || 256 * ldb >= ((int64_t)1 << 31)) return false;
+  if ((p.m / DM) * (p.n / DN) > ((int64_t)1 << 30)) return false;
+  return true;
+}
+
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
+  DmaParams P;
+  P.A = static_cast<const uint8_t *>(p.A);
+  P.B = static_cast<const uint8_t *>(p.B);
+  P.C = p.C;
+  P.lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
+  P.ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
+  P.ldc = p.ldc;
+  P.tiles_m = (int)(p.m / DM);
+  P.tiles_n = (int)(p.n / DN);
+  P.nkt = (int)(p.k / KD2);
+  const int ntiles = P.tiles_m * P.tiles_n;
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
+  const size_t lds = (size_t)2 * STAGE2_BYTES;
+  const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  void (*kern)(DmaParams) =
+      a_kc ? (b_kc ? dma128_kernel<true, true> : dma128_kernel<true, false>)
+           : (b_kc ? dma128_kernel<false, true> : dma128_kernel<false, false>);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);
+  return hipGetLastError();
+}
+
+}  // namespace mip

@@ -195,13 +195,13 @@ static hipError_t launch_cfg(const Problem &p, int splits, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_tile(const Problem &p, Variant v, int splits, hipStream_t s) {
-  switch (v) {
-    case VARIANT_TILE256: return launch_cfg<256, 256>(p, splits, s);
-    case VARIANT_TILE128: return launch_cfg<128, 128>(p, splits, s);
-    case VARIANT_TILE64: return launch_cfg<64, 64>(p, splits, s);
-    case VARIANT_TILE64X256: return launch_cfg<64, 256>(p, splits, s);
-    case VARIANT_TILE256X64: return launch_cfg<256, 64>(p, splits, s);
+hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t s) {
+  switch (shape) {
+    case SHAPE_256: return launch_cfg<256, 256>(p, splits, s);
+    case SHAPE_128: return launch_cfg<128, 128>(p, splits, s);
+    case SHAPE_64: return launch_cfg<64, 64>(p, splits, s);
+    case SHAPE_64X256: return launch_cfg<64, 256>(p, splits, s);
+    case SHAPE_256X64: return launch_cfg<256, 64>(p, splits, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -22,33 +22,45 @@ struct Problem {
   int accumulate;
 };
 
-enum Variant {
-  VARIANT_NONE = 0,   // nothing to launch (m == 0 or n == 0, or k == 0 with accumulate)
-  VARIANT_FILL,       // k == 0, overwrite: C := 0
-  VARIANT_SIMPLE,     // one thread per C element, any layout
-  VARIANT_DMA256,     // MFMA, 256 x 256 tile, global->LDS direct loads, aligned full tiles only
-  VARIANT_DMA256K128, // same, k blocks of 128 in two LDS stages
-  VARIANT_TILE256,    // MFMA, 256 x 256 workgroup tile
-  VARIANT_TILE128,    // MFMA, 128 x 128 workgroup tile
-  VARIANT_TILE64,     // MFMA, 64 x 64 workgroup tile
-  VARIANT_TILE64X256, // MFMA, 64 x 256 tile: few rows, many columns
-  VARIANT_TILE256X64, // MFMA, 256 x 64 tile: many rows, few columns
-  VARIANT_COUNT
+// Workgroup tile of the MFMA kernels (rows x columns of C).
+enum Shape { SHAPE_256, SHAPE_128, SHAPE_64, SHAPE_64X256, SHAPE_256X64, SHAPE_COUNT };
+
+enum Kind {
+  KIND_NONE = 0,  // nothing to launch (m == 0 or n == 0, or k == 0 with accumulate)
+  KIND_FILL,      // k == 0, overwrite: C := 0
+  KIND_SIMPLE,    // one thread per C element, any layout
+  KIND_STAGED,    // MFMA tiles, operands staged through registers: any alignment, any size
+  KIND_DMA,       // MFMA tiles, operands streamed global -> LDS directly (aligned, k % 64 == 0)
+  KIND_DMA_K128   // 256 x 256 tiles, 128-deep k blocks: large aligned signed problems
 };
 
-const char *variant_name(Variant v);
-// Kernel and, for the tile kernels, the number of k ranges worked on by separate
-// workgroups (1 = no split).
 struct Plan {
-  Variant variant;
-  int splits;
+  Kind kind;
+  Shape shape;  // KIND_STAGED and KIND_DMA
+  int splits;   // k ranges worked on by separate workgroups (1 = no split)
 };
+
 Plan choose_plan(const Problem &p);
+const char *plan_name(const Plan &plan);  // static string
 
 hipError_t launch_fill_zero(const Problem &p, hipStream_t s);
 hipError_t launch_simple(const Problem &p, hipStream_t s);
-hipError_t launch_tile(const Problem &p, Variant v, int splits, hipStream_t s);
-bool dma_eligible(const Problem &p, bool deep);  // deep: k blocks of 128 instead of 64
-hipError_t launch_dma(const Problem &p, bool deep, hipStream_t s);
+hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t s);
+
+bool dma_k128_eligible(const Problem &p);
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s);
+
+#define MIP_DECLARE_DMA(BM, BN)                        \
+  bool dma_eligible_##BM##x##BN(const Problem &p);     \
+  hipError_t launch_dma_##BM##x##BN(const Problem &p, int splits, hipStream_t s);
+MIP_DECLARE_DMA(256, 256)
+MIP_DECLARE_DMA(128, 128)
+MIP_DECLARE_DMA(64, 64)
+MIP_DECLARE_DMA(64, 256)
+MIP_DECLARE_DMA(256, 64)
+#undef MIP_DECLARE_DMA
+
+bool dma_eligible(const Problem &p, Shape shape);
+hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);
 
 }  // namespace mip

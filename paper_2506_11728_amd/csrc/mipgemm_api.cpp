@@ -9,37 +9,72 @@
 
 namespace mip {
 
-const char *variant_name(Variant v) {
-  switch (v) {
-    case VARIANT_NONE: return "none";
-    case VARIANT_FILL: return "fill_zero";
-    case VARIANT_SIMPLE: return "simple";
-    case VARIANT_DMA256: return "mfma_dma256";
-    case VARIANT_DMA256K128: return "mfma_dma256_k128";
-    case VARIANT_TILE256: return "mfma_tile256";
-    case VARIANT_TILE128: return "mfma_tile128";
-    case VARIANT_TILE64: return "mfma_tile64";
-    case VARIANT_TILE64X256: return "mfma_tile64x256";
-    case VARIANT_TILE256X64: return "mfma_tile256x64";
+bool dma_eligible(const Problem &p, Shape shape) {
+  switch (shape) {
+    case SHAPE_256: return dma_eligible_256x256(p);
+    case SHAPE_128: return dma_eligible_128x128(p);
+    case SHAPE_64: return dma_eligible_64x64(p);
+    case SHAPE_64X256: return dma_eligible_64x256(p);
+    case SHAPE_256X64: return dma_eligible_256x64(p);
+    default: return false;
+  }
+}
+
+hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s) {
+  switch (shape) {
+    case SHAPE_256: return launch_dma_256x256(p, splits, s);
+    case SHAPE_128: return launch_dma_128x128(p, splits, s);
+    case SHAPE_64: return launch_dma_64x64(p, splits, s);
+    case SHAPE_64X256: return launch_dma_64x256(p, splits, s);
+    case SHAPE_256X64: return launch_dma_256x64(p, splits, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+static const char *const kShapeNames[SHAPE_COUNT] = {"256", "128", "64", "64x256", "256x64"};
+static const int64_t kShapeRows[SHAPE_COUNT] = {256, 128, 64, 64, 256};
+static const int64_t kShapeCols[SHAPE_COUNT] = {256, 128, 64, 256, 64};
+
+const char *plan_name(const Plan &plan) {
+  static const char *const staged[SHAPE_COUNT] = {"mfma_tile256", "mfma_tile128", "mfma_tile64",
+                                                  "mfma_tile64x256", "mfma_tile256x64"};
+  static const char *const dma[SHAPE_COUNT] = {"mfma_dma256", "mfma_dma128", "mfma_dma64",
+                                               "mfma_dma64x256", "mfma_dma256x64"};
+  switch (plan.kind) {
+    case KIND_NONE: return "none";
+    case KIND_FILL: return "fill_zero";
+    case KIND_SIMPLE: return "simple";
+    case KIND_STAGED: return staged[plan.shape];
+    case KIND_DMA: return dma[plan.shape];
+    case KIND_DMA_K128: return "mfma_dma256_k128";
     default: return "?";
   }
 }
 
-// MIPGEMM_VARIANT pins the kernel (tuning and tests): simple, dma256, dma256k128,
-// tile256, tile128, tile64, tile64x256, tile256x64.  The two dma variants only apply
-// to problems they are eligible for; others keep the automatic choice.
+// MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
+// "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
+// 256, 128, 64, 64x256, 256x64.  A dma variant only applies to problems it is
+// eligible for; others fall back to the staged kernel of the same shape.
 // MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
-static Variant forced_variant() {
+static bool forced_plan(const Problem &p, Plan *plan) {
   const char *e = std::getenv("MIPGEMM_VARIANT");
-  if (!e || !*e) return VARIANT_NONE;
-  static const struct { const char *name; Variant v; } table[] = {
-      {"simple", VARIANT_SIMPLE},         {"dma256", VARIANT_DMA256},
-      {"dma256k128", VARIANT_DMA256K128}, {"tile256", VARIANT_TILE256},
-      {"tile128", VARIANT_TILE128},       {"tile64", VARIANT_TILE64},
-      {"tile64x256", VARIANT_TILE64X256}, {"tile256x64", VARIANT_TILE256X64}};
-  for (const auto &t : table)
-    if (!std::strcmp(e, t.name)) return t.v;
-  return VARIANT_NONE;
+  if (!e || !*e) return false;
+  if (!std::strcmp(e, "simple")) { *plan = {KIND_SIMPLE, SHAPE_64, 1}; return true; }
+  if (!std::strcmp(e, "dma256k128")) {
+    if (!dma_k128_eligible(p)) return false;
+    *plan = {KIND_DMA_K128, SHAPE_256, 1};
+    return true;
+  }
+  const bool want_dma = !std::strncmp(e, "dma", 3);
+  if (!want_dma && std::strncmp(e, "tile", 4)) return false;
+  const char *shape = e + (want_dma ? 3 : 4);
+  for (int i = 0; i < SHAPE_COUNT; ++i)
+    if (!std::strcmp(shape, kShapeNames[i])) {
+      const Shape sh = static_cast<Shape>(i);
+      *plan = {want_dma && dma_eligible(p, sh) ? KIND_DMA : KIND_STAGED, sh, 1};
+      return true;
+    }
+  return false;
 }
 
 static int forced_splits() {
@@ -49,64 +84,50 @@ static int forced_splits() {
   return v > 0 ? v : 0;
 }
 
-static int64_t tile_count(const Problem &p, int64_t bm, int64_t bn) {
-  return ((p.m + bm - 1) / bm) * ((p.n + bn - 1) / bn);
-}
-
-static void tile_shape(Variant v, int64_t *bm, int64_t *bn) {
-  switch (v) {
-    case VARIANT_TILE256: *bm = 256; *bn = 256; break;
-    case VARIANT_TILE128: *bm = 128; *bn = 128; break;
-    case VARIANT_TILE64X256: *bm = 64; *bn = 256; break;
-    case VARIANT_TILE256X64: *bm = 256; *bn = 64; break;
-    default: *bm = 64; *bn = 64; break;
-  }
+static int64_t tile_count(const Problem &p, Shape s) {
+  return ((p.m + kShapeRows[s] - 1) / kShapeRows[s]) * ((p.n + kShapeCols[s] - 1) / kShapeCols[s]);
 }
 
 Plan choose_plan(const Problem &p) {
   constexpr int64_t kComputeUnits = 256;
-  if (p.m == 0 || p.n == 0) return {VARIANT_NONE, 1};
-  if (p.k == 0) return {p.accumulate ? VARIANT_NONE : VARIANT_FILL, 1};
-  Variant v = forced_variant();
-  if (v == VARIANT_DMA256 && !dma_eligible(p, false)) v = VARIANT_NONE;
-  if (v == VARIANT_DMA256K128 && !dma_eligible(p, true)) v = VARIANT_NONE;
-  if (v == VARIANT_NONE) {
+  if (p.m == 0 || p.n == 0) return {KIND_NONE, SHAPE_64, 1};
+  if (p.k == 0) return {p.accumulate ? KIND_NONE : KIND_FILL, SHAPE_64, 1};
+  Plan plan;
+  if (!forced_plan(p, &plan)) {
     // The largest tile that still gives most compute units a workgroup; a
     // matrix that is short in one dimension takes a tile that is short there too.
-    if (tile_count(p, 256, 256) >= 192) {
-      // deep k blocks pay off once the k loop is long enough to amortise their prologue
-      if (p.k >= 6144 && dma_eligible(p, true)) v = VARIANT_DMA256K128;
-      else if (dma_eligible(p, false)) v = VARIANT_DMA256;
-      else v = VARIANT_TILE256;
-    } else if (p.m <= 64 && p.n > 128) {
-      v = VARIANT_TILE64X256;
-    } else if (p.n <= 64 && p.m > 128) {
-      v = VARIANT_TILE256X64;
-    } else if (tile_count(p, 128, 128) >= 192) {
-      v = VARIANT_TILE128;
-    } else {
-      v = VARIANT_TILE64;
-    }
+    Shape sh;
+    if (p.m <= 64 && p.n > 128) sh = SHAPE_64X256;
+    else if (p.n <= 64 && p.m > 128) sh = SHAPE_256X64;
+    else if (tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
+    else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
+    else sh = SHAPE_64;
+    // deep k blocks pay off once the k loop is long enough to amortise their prologue
+    if (sh == SHAPE_256 && p.k >= 6144 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    else plan = {dma_eligible(p, sh) ? KIND_DMA : KIND_STAGED, sh, 1};
   }
-  int splits = 1;
-  if (v >= VARIANT_TILE256) {
-    splits = forced_splits();
-    if (splits == 0) {
-      // Too few tiles to fill the chip: cut k into ranges, at least 256 deep each,
-      // until there are about two workgroups per compute unit.
-      int64_t bm, bn;
-      tile_shape(v, &bm, &bn);
-      const int64_t tiles = tile_count(p, bm, bn);
+  if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
+    plan.splits = forced_splits();
+    if (plan.splits == 0) {
+      // Too few tiles to fill the chip: cut k into ranges of at least 256 until
+      // there are about two workgroups per compute unit.  Every range adds its
+      // partial sums into C with atomics, so short problems (few rows of C per
+      // byte of operand) may split further than tall ones.
+      const int64_t tiles = tile_count(p, plan.shape);
       const int64_t nkt = (p.k + 63) / 64;
-      splits = 1;
+      plan.splits = 1;
       if (tiles < kComputeUnits / 2) {
-        int64_t want = (2 * kComputeUnits + tiles - 1) / tiles;
-        int64_t most = nkt / 4 > 1 ? nkt / 4 : 1;
-        splits = (int)(want < most ? want : most);
+        const int64_t want = (2 * kComputeUnits + tiles - 1) / tiles;
+        const int64_t most = nkt / 4 > 1 ? nkt / 4 : 1;
+        const int64_t short_side = p.m < p.n ? p.m : p.n;
+        const int64_t atomics_ok = short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4);
+        int64_t sp = want < most ? want : most;
+        if (sp > atomics_ok) sp = atomics_ok;
+        plan.splits = (int)sp;
       }
     }
   }
-  return {v, splits};
+  return plan;
 }
 
 }  // namespace mip
@@ -181,14 +202,13 @@ int run(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const v
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   const mip::Plan plan = mip::choose_plan(p);
-  const mip::Variant v = plan.variant;
-  switch (v) {
-    case mip::VARIANT_NONE: break;
-    case mip::VARIANT_FILL: e = mip::launch_fill_zero(p, s); break;
-    case mip::VARIANT_SIMPLE: e = mip::launch_simple(p, s); break;
-    case mip::VARIANT_DMA256: e = mip::launch_dma(p, false, s); break;
-    case mip::VARIANT_DMA256K128: e = mip::launch_dma(p, true, s); break;
-    default: e = mip::launch_tile(p, v, plan.splits, s); break;
+  switch (plan.kind) {
+    case mip::KIND_NONE: break;
+    case mip::KIND_FILL: e = mip::launch_fill_zero(p, s); break;
+    case mip::KIND_SIMPLE: e = mip::launch_simple(p, s); break;
+    case mip::KIND_STAGED: e = mip::launch_staged(p, plan.shape, plan.splits, s); break;
+    case mip::KIND_DMA: e = mip::launch_dma(p, plan.shape, plan.splits, s); break;
+    case mip::KIND_DMA_K128: e = mip::launch_dma_k128(p, s); break;
   }
   return static_cast<int>(e);
 }
@@ -250,7 +270,7 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, i
                                   orderB, reinterpret_cast<int32_t *>(uintptr_t(4096)), ldc,
                                   orderC, MIPGEMM_OVERWRITE, nullptr, 0, &p);
   if (rc != 0) return "invalid";
-  return mip::variant_name(mip::choose_plan(p).variant);
+  return mip::plan_name(mip::choose_plan(p));
 }
 
 }  // extern "C"

@@ -86,15 +86,23 @@ def test_variant_choice(M):
     name = M.mipgemm_variant_name
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256_k128"
     assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256"
-    # unaligned operands or odd sizes cannot use the direct-to-LDS kernels
+    # unaligned operands cannot use the direct-to-LDS kernels
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile256"
-    assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
-    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_tile256"
+    # a ragged row edge or an unsigned operand can, but not with the deep-k kernel
+    assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256"
+    # a row-major B with n not a multiple of 16 cannot
+    assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
     # short in one dimension: a tile that is short there too
-    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_tile64x256"
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64x256"
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0, aligned16=False) == "mfma_tile64x256"
     assert name(4095, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"
     # column-major C swaps the operand roles
-    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 16, 1) == "mfma_tile256x64"
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 16, 1) == "mfma_dma256x64"
+    # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
+    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    # k not a multiple of 64 does not
+    assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
     assert name(0, 4, 4, 4, 0, 4, 0, 4, 0) == "none"
     assert name(4, 4, 4, 1, 0, 4, 0, 4, 0) == "invalid"
