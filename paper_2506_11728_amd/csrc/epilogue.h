@@ -88,23 +88,36 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
 }
 
 // Split-k write-back: every workgroup adds its partial sums into C with integer
-// atomics (order-independent, so still bit-exact).
+// atomics (order-independent, so still bit-exact).  The blocks sit transposed in
+// registers (lane = row), which would scatter one atomic instruction over 64
+// cache lines; each block is turned through a wave-private 32 x 33 word patch of
+// LDS so that the lanes of one instruction cover 32 consecutive columns of a row.
+// `patch` is this wave's 4224-byte LDS area; the caller has made sure that no
+// wave still reads operand stages from LDS.
+constexpr int ATOMIC_PATCH_BYTES = 32 * 33 * 4;
+
 template <int FM, int FN>
 __device__ __forceinline__ void add_blocks_atomic(const v16i (&acc)[FM][FN], int32_t *C,
                                                   int64_t ldc, int64_t rows, int64_t cols,
-                                                  int lane) {
+                                                  int lane, int32_t *patch) {
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-    const int row = i * 32 + (lane & 31);
-    if (row >= rows) continue;
-    int32_t *crow = C + row * ldc + 4 * (lane >> 5);
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int j = 0; j < FN; ++j) {
+      if (i * 32 >= rows || j * 32 >= cols) continue;  // wave-uniform
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int col = j * 32 + 8 * (v >> 2) + (v & 3);
-        if (col + 4 * (lane >> 5) < cols) atomicAdd(crow + col, acc[i][j][v]);
+      for (int v = 0; v < 16; ++v)
+        patch[(lane & 31) * 33 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = acc[i][j][v];
+      // same wave wrote and reads: LDS operations of a wave complete in order
+      const int col = j * 32 + (lane & 31);
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const int r = 2 * t + (lane >> 5);
+        const int val = patch[r * 33 + (lane & 31)];
+        const int row = i * 32 + r;
+        if (row < rows && col < cols) atomicAdd(C + row * ldc + col, val);
       }
+    }
   }
 }
 

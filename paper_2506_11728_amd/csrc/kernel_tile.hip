@@ -45,7 +45,10 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   using SA = Stage<BM, A_KC>;
   using SB = Stage<BN, B_KC>;
   constexpr int STAGE_BYTES = (BM + BN) * BK;
-  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE_BYTES];
+  // two operand stages; the split-k write-back reuses the space as four transpose patches
+  constexpr int SMEM_BYTES =
+      2 * STAGE_BYTES > 4 * ATOMIC_PATCH_BYTES ? 2 * STAGE_BYTES : 4 * ATOMIC_PATCH_BYTES;
+  __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
 
   const Problem &p = tp.p;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -159,7 +162,11 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < p.m && nw < p.n) {
     int32_t *C = p.C + mw * p.ldc + nw;
-    if (tp.atomic) add_blocks_atomic<FM, FN>(acc, C, p.ldc, p.m - mw, p.n - nw, lane);
+    if (tp.atomic) {
+      // the k loop ended on a workgroup barrier: no wave still reads the stages
+      add_blocks_atomic<FM, FN>(acc, C, p.ldc, p.m - mw, p.n - nw, lane,
+                                reinterpret_cast<int32_t *>(smem + wave * ATOMIC_PATCH_BYTES));
+    }
     else if (!edge_tile) store_blocks<FM, FN, true>(acc, C, p.ldc, BM / 2, BN / 2, p.accumulate, lane);
     else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane);
   }

@@ -106,7 +106,7 @@ def test_variant_choice(M):
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
     assert name(0, 4, 4, 4, 0, 4, 0, 4, 0) == "none"
     assert name(4, 4, 4, 1, 0, 4, 0, 4, 0) == "invalid"
-    assert name(256, 256, 256, 256, 0, 256, 0, 256, 0).startswith("mfma_tile")
+    assert name(256, 256, 256, 256, 0, 256, 0, 256, 0) == "mfma_dma64"
 
 
 def test_binding_fails_loudly_without_library(M, monkeypatch):
