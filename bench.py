@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy and exit (scales the HBM byte counters)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the register-resident MFMA rate probe")
     ap.add_argument("--suite", action="store_true",
                     help="time every workload case once and print a table instead of the JSON line")
     return ap.parse_args()
@@ -73,6 +77,54 @@ def cpu_baseline(case: W.Case, ops: W.Operands, rows: int):
         "sample": "first %d of %d rows of C (m=%d, n=%d, k=%d), %.2f s, plain C triple loop, "
                   "OpenMP over rows" % (rows, case.m, rows, case.n, case.k, dt),
     }, C
+
+
+KERNEL_SOURCES = ("dma_common.h", "dma_tile.h", "epilogue.h", "lds_layout.h",
+                  "kernel_dma_k128.hip", "kernel_dma_256x256.hip")
+
+
+def kernel_fingerprint() -> str:
+    """Hash of the sources of the headline kernel: counters taken on other code do not count."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2506_11728_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(variant: str, case: W.Case):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None if the
+    summary is missing, is for another kernel or workload, or predates a change of the kernel."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_%dx%dx%d.txt" % (
+        variant, case.m, case.n, case.k))
+    if not os.path.exists(path):
+        return None
+    fields = {}
+    with open(path) as f:
+        for line in f:
+            if ":" in line and not line.startswith("#"):
+                k, v = line.split(":", 1)
+                fields[k.strip()] = v.strip()
+    if fields.get("kernel_fingerprint") != kernel_fingerprint():
+        return None
+    try:
+        return float(fields["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def copy_calibration():
+    """A plain copy kernel of known size: 1 GiB read, 1 GiB written, five times."""
+    import torch
+    n = 1 << 30
+    src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
 
 
 def time_case(M, case, steps, warmup):
@@ -135,6 +187,9 @@ def main():
     import paper_2506_11728_amd as M
     M.load_library()
 
+    if args.copy_calibration:
+        copy_calibration()
+        return
     if args.suite:
         run_suite(M, args)
         return
@@ -181,6 +236,8 @@ def main():
                     "unit": "GB/s", "frac": kernel_gbs / HBM_PEAK_GBS, "traffic": None}
     roofline["kernel"] = variant
     roofline["kernel_ms"] = kernel_ms
+    roofline["traffic"] = recorded_traffic(variant, case)
+    roofline["algorithmic_bytes"] = case.algorithmic_bytes
 
     out = {
         "metric": "int8 GEMM TOPS (int32 acc) at m=n=k=8192; % of MI355X int8 MFMA peak",
@@ -193,6 +250,15 @@ def main():
         "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
         "roofline": roofline,
     }
+
+    if not args.no_ceiling:
+        # what the matrix instruction itself sustains on this device, operands in registers:
+        # the chip is power-limited and the rate depends on the operand bits
+        zero = M.mipgemm_mfma_ceiling(0, 20000)
+        rand = M.mipgemm_mfma_ceiling(1, 20000)
+        out["mfma_only_ceiling"] = {
+            "unit": "TOPS", "near_zero_operands": zero, "random_operands": rand,
+            "kernel_frac_of_random_ceiling": kernel_tops / rand}
 
     check_rows = None
     if not args.no_cpu_baseline:

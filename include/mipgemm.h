@@ -127,6 +127,22 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k,
                                  int64_t ldc, int orderC,
                                  int a_unsigned, int b_unsigned, int aligned16);
 
+/*
+ * Device characterisation for benchmarks: the throughput, in 10^12 operations
+ * per second (2 operations per multiply-accumulate, the count of the paper's
+ * Section 7.4), of the int8 matrix instruction the GEMM kernels are built on
+ * when every operand is already in registers.  No kernel that uses the
+ * instruction can exceed it on this device at this moment.  pattern 0 uses
+ * operands that are almost all zero bits; pattern 1 uses random bytes that
+ * change every iteration, as a GEMM on random data does.  The device is
+ * power-limited, so the two differ widely.  One iteration is 128 x 128 x 64
+ * multiply-accumulates per wave.  `tops` is a HOST pointer.  Unlike the GEMM
+ * entry points this call allocates a few bytes of device memory, waits for its
+ * kernel to finish and frees them again.  Returns 0, the negative number of an
+ * invalid argument (1 pattern, 2 iterations, 4 tops), or a positive hipError_t.
+ */
+int mipgemm_mfma_ceiling(int pattern, int iterations, void *stream, double *tops);
+
 #ifdef __cplusplus
 }
 #endif

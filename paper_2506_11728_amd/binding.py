@@ -42,7 +42,8 @@ def library_path() -> str:
 def exported_symbols():
     """Names include/mipgemm.h declares; the library must export every one."""
     return ["mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32",
-            "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name"]
+            "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
+            "mipgemm_mfma_ceiling"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -66,6 +67,9 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_variant_name.argtypes = ([ctypes.c_int64] * 3
                                                  + [ctypes.c_int64, ctypes.c_int] * 3
                                                  + [ctypes.c_int] * 3)
+            lib.mipgemm_mfma_ceiling.restype = ctypes.c_int
+            lib.mipgemm_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                                 ctypes.POINTER(ctypes.c_double)]
             _lib = lib
     return _lib
 
@@ -131,3 +135,12 @@ def mipgemm_variant_name(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
     return load_library().mipgemm_variant_name(
         m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
         int(a_unsigned), int(b_unsigned), int(aligned16)).decode()
+
+
+def mipgemm_mfma_ceiling(pattern: int, iterations: int = 20000, stream=None) -> float:
+    """TOPS of the register-resident int8 MFMA loop (0: near-zero operands, 1: random operands)."""
+    out = ctypes.c_double(0.0)
+    rc = load_library().mipgemm_mfma_ceiling(pattern, iterations, _stream(stream), ctypes.byref(out))
+    if rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc) if rc > 0 else "invalid argument %d" % -rc)
+    return out.value
