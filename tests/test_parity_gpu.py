@@ -221,3 +221,62 @@ def test_runs_on_a_side_stream(gpu, oracle):
                         case.mode, stream=s)
     s.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)
+
+
+# ---------------------------------------------------------------------------
+# seeded sweep over shapes, orders, leading dimensions, signedness and modes
+# ---------------------------------------------------------------------------
+
+def _sweep_cases():
+    rng = np.random.default_rng(2024)
+    cases = []
+    for idx in range(160):
+        aligned = idx % 2 == 0            # half the cases can take the direct-to-LDS kernels
+        if aligned:
+            k = int(rng.integers(1, 9)) * 64
+            m = int(rng.integers(1, 420))
+            n = int(rng.integers(1, 420))
+            pad = int(rng.choice([0, 16, 32, 48]))
+        else:
+            k = int(rng.integers(1, 400))
+            m = int(rng.integers(1, 300))
+            n = int(rng.integers(1, 300))
+            pad = int(rng.choice([0, 1, 3, 17]))
+        oa, ob, oc = (int(x) for x in rng.integers(0, 2, size=3))
+        if aligned:
+            # leading dimensions become multiples of 16: round the contiguous extents up
+            def up16(x):
+                return (x + 15) // 16 * 16
+            if oa == W.COL_MAJOR:
+                m = up16(m)
+            if ob == W.ROW_MAJOR:
+                n = up16(n)
+            if oa == W.ROW_MAJOR:
+                pass                       # lda = k + pad, already a multiple of 16
+            if ob == W.COL_MAJOR:
+                pass                       # ldb = k + pad
+        uns = int(rng.integers(0, 3))
+        mode = int(rng.integers(0, 2))
+        cases.append(W.Case(
+            "sweep%03d_%dx%dx%d_%d%d%d_p%d_u%d_m%d" % (idx, m, n, k, oa, ob, oc, pad, uns, mode),
+            8, idx, m, n, k, a_unsigned=uns == 1, b_unsigned=uns == 2,
+            orderA=oa, orderB=ob, orderC=oc, pad=pad, mode=mode,
+            a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+            b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+            c_dist=("uniform", -1000, 1000), seed=7))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: c.name)
+def test_seeded_sweep(gpu, oracle, case):
+    check_case(gpu, oracle, case, "auto")
+    if case.k >= 128:
+        check_case(gpu, oracle, case, "auto", splits=2)
+
+
+def test_mfma_ceiling_probe(gpu):
+    zero = gpu.mipgemm_mfma_ceiling(0, 2000)
+    rand = gpu.mipgemm_mfma_ceiling(1, 2000)
+    assert 500 < rand <= zero * 1.05 and zero < 5600      # TOPS, below the datasheet peak + margin
+    with pytest.raises(gpu.MipGemmError):
+        gpu.mipgemm_mfma_ceiling(2, 2000)
