@@ -214,7 +214,7 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   step(t, integral_constant<bool, false>{}, integral_constant<int, -1>{});
 
   // ---- write-back: unsigned-operand correction, then C = / += / atomic += ----
-  if (P.atomic) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // stages are dead from here on
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // stages are dead from here on
   unsigned_correction<FM, FN>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < P.m && nw < P.n) {
@@ -223,7 +223,9 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
     if (P.atomic)
       add_blocks_atomic<FM, FN>(acc, C, P.ldc, P.m - mw, P.n - nw, lane,
                                 reinterpret_cast<int32_t *>(smem + wave * ATOMIC_PATCH_BYTES));
-    else if (full) store_blocks<FM, FN, true>(acc, C, P.ldc, BM / 2, BN / 2, P.accumulate, lane);
+    else if (full)
+      store_blocks_via_lds<FM, FN>(acc, C, P.ldc, P.accumulate, lane,
+                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
     else store_blocks<FM, FN, false>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate, lane);
   }
 }

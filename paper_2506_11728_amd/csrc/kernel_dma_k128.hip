@@ -139,8 +139,10 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   if (t + 1 < nkt) { step(t, T{}, F{}); ++t; }
   step(t, F{}, F{});
 
-  store_blocks<4, 4, true>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc, 128, 128,
-                           false, lane);
+  // the last step has no barrier of its own: wait until no wave reads the stages any more
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  store_blocks_via_lds<4, 4>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc, false, lane,
+                             reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
 }
 
 }  // namespace

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   constexpr int STAGE_BYTES = (BM + BN) * BK;
   // two operand stages; the split-k write-back reuses the space as four transpose patches
   constexpr int SMEM_BYTES =
-      2 * STAGE_BYTES > 4 * ATOMIC_PATCH_BYTES ? 2 * STAGE_BYTES : 4 * ATOMIC_PATCH_BYTES;
+      2 * STAGE_BYTES > 4 * STORE_PATCH_BYTES ? 2 * STAGE_BYTES : 4 * STORE_PATCH_BYTES;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
 
   const Problem &p = tp.p;
@@ -167,7 +167,9 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
       add_blocks_atomic<FM, FN>(acc, C, p.ldc, p.m - mw, p.n - nw, lane,
                                 reinterpret_cast<int32_t *>(smem + wave * ATOMIC_PATCH_BYTES));
     }
-    else if (!edge_tile) store_blocks<FM, FN, true>(acc, C, p.ldc, BM / 2, BN / 2, p.accumulate, lane);
+    else if (!edge_tile)
+      store_blocks_via_lds<FM, FN>(acc, C, p.ldc, p.accumulate, lane,
+                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
     else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane);
   }
 }
