@@ -1,11 +1,11 @@
-// The kernel for large, aligned, signed problems (the m = n = k = 8192 class):
+// The kernel for large, aligned problems (the m = n = k = 8192 class):
 // 256 x 256 tile of C per workgroup, operands streamed global -> LDS directly.
 // See dma_tile.h for the general form; this one trades generality for a deeper
 // k block.
 //
-// Preconditions, checked on the host (dma_k128_eligible): signed operands,
-// overwrite mode, m and n multiples of 256, k a multiple of 128, 16-byte aligned
-// operand bases and leading dimensions, 256 * ld below 2^31.
+// Preconditions, checked on the host (dma_k128_eligible): m and n multiples of
+// 256, k a multiple of 128, 16-byte aligned operand bases and leading
+// dimensions, 256 * ld below 2^31.
 #include "dma_common.h"
 
 namespace mip {
@@ -20,6 +20,7 @@ struct DmaParams {
   int64_t lda, ldb, ldc;  // the one stride of each operand that is not 1
   int tiles_m, tiles_n;
   int nkt;                // k / 128
+  int accumulate;         // C += instead of C =
 };
 
 // ---------------------------------------------------------------------------
@@ -33,7 +34,8 @@ constexpr int KD2 = 128;
 constexpr int STAGE2_BYTES = (DM + DN) * KD2;          // 64 KiB
 constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
 
-template <bool A_KC, bool B_KC>
+// UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
+template <bool A_KC, bool B_KC, int UNS>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   using SA = Stage<DM, A_KC, KD2>;
   using SB = Stage<DN, B_KC, KD2>;
@@ -83,7 +85,29 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+  int sumA[4] = {0, 0, 0, 0}, sumB[4] = {0, 0, 0, 0};  // k sums of the signed operand
   v4i fa[2][4], fb[2][4];
+  // unsigned operand: bias its bytes to signed, and sum the other operand over k
+  auto prepare = [&](v4i (&a)[4], v4i (&b)[4]) {
+    if (UNS == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] ^= (int)0x80808080u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          sumB[j] = __builtin_amdgcn_sdot4(b[j][r], 0x01010101, sumB[j], false);
+    }
+    if (UNS == 2) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] ^= (int)0x80808080u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          sumA[i] = __builtin_amdgcn_sdot4(a[i][r], 0x01010101, sumA[i], false);
+    }
+  };
   auto read_frag = [&](int stage, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
     const uint8_t *sa = smem + stage * STAGE2_BYTES;
     if (f < 4) a[f] = SA::fragment(sa, wm * 128 + f * 32, ks, lane);
@@ -105,6 +129,7 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
 
   // 16 MFMAs of one sub-block, with up to 8 fragment reads and 8 direct loads between them
   auto phase = [&](int set, auto reader, auto loader) {
+    prepare(fa[set], fb[set]);
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
@@ -141,14 +166,15 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
 
   // the last step has no barrier of its own: wait until no wave reads the stages any more
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  store_blocks_via_lds<4, 4>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc, false, lane,
+  unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
+  store_blocks_via_lds<4, 4>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc,
+                             P.accumulate != 0, lane,
                              reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
 }
 
 }  // namespace
 
 bool dma_k128_eligible(const Problem &p) {
-  if (p.a_unsigned || p.b_unsigned || p.accumulate) return false;
   if (p.m % DM || p.n % DN || p.k % KD2 || p.k < KD2) return false;
   const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
   const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
@@ -170,13 +196,21 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
   P.tiles_m = (int)(p.m / DM);
   P.tiles_n = (int)(p.n / DN);
   P.nkt = (int)(p.k / KD2);
+  P.accumulate = p.accumulate;
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
   const size_t lds = (size_t)2 * STAGE2_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
-  void (*kern)(DmaParams) =
-      a_kc ? (b_kc ? dma128_kernel<true, true> : dma128_kernel<true, false>)
-           : (b_kc ? dma128_kernel<false, true> : dma128_kernel<false, false>);
+  const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
+  void (*kern)(DmaParams) = nullptr;
+#define MIP_PICK(AK, BKC)                                                        \
+  kern = uns == 0 ? dma128_kernel<AK, BKC, 0>                                    \
+                  : (uns == 1 ? dma128_kernel<AK, BKC, 1> : dma128_kernel<AK, BKC, 2>)
+  if (a_kc && b_kc) MIP_PICK(true, true);
+  else if (a_kc) MIP_PICK(true, false);
+  else if (b_kc) MIP_PICK(false, true);
+  else MIP_PICK(false, false);
+#undef MIP_PICK
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

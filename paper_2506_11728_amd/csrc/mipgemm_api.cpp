@@ -103,7 +103,7 @@ Plan choose_plan(const Problem &p) {
     else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
-    if (sh == SHAPE_256 && p.k >= 6144 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     else plan = {dma_eligible(p, sh) ? KIND_DMA : KIND_STAGED, sh, 1};
   }
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {

@@ -85,12 +85,13 @@ def test_strerror_and_workspace(M):
 def test_variant_choice(M):
     name = M.mipgemm_variant_name
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256_k128"
-    assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256"
+    assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
+    assert name(4096, 4096, 1024, 1024, 0, 4096, 0, 4096, 0) == "mfma_dma256"
     # unaligned operands cannot use the direct-to-LDS kernels
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile256"
-    # a ragged row edge or an unsigned operand can, but not with the deep-k kernel
+    # a ragged row edge can, but not with the deep-k kernel; an unsigned operand can
     assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256"
-    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256_k128"
     # a row-major B with n not a multiple of 16 cannot
     assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
     # short in one dimension: a tile that is short there too

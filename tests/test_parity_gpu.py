@@ -168,6 +168,14 @@ def test_wraparound_on_device(gpu, oracle):
     case = W.Case("wrap", 9, 0, 40, 33, k, a_dist=("const", -128), b_dist=("const", -128))
     check_case(gpu, oracle, case, "auto")
     check_case(gpu, oracle, case, "tile128")
+    # k a multiple of 128: the direct-to-LDS kernels, with and without split k
+    case = W.Case("wrap_dma", 9, 1, 64, 48, 131072 + 128, a_dist=("const", -128),
+                  b_dist=("const", -128))
+    check_case(gpu, oracle, case, "dma64")
+    check_case(gpu, oracle, case, "dma64", splits=1)
+    case = W.Case("wrap_deepk", 9, 2, 256, 256, 131072 + 128, a_dist=("const", -128),
+                  b_dist=("const", -128))
+    check_case(gpu, oracle, case, "dma256k128")
 
 
 def test_empty_problems(gpu):
@@ -280,3 +288,31 @@ def test_mfma_ceiling_probe(gpu):
     assert 500 < rand <= zero * 1.05 and zero < 5600      # TOPS, below the datasheet peak + margin
     with pytest.raises(gpu.MipGemmError):
         gpu.mipgemm_mfma_ceiling(2, 2000)
+
+
+def _deep_k_cases():
+    out = []
+    idx = 0
+    for (m, n, k) in ((512, 768, 2048), (256, 256, 128), (768, 512, 384)):
+        for uns in (0, 1, 2):
+            for mode in (W.OVERWRITE, W.ACCUMULATE):
+                for (oa, ob, oc) in ((0, 0, 0), (0, 1, 0), (1, 0, 1), (1, 1, 0)):
+                    out.append(W.Case(
+                        "deepk_%dx%dx%d_u%d_m%d_%d%d%d" % (m, n, k, uns, mode, oa, ob, oc), 8, idx,
+                        m, n, k, a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob,
+                        orderC=oc, pad=16 * (idx % 3), mode=mode,
+                        a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+                        b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+                        c_dist=("uniform", -1000, 1000), seed=9))
+                    idx += 1
+    return out
+
+
+@pytest.mark.parametrize("case", _deep_k_cases(), ids=lambda c: c.name)
+def test_deep_k_kernel_unsigned_and_accumulate(gpu, oracle, case):
+    """The 256 x 256, 128-deep kernel pinned on shapes it is eligible for."""
+    name = gpu.mipgemm_variant_name
+    with VariantEnv("dma256k128"):
+        assert name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB, case.ldc,
+                    case.orderC, case.a_unsigned, case.b_unsigned, True) == "mfma_dma256_k128"
+    check_case(gpu, oracle, case, "dma256k128")
