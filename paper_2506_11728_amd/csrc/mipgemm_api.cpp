@@ -96,9 +96,12 @@ Plan choose_plan(const Problem &p) {
   if (!forced_plan(p, &plan)) {
     // The largest tile that still gives most compute units a workgroup; a
     // matrix that is short in one dimension takes a tile that is short there too.
+    // A short side (a few tokens, a few output channels) makes the problem a
+    // stream over the long operand: wide tiles only when the long side alone
+    // fills the chip, else 64 x 64 tiles, which give four times as many workgroups.
     Shape sh;
-    if (p.m <= 64 && p.n > 128) sh = SHAPE_64X256;
-    else if (p.n <= 64 && p.m > 128) sh = SHAPE_256X64;
+    if (p.m <= 64 && p.n > 128) sh = tile_count(p, SHAPE_64X256) >= kComputeUnits ? SHAPE_64X256 : SHAPE_64;
+    else if (p.n <= 64 && p.m > 128) sh = tile_count(p, SHAPE_256X64) >= kComputeUnits ? SHAPE_256X64 : SHAPE_64;
     else if (tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
     else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
@@ -109,16 +112,17 @@ Plan choose_plan(const Problem &p) {
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
     plan.splits = forced_splits();
     if (plan.splits == 0) {
-      // Too few tiles to fill the chip: cut k into ranges of at least 256 until
-      // there are about two workgroups per compute unit.  Every range adds its
-      // partial sums into C with atomics, so short problems (few rows of C per
-      // byte of operand) may split further than tall ones.
+      // Too few tiles to fill the chip: cut k into ranges of at least 512 until
+      // there is about one workgroup per compute unit.  Every range adds its
+      // partial sums into C with atomics (and an overwrite needs C zeroed first),
+      // so short problems (few rows of C per byte of operand) may split further
+      // than tall ones.
       const int64_t tiles = tile_count(p, plan.shape);
       const int64_t nkt = (p.k + 63) / 64;
       plan.splits = 1;
       if (tiles < kComputeUnits / 2) {
-        const int64_t want = (2 * kComputeUnits + tiles - 1) / tiles;
-        const int64_t most = nkt / 4 > 1 ? nkt / 4 : 1;
+        const int64_t want = kComputeUnits / tiles;
+        const int64_t most = nkt / 8 > 1 ? nkt / 8 : 1;
         const int64_t short_side = p.m < p.n ? p.m : p.n;
         const int64_t atomics_ok = short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4);
         int64_t sp = want < most ? want : most;

@@ -95,11 +95,13 @@ def test_variant_choice(M):
     # a row-major B with n not a multiple of 16 cannot
     assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
     # short in one dimension: a tile that is short there too
-    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64x256"
-    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0, aligned16=False) == "mfma_tile64x256"
-    assert name(4095, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"
+    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64"
+    assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0) == "mfma_dma64x256"
+    assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0, aligned16=False) == "mfma_tile64x256"
+    assert name(4095, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile64"
+    assert name(100000, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"
     # column-major C swaps the operand roles
-    assert name(16, 4096, 4096, 4096, 0, 4096, 0, 16, 1) == "mfma_dma256x64"
+    assert name(64, 100352, 576, 576, 0, 100352, 0, 64, 1) == "mfma_dma256x64"
     # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
     assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
     # k not a multiple of 64 does not
