@@ -107,7 +107,10 @@ Plan choose_plan(const Problem &p) {
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
     if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
-    else plan = {dma_eligible(p, sh) ? KIND_DMA : KIND_STAGED, sh, 1};
+    else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
+    // the register-staged kernel keeps its operands in flight in VGPRs, which a
+    // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128
+    else plan = {KIND_STAGED, sh == SHAPE_256 ? SHAPE_128 : sh, 1};
   }
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
     plan.splits = forced_splits();

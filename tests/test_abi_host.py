@@ -88,12 +88,12 @@ def test_variant_choice(M):
     assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
     assert name(4096, 4096, 1024, 1024, 0, 4096, 0, 4096, 0) == "mfma_dma256"
     # unaligned operands cannot use the direct-to-LDS kernels
-    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile256"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128"
     # a ragged row edge can, but not with the deep-k kernel; an unsigned operand can
     assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256"
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256_k128"
     # a row-major B with n not a multiple of 16 cannot
-    assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile256"
+    assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile128"
     # short in one dimension: a tile that is short there too
     assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64"
     assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0) == "mfma_dma64x256"
