@@ -127,15 +127,24 @@ def copy_calibration():
     print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
 
 
-def time_case(M, case, steps, warmup):
-    """Average milliseconds per call, operands resident, events on the launch stream."""
+def time_case(M, case, steps, warmup, dequant=False):
+    """Average milliseconds per call, operands resident, events on the launch stream.
+
+    dequant: time the float-output entry point (scale fused into the write-back) instead."""
     import torch
     ops = W.materialize(case)
-    fn = getattr(M, "mipgemm_" + case.entry)
     dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
     dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
-    dC = torch.from_numpy(ops.C).cuda()
     stream = torch.cuda.current_stream()
+    if dequant:
+        dC = torch.zeros(ops.C.size, dtype=torch.float32, device="cuda")
+        entry = getattr(M, "mipgemm_" + case.entry.replace("s32", "f32"))
+
+        def fn(*a, **kw):
+            return entry(*a, scale=0.00731, **kw)
+    else:
+        dC = torch.from_numpy(ops.C).cuda()
+        fn = getattr(M, "mipgemm_" + case.entry)
     for _ in range(warmup):
         fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
            dC, case.ldc, case.orderC, case.mode, stream=stream)
@@ -172,6 +181,19 @@ def run_suite(M, args):
             case.name, case.entry, case.m, case.n, case.k, variant, ms * 1e3,
             case.ops / ms / 1e9, case.algorithmic_bytes / ms / 1e6,
             "mfma" if t_mfma >= t_hbm else "hbm", max(t_mfma, t_hbm) / (ms * 1e-3)), flush=True)
+    print()
+    print("Float output with the dequantising scale fused into the write-back (f32 entry points;")
+    print("no split k there, float sums are not combined out of order):")
+    print()
+    print("| case | entry | us (s32) | us (f32) |")
+    print("|---|---|---|---|")
+    for name in ("c2_8192_rand", "c2_4096_rand", "c3_b32_64x100352x576", "c3_b32_256x6272x2304",
+                 "c4_enc_1024x3072x768", "c4_dec_16x4096x4096"):
+        case = next(c for c in W.all_cases() if c.name == name)
+        a = time_case(M, case, args.steps, args.warmup)
+        b = time_case(M, case, args.steps, args.warmup, dequant=True)
+        print("| %s | %s | %.1f | %.1f |" % (name, case.entry.replace("s32", "f32"), a * 1e3, b * 1e3),
+              flush=True)
 
 
 def main():

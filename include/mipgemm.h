@@ -106,6 +106,44 @@ int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k,
                     void *stream);
 
 /*
+ * Dequantised output, the step the paper's quantization scheme puts right after
+ * the integer GEMM (Section 7.3: C^r = s_A s_B A^q B^q = s_A s_B C^q): the same
+ * three GEMMs, but C holds floats and receives
+ *     overwrite:   C(i,j) = float(S(i,j)) * scale
+ *     accumulate:  C(i,j) = fma(float(S(i,j)), scale, C(i,j))
+ * where S(i,j) is the int32 sum of the s32 entry points (wrapping modulo 2^32),
+ * float() rounds to nearest even, and `scale` is the product s_A * s_B formed
+ * by the caller.  Each element is rounded at most twice: within 2^-23 relative
+ * of the exact s_A s_B C^q.  The result does not depend on tile sizes: the sum
+ * is completed in integers before anything is converted.  Same arguments, same
+ * numbering and same rules as the s32 entry points; `scale` is argument 17 and
+ * must be finite.
+ */
+int mipgemm_s8s8f32(int64_t m, int64_t n, int64_t k,
+                    const int8_t *A, int64_t lda, int orderA,
+                    const int8_t *B, int64_t ldb, int orderB,
+                    float *C, int64_t ldc, int orderC,
+                    int mode,
+                    void *workspace, size_t workspace_bytes,
+                    void *stream, float scale);
+
+int mipgemm_u8s8f32(int64_t m, int64_t n, int64_t k,
+                    const uint8_t *A, int64_t lda, int orderA,
+                    const int8_t *B, int64_t ldb, int orderB,
+                    float *C, int64_t ldc, int orderC,
+                    int mode,
+                    void *workspace, size_t workspace_bytes,
+                    void *stream, float scale);
+
+int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k,
+                    const int8_t *A, int64_t lda, int orderA,
+                    const uint8_t *B, int64_t ldb, int orderB,
+                    float *C, int64_t ldc, int orderC,
+                    int mode,
+                    void *workspace, size_t workspace_bytes,
+                    void *stream, float scale);
+
+/*
  * Bytes of device workspace a call with these sizes and orders may use.
  * Returns 0 when none is needed (and for invalid sizes).
  */

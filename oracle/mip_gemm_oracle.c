@@ -42,7 +42,10 @@
  * identity / permutation matrices, row and column sums, linearity and k-split,
  * layout identities, the u8 <-> s8 identity, numpy int64 matmul, the
  * instruction-tile definitions the paper prints (sdot, vmadot, AMX tile) and a
- * hand-worked example stored under tests/golden/.
+ * hand-worked example stored under tests/golden/.  The dequantised variant at
+ * the end of the file is pinned by the same hand-worked example with exact
+ * scales, by scale = 1 against the integer function, by closed forms and by
+ * linearity in the scale.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -99,6 +102,55 @@ int oracle_mip_gemm(int a_unsigned, int b_unsigned,
                 uint32_t b = widen(B, at(p, j, ldb, orderB), b_unsigned);
                 Cu[at(i, j, ldc, orderC)] += a * b;
             }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Dequantised result, fp64: the step the paper's quantization scheme applies to
+ * the integer product (Section 7.3: C^r = s_A s_B A^q B^q = s_A s_B C^q).
+ *
+ *     out(i,j) = scale * S(i,j)                 (overwrite)
+ *     out(i,j) = C0(i,j) + scale * S(i,j)       (accumulate)
+ *
+ * S is the int32 sum defined at the top of this file (same wraparound reading),
+ * `scale` the product s_A * s_B handed over as a float, C0 the float matrix the
+ * caller wants updated (read through ldc / orderC, may be NULL for overwrite).
+ * The arithmetic after the integer sum is done in double: every int32 and every
+ * float is exact in double, so scale * S is exact and the one addition is
+ * rounded once, far below the float result it is compared with.
+ * `out` is a dense row-major m x n array of doubles.
+ */
+int oracle_mip_gemm_dequant(int a_unsigned, int b_unsigned,
+                            int64_t m, int64_t n, int64_t k,
+                            const void *A, int64_t lda, int orderA,
+                            const void *B, int64_t ldb, int orderB,
+                            float scale,
+                            const float *C0, int64_t ldc, int orderC,
+                            int mode, double *out)
+{
+    if (m < 0 || n < 0 || k < 0) return -1;
+    if (orderA != ORACLE_ROW_MAJOR && orderA != ORACLE_COL_MAJOR) return -1;
+    if (orderB != ORACLE_ROW_MAJOR && orderB != ORACLE_COL_MAJOR) return -1;
+    if (orderC != ORACLE_ROW_MAJOR && orderC != ORACLE_COL_MAJOR) return -1;
+    if (mode != ORACLE_OVERWRITE && mode != ORACLE_ACCUMULATE) return -1;
+    if (lda < (orderA == ORACLE_ROW_MAJOR ? k : m)) return -1;
+    if (ldb < (orderB == ORACLE_ROW_MAJOR ? n : k)) return -1;
+    if (ldc < (orderC == ORACLE_ROW_MAJOR ? n : m)) return -1;
+    if (mode == ORACLE_ACCUMULATE && !C0 && m > 0 && n > 0) return -1;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t j = 0; j < n; ++j) {
+            uint32_t s = 0u;
+            for (int64_t p = 0; p < k; ++p)
+                s += widen(A, at(i, p, lda, orderA), a_unsigned)
+                   * widen(B, at(p, j, ldb, orderB), b_unsigned);
+            double r = (double)scale * (double)(int32_t)s;
+            if (mode == ORACLE_ACCUMULATE)
+                r += (double)C0[at(i, j, ldc, orderC)];
+            out[(size_t)i * (size_t)n + (size_t)j] = r;
         }
     }
     return 0;

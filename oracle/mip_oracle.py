@@ -51,6 +51,9 @@ def _load():
             lib.oracle_mip_gemm.argtypes = [ci, ci, i64, i64, i64,
                                             vp, i64, ci, vp, i64, ci,
                                             vp, i64, ci, ci]
+            lib.oracle_mip_gemm_dequant.restype = ci
+            lib.oracle_mip_gemm_dequant.argtypes = [ci, ci, i64, i64, i64, vp, i64, ci, vp, i64, ci,
+                                                    ctypes.c_float, vp, i64, ci, ci, vp]
             lib.oracle_num_threads.restype = ci
             _lib = lib
     return _lib
@@ -107,3 +110,34 @@ def gemm_u8s8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode):
 
 def gemm_s8u8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode):
     return gemm(False, True, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode)
+
+
+def gemm_dequant(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB, scale,
+                 C0, ldc, orderC, mode):
+    """scale * (A * B) [+ C0] in fp64 (paper Section 7.3, C^r = s_A s_B C^q), dense (m, n) array.
+
+    ``scale`` is rounded to float32 first, as the GPU entry points take a float.
+    ``C0`` is the flat float32 buffer to be updated (only read, only in accumulate mode).
+    """
+    A = np.asarray(A)
+    B = np.asarray(B)
+    want_a = np.uint8 if a_unsigned else np.int8
+    want_b = np.uint8 if b_unsigned else np.int8
+    if A.dtype != want_a or B.dtype != want_b:
+        raise TypeError("operand dtypes do not match the entry point")
+    if A.size < _min_len(m, k, lda, orderA) or B.size < _min_len(k, n, ldb, orderB):
+        raise ValueError("buffer shorter than the matrix it is said to hold")
+    c_ptr = None
+    if C0 is not None:
+        C0 = np.asarray(C0)
+        if C0.dtype != np.float32 or C0.size < _min_len(m, n, ldc, orderC):
+            raise ValueError("C0 must be a float32 buffer that holds the m x n matrix")
+        c_ptr = C0.ctypes.data
+    out = np.empty((m, n), dtype=np.float64)
+    rc = _load().oracle_mip_gemm_dequant(
+        int(bool(a_unsigned)), int(bool(b_unsigned)), m, n, k, A.ctypes.data, lda, orderA,
+        B.ctypes.data, ldb, orderB, float(np.float32(scale)), c_ptr, ldc, orderC, mode,
+        out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return out

@@ -42,6 +42,7 @@ def library_path() -> str:
 def exported_symbols():
     """Names include/mipgemm.h declares; the library must export every one."""
     return ["mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32",
+            "mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32",
             "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
             "mipgemm_mfma_ceiling"]
 
@@ -59,6 +60,10 @@ def load_library() -> ctypes.CDLL:
                 fn = getattr(lib, name)
                 fn.restype = ctypes.c_int
                 fn.argtypes = _GEMM_ARGTYPES
+            for name in ("mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32"):
+                fn = getattr(lib, name)
+                fn.restype = ctypes.c_int
+                fn.argtypes = _GEMM_ARGTYPES + [ctypes.c_float]
             lib.mipgemm_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_workspace_size.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
             lib.mipgemm_strerror.restype = ctypes.c_char_p
@@ -92,10 +97,10 @@ def _stream(stream):
 
 
 def _call(name, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
-          workspace, workspace_bytes, stream, check):
+          workspace, workspace_bytes, stream, check, *extra):
     rc = getattr(load_library(), name)(
         m, n, k, _ptr(A), lda, orderA, _ptr(B), ldb, orderB, _ptr(C), ldc, orderC, mode,
-        _ptr(workspace), workspace_bytes, _stream(stream))
+        _ptr(workspace), workspace_bytes, _stream(stream), *extra)
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc
@@ -120,6 +125,27 @@ def mipgemm_s8u8s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mod
     """Same with an unsigned B."""
     return _call("mipgemm_s8u8s32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
                  mode, workspace, workspace_bytes, stream, check)
+
+
+def mipgemm_s8s8f32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """C (float) = [C +] scale * (A * B): the integer GEMM with the dequantising scale fused in."""
+    return _call("mipgemm_s8s8f32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
+
+
+def mipgemm_u8s8f32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """Same with an unsigned A."""
+    return _call("mipgemm_u8s8f32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
+
+
+def mipgemm_s8u8f32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                    workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """Same with an unsigned B."""
+    return _call("mipgemm_s8u8f32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
 
 
 def mipgemm_workspace_size(m, n, k, orderA, orderB, orderC) -> int:

@@ -34,6 +34,8 @@ struct DmaTileParams {
   int kt_per_split;       // k blocks per workgroup (blockIdx.y picks the range)
   int accumulate;         // C += instead of C =
   int atomic;             // several workgroups add into the same tile (split k)
+  int out_float;          // dequantised output: float(sum) * scale
+  float scale;
 };
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
@@ -220,13 +222,14 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   if (mw < P.m && nw < P.n) {
     int32_t *C = P.C + mw * P.ldc + nw;
     const bool full = m0 + BM <= P.m && n0 + BN <= P.n;
+    const Finish fin = {P.scale, P.out_float};
     if (P.atomic)
       add_blocks_atomic<FM, FN>(acc, C, P.ldc, P.m - mw, P.n - nw, lane,
                                 reinterpret_cast<int32_t *>(smem + wave * ATOMIC_PATCH_BYTES));
     else if (full)
       store_blocks_via_lds<FM, FN>(acc, C, P.ldc, P.accumulate, lane,
-                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
-    else store_blocks<FM, FN, false>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate, lane);
+                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES), fin);
+    else store_blocks<FM, FN, false>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate, lane, fin);
   }
 }
 
@@ -267,6 +270,9 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   P.kt_per_split = (P.nkt + splits - 1) / splits;
   splits = (P.nkt + P.kt_per_split - 1) / P.kt_per_split;  // no empty ranges
   P.accumulate = p.accumulate;
+  P.out_float = p.out_float;
+  P.scale = p.scale;
+  if (p.out_float) splits = 1;  // float sums must not be combined in arbitrary order
   P.atomic = splits > 1;
   if (P.atomic && !p.accumulate) {
     hipError_t e = launch_fill_zero(p, s);  // partial sums are added into C: start from zero

@@ -13,6 +13,23 @@
 namespace mip {
 
 struct __attribute__((packed, aligned(4))) c_quad { v4i v; };
+
+// What becomes of an accumulator on its way to C.  Integer output: the sum
+// itself, plus the old C when accumulating (wraps modulo 2^32).  Dequantised
+// output (paper Section 7.3, C^r = s_A s_B C^q): the int32 sum converted to
+// float (round to nearest even) times `scale`; when accumulating, one fused
+// multiply-add onto the old float.  Both views of C are 4-byte words, so the
+// stores below move bit patterns.
+struct Finish {
+  float scale;
+  int to_float;
+  __device__ __forceinline__ int operator()(int acc, int old, bool accumulate) const {
+    if (!to_float) return accumulate ? (int)((uint32_t)acc + (uint32_t)old) : acc;
+    const float s = (float)acc;
+    const float r = accumulate ? __fmaf_rn(s, scale, __int_as_float(old)) : __fmul_rn(s, scale);
+    return __float_as_int(r);
+  }
+};
 typedef v4i v4i_dword_aligned __attribute__((aligned(4)));  // four int32 of C: only dword alignment is known
 
 // Unsigned-operand correction (exact modulo 2^32).  sumB[j]: this lane's partial
@@ -52,7 +69,7 @@ __device__ __forceinline__ void unsigned_correction(v16i (&acc)[FM][FN], const i
 template <int FM, int FN, bool FULL>
 __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t *C, int64_t ldc,
                                              int64_t rows, int64_t cols, bool accumulate,
-                                             int lane) {
+                                             int lane, const Finish fin) {
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     const int row = i * 32 + (lane & 31);
@@ -67,20 +84,16 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
                    acc[i][j][4 * q + 3]};
         if (FULL || col + 4 * (lane >> 5) + 3 < cols) {
           c_quad *dst = reinterpret_cast<c_quad *>(crow + col);
-          if (accumulate) {
-            v4i old = dst->v;
+          v4i old = {0, 0, 0, 0};
+          if (accumulate) old = dst->v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) val[e] = (int)((uint32_t)val[e] + (uint32_t)old[e]);
-          }
+          for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[e], accumulate);
           dst->v = val;
         } else {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            if (col + 4 * (lane >> 5) + e < cols) {
-              uint32_t x = (uint32_t)val[e];
-              if (accumulate) x += (uint32_t)crow[col + e];
-              crow[col + e] = (int32_t)x;
-            }
+            if (col + 4 * (lane >> 5) + e < cols)
+              crow[col + e] = fin(val[e], accumulate ? crow[col + e] : 0, accumulate);
           }
         }
       }
@@ -104,7 +117,7 @@ constexpr int STORE_PATCH_BYTES = STORE_PATCH_WORDS * 4;
 template <int FM, int FN>
 __device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], int32_t *C,
                                                      int64_t ldc, bool accumulate, int lane,
-                                                     int32_t *patch) {
+                                                     int32_t *patch, const Finish fin) {
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -122,11 +135,10 @@ __device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], 
         v4i val = *reinterpret_cast<const v4i *>(patch + r * 36 + c);
         v4i_dword_aligned *dst =
             reinterpret_cast<v4i_dword_aligned *>(C + (int64_t)(i * 32 + r) * ldc + j * 32 + c);
-        if (accumulate) {
-          v4i old = __builtin_nontemporal_load(dst);
+        v4i old = {0, 0, 0, 0};
+        if (accumulate) old = __builtin_nontemporal_load(dst);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) val[e] = (int)((uint32_t)val[e] + (uint32_t)old[e]);
-        }
+        for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[e], accumulate);
         __builtin_nontemporal_store(val, dst);
       }
     }

@@ -21,6 +21,8 @@ struct DmaParams {
   int tiles_m, tiles_n;
   int nkt;                // k / 128
   int accumulate;         // C += instead of C =
+  int out_float;          // dequantised output: float(sum) * scale
+  float scale;
 };
 
 // ---------------------------------------------------------------------------
@@ -169,7 +171,8 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
   store_blocks_via_lds<4, 4>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc,
                              P.accumulate != 0, lane,
-                             reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
+                             reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES),
+                             Finish{P.scale, P.out_float});
 }
 
 }  // namespace
@@ -197,6 +200,8 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
   P.tiles_n = (int)(p.n / DN);
   P.nkt = (int)(p.k / KD2);
   P.accumulate = p.accumulate;
+  P.out_float = p.out_float;
+  P.scale = p.scale;
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
   const size_t lds = (size_t)2 * STAGE2_BYTES;

@@ -28,7 +28,13 @@ __global__ __launch_bounds__(256) void simple_kernel(Problem p) {
     acc += av * bv;
   }
   uint32_t *c = reinterpret_cast<uint32_t *>(p.C) + i * p.ldc + j;
-  *c = p.accumulate ? *c + acc : acc;
+  if (!p.out_float) {
+    *c = p.accumulate ? *c + acc : acc;
+  } else {  // dequantised output (paper Section 7.3): float(sum) * scale
+    const float s = (float)(int32_t)acc;
+    const float r = p.accumulate ? __fmaf_rn(s, p.scale, __uint_as_float(*c)) : __fmul_rn(s, p.scale);
+    *c = __float_as_uint(r);
+  }
 }
 
 // 64 columns x 4 rows per block; the caller keeps rows <= 65535 * 4

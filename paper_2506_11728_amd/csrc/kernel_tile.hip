@@ -162,6 +162,7 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < p.m && nw < p.n) {
     int32_t *C = p.C + mw * p.ldc + nw;
+    const Finish fin = {p.scale, p.out_float};
     if (tp.atomic) {
       // the k loop ended on a workgroup barrier: no wave still reads the stages
       add_blocks_atomic<FM, FN>(acc, C, p.ldc, p.m - mw, p.n - nw, lane,
@@ -169,8 +170,8 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
     }
     else if (!edge_tile)
       store_blocks_via_lds<FM, FN>(acc, C, p.ldc, p.accumulate, lane,
-                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES));
-    else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane);
+                                   reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES), fin);
+    else store_blocks<FM, FN, false>(acc, C, p.ldc, p.m - mw, p.n - nw, p.accumulate, lane, fin);
   }
 }
 
@@ -183,7 +184,7 @@ static hipError_t launch_cfg(const Problem &p, int splits, hipStream_t s) {
   tp.tiles_m = (int)tiles_m;
   tp.tiles_n = (int)tiles_n;
   const int64_t nkt = (p.k + BK - 1) / BK;
-  if (splits < 1) splits = 1;
+  if (splits < 1 || p.out_float) splits = 1;  // float sums must not be combined in arbitrary order
   if (splits > nkt) splits = (int)nkt;
   if (splits > 65535) splits = 65535;
   tp.kt_per_split = (int)((nkt + splits - 1) / splits);

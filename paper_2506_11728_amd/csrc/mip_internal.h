@@ -20,6 +20,9 @@ struct Problem {
   int64_t ldc;
   int a_unsigned, b_unsigned;
   int accumulate;
+  // dequantised output (paper Section 7.3): C holds floats, float(sum) * scale
+  int out_float;
+  float scale;
 };
 
 // Workgroup tile of the MFMA kernels (rows x columns of C).

@@ -113,7 +113,7 @@ Plan choose_plan(const Problem &p) {
     else plan = {KIND_STAGED, sh == SHAPE_256 ? SHAPE_128 : sh, 1};
   }
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
-    plan.splits = forced_splits();
+    plan.splits = p.out_float ? 1 : forced_splits();  // float sums are not combined out of order
     if (plan.splits == 0) {
       // Too few tiles to fill the chip: cut k into ranges of at least 512 until
       // there is about one workgroup per compute unit.  Every range adds its
@@ -123,7 +123,7 @@ Plan choose_plan(const Problem &p) {
       const int64_t tiles = tile_count(p, plan.shape);
       const int64_t nkt = (p.k + 63) / 64;
       plan.splits = 1;
-      if (tiles < kComputeUnits / 2) {
+      if (tiles < kComputeUnits / 2 && !p.out_float) {
         const int64_t want = kComputeUnits / tiles;
         const int64_t most = nkt / 8 > 1 ? nkt / 8 : 1;
         const int64_t short_side = p.m < p.n ? p.m : p.n;
@@ -148,7 +148,7 @@ bool order_ok(int o) { return o == MIPGEMM_ROW_MAJOR || o == MIPGEMM_COL_MAJOR; 
 // Fills `out` and returns 0, or returns the negative argument number.
 int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k,
                            const void *A, int64_t lda, int orderA, const void *B, int64_t ldb,
-                           int orderB, int32_t *C, int64_t ldc, int orderC, int mode,
+                           int orderB, void *C, int64_t ldc, int orderC, int mode,
                            void *workspace, size_t workspace_bytes, Problem *out) {
   if (m < 0 || m > MIPGEMM_MAX_DIM) return -1;
   if (n < 0 || n > MIPGEMM_MAX_DIM) return -2;
@@ -192,20 +192,26 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
     p.B = A; p.b_sk = a_sk; p.b_sn = a_sm; p.b_unsigned = a_unsigned;
   }
   p.k = k;
-  p.C = C;
+  p.C = static_cast<int32_t *>(C);
   p.ldc = ldc;
   p.accumulate = mode == MIPGEMM_ACCUMULATE;
+  p.out_float = 0;
+  p.scale = 1.0f;
   *out = p;
   return 0;
 }
 
-int run(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const void *A,
-        int64_t lda, int orderA, const void *B, int64_t ldb, int orderB, int32_t *C, int64_t ldc,
-        int orderC, int mode, void *workspace, size_t workspace_bytes, void *stream) {
+// out_float: C holds floats and receives float(sum) * scale (the f32 entry points)
+int run(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
+        int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb, int orderB,
+        void *C, int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
+        void *stream) {
   Problem p;
   int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB,
                                   C, ldc, orderC, mode, workspace, workspace_bytes, &p);
   if (rc != 0) return rc;
+  p.out_float = out_float;
+  p.scale = scale;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   const mip::Plan plan = mip::choose_plan(p);
@@ -227,22 +233,60 @@ extern "C" {
 int mipgemm_s8s8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
                     const int8_t *B, int64_t ldb, int orderB, int32_t *C, int64_t ldc, int orderC,
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
-  return run(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+  return run(0, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
 }
 
 int mipgemm_u8s8s32(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda, int orderA,
                     const int8_t *B, int64_t ldb, int orderB, int32_t *C, int64_t ldc, int orderC,
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
-  return run(1, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+  return run(1, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
 }
 
 int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
                     const uint8_t *B, int64_t ldb, int orderB, int32_t *C, int64_t ldc, int orderC,
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
-  return run(0, 1, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+  return run(0, 1, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
+}
+
+// Dequantised output (paper Section 7.3).  Same arguments and numbering as the
+// s32 entry points; scale is argument 17.
+static int run_f32(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const void *A,
+                   int64_t lda, int orderA, const void *B, int64_t ldb, int orderB, float *C,
+                   int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
+                   void *stream, float scale) {
+  if (!(scale == scale) || scale - scale != 0.0f) {  // NaN or infinity
+    // still report an earlier invalid argument first
+    Problem p;
+    int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb,
+                                    orderB, C, ldc, orderC, mode, workspace, workspace_bytes, &p);
+    return rc != 0 ? rc : -17;
+  }
+  return run(a_unsigned, b_unsigned, 1, scale, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc,
+             orderC, mode, workspace, workspace_bytes, stream);
+}
+
+int mipgemm_s8s8f32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
+                    const int8_t *B, int64_t ldb, int orderB, float *C, int64_t ldc, int orderC,
+                    int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_f32(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                 workspace_bytes, stream, scale);
+}
+
+int mipgemm_u8s8f32(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda, int orderA,
+                    const int8_t *B, int64_t ldb, int orderB, float *C, int64_t ldc, int orderC,
+                    int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_f32(1, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                 workspace_bytes, stream, scale);
+}
+
+int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
+                    const uint8_t *B, int64_t ldb, int orderB, float *C, int64_t ldc, int orderC,
+                    int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_f32(0, 1, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                 workspace_bytes, stream, scale);
 }
 
 size_t mipgemm_workspace_size(int64_t, int64_t, int64_t, int, int, int) {
@@ -261,8 +305,9 @@ const char *mipgemm_strerror(int code) {
       "invalid argument 10 (C is null)", "invalid argument 11 (ldc too small)",
       "invalid argument 12 (orderC)", "invalid argument 13 (mode)",
       "invalid argument 14 (workspace is null)",
-      "invalid argument 15 (workspace_bytes too small)", "invalid argument 16 (stream)"};
-  if (code <= 0 && code >= -16) return args[-code];
+      "invalid argument 15 (workspace_bytes too small)", "invalid argument 16 (stream)",
+      "invalid argument 17 (scale is not finite)"};
+  if (code <= 0 && code >= -17) return args[-code];
   if (code > 0) return hipGetErrorString(static_cast<hipError_t>(code));
   return "unknown mipgemm error code";
 }

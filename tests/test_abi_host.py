@@ -63,6 +63,26 @@ def test_argument_validation_codes(M, entry):
     assert call(M, entry, lda=0, k=0) == -5          # leading dimensions are at least 1
 
 
+@pytest.mark.parametrize("entry", ["mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32"])
+def test_dequant_entry_points_share_the_numbering(M, entry):
+    def callf(scale=0.5, **kw):
+        args = dict(m=4, n=5, k=6, A=4096, lda=6, oa=0, B=4096, ldb=5, ob=0, C=4096, ldc=5, oc=0,
+                    mode=0)
+        args.update(kw)
+        return getattr(M, entry)(args["m"], args["n"], args["k"], args["A"], args["lda"],
+                                 args["oa"], args["B"], args["ldb"], args["ob"], args["C"],
+                                 args["ldc"], args["oc"], args["mode"], None, 0, 0, scale=scale,
+                                 check=False)
+    assert callf(m=-1) == -1
+    assert callf(lda=5) == -5
+    assert callf(C=0) == -10
+    assert callf(ldc=4) == -11
+    assert callf(mode=3) == -13
+    assert callf(scale=float("inf"), m=0) == -17
+    assert callf(scale=float("nan"), lda=5) == -5
+    assert "17" in M.mipgemm_strerror(-17)
+
+
 def test_first_bad_argument_wins(M):
     assert call(M, m=-1, n=-1, mode=9) == -1
     assert call(M, lda=1, ldb=1, ldc=1) == -5
@@ -76,7 +96,7 @@ def test_empty_problems_need_no_pointers(M):
 
 def test_strerror_and_workspace(M):
     assert M.mipgemm_strerror(0) == "success"
-    for code in range(-16, 0):
+    for code in range(-17, 0):
         assert str(-code) in M.mipgemm_strerror(code)
     assert "unknown" in M.mipgemm_strerror(-99)
     assert M.mipgemm_workspace_size(8192, 8192, 8192, 0, 0, 0) == 0

@@ -1,0 +1,127 @@
+"""GPU parity of the dequantised-output entry points (paper Section 7.3, C^r = s_A s_B C^q).
+
+Floating point: compared with the fp64 oracle within the bound the arithmetic gives.  The
+kernels convert the exact int32 sum to float (one rounding, relative 2^-24) and multiply by
+the scale, or fuse multiply and add onto the old float (one more rounding, relative 2^-24 of
+the result), so |got - want| <= 2^-23 * (|want| + |C0|).  Overwrite results are also compared
+bit for bit with the same two float operations done by numpy.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2506_11728_amd as M
+    M.load_library()
+    return M
+
+
+def _cases():
+    out = []
+    idx = 0
+    shapes = [(256, 256, 256), (300, 200, 333), (64, 3136, 576), (1024, 768, 768), (16, 4096, 1024),
+              (512, 768, 2048), (1000, 999, 1001), (7, 7, 3), (2048, 1568, 512), (768, 512, 384)]
+    for (m, n, k) in shapes:
+        for uns in (0, 1, 2):
+            mode = (idx // 2) % 2
+            oa, ob, oc = idx % 2, (idx // 3) % 2, (idx // 5) % 2
+            pad = 0 if (m, n, k) not in ((1000, 999, 1001), (7, 7, 3), (300, 200, 333)) else 17
+            out.append((W.Case(
+                "deq_%dx%dx%d_u%d_m%d_%d%d%d" % (m, n, k, uns, mode, oa, ob, oc), 8, idx, m, n, k,
+                a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob, orderC=oc, pad=pad,
+                mode=mode,
+                a_dist=("uniform", 0, 255) if uns == 1 else ("normal", 24.0),
+                b_dist=("uniform", 0, 255) if uns == 2 else ("normal", 32.0),
+                c_dist=("uniform", -1000, 1000), seed=13), [0.0123, 2.0 ** -8, -3.3e-5][idx % 3]))
+            idx += 1
+    return out
+
+
+VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128"]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("case,scale", _cases(), ids=lambda x: x.name if hasattr(x, "name") else None)
+def test_dequant_against_oracle(gpu, oracle, case, scale, variant):
+    import torch
+    print("case", case.name, "scale", scale, "variant", variant, flush=True)
+    ops = W.materialize(case)
+    rng = np.random.default_rng(case.index)
+    C0 = (rng.standard_normal(ops.C.size) * 50).astype(np.float32)   # floats where the ints were
+    pad_mask = W.padding_mask(case.m, case.n, case.orderC, case.ldc)
+    want = oracle.gemm_dequant(case.a_unsigned, case.b_unsigned, case.m, case.n, case.k,
+                               ops.A, case.lda, case.orderA, ops.B, case.ldb, case.orderB,
+                               scale, C0, case.ldc, case.orderC, case.mode)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(C0.copy()).cuda()
+    fn = getattr(gpu, "mipgemm_" + case.entry.replace("s32", "f32"))
+    old = os.environ.pop("MIPGEMM_VARIANT", None)
+    if variant != "auto":
+        os.environ["MIPGEMM_VARIANT"] = variant
+    try:
+        fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+           dC, case.ldc, case.orderC, case.mode, scale=scale)
+    finally:
+        os.environ.pop("MIPGEMM_VARIANT", None)
+        if old is not None:
+            os.environ["MIPGEMM_VARIANT"] = old
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy()
+    assert np.array_equal(raw[pad_mask], C0[pad_mask])               # padding untouched
+    got = W.extract(raw, case.m, case.n, case.orderC, case.ldc).astype(np.float64)
+    c0 = W.extract(C0, case.m, case.n, case.orderC, case.ldc).astype(np.float64)
+    bound = 2.0 ** -23 * (np.abs(want) + (np.abs(c0) if case.mode == W.ACCUMULATE else 0.0))
+    err = np.abs(got - want)
+    assert (err <= bound).all(), "max excess %g at %s" % (
+        (err - bound).max(), np.unravel_index(np.argmax(err - bound), err.shape))
+    if case.mode == W.OVERWRITE:
+        # the same two IEEE operations in numpy: float(S) then one float multiply
+        S = np.rint(want / float(np.float32(scale)))                  # exact: want = scale * S
+        emul = S.astype(np.float32) * np.float32(scale)
+        assert np.array_equal(got.astype(np.float32), emul)
+
+
+def test_dequant_scale_one_equals_integer_result(gpu):
+    import torch
+    case = W.config1()[0]
+    ops = W.materialize(case)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dCi = torch.zeros(case.m * case.n, dtype=torch.int32, device="cuda")
+    dCf = torch.zeros(case.m * case.n, dtype=torch.float32, device="cuda")
+    gpu.mipgemm_s8s8s32(case.m, case.n, case.k, dA, case.lda, 0, dB, case.ldb, 0, dCi, case.n, 0, 0)
+    gpu.mipgemm_s8s8f32(case.m, case.n, case.k, dA, case.lda, 0, dB, case.ldb, 0, dCf, case.n, 0, 0,
+                        scale=1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(dCf.cpu().numpy(), dCi.cpu().numpy().astype(np.float32))
+
+
+def test_dequant_rejects_bad_scale_and_empty_k(gpu):
+    import torch
+    dA = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    C0 = np.full(12, 7.5, dtype=np.float32)
+    dC = torch.from_numpy(C0).cuda()
+    R = W.ROW_MAJOR
+    for bad in (float("nan"), float("inf")):
+        assert gpu.mipgemm_s8s8f32(3, 3, 4, dA, 4, R, dA, 3, R, dC, 4, R, 0, scale=bad,
+                                   check=False) == -17
+    assert gpu.mipgemm_s8s8f32(3, 3, 4, dA, 3, R, dA, 3, R, dC, 4, R, 0, scale=float("nan"),
+                               check=False) == -5                     # earlier argument first
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), C0)
+    gpu.mipgemm_s8s8f32(3, 3, 0, dA, 1, R, dA, 3, R, dC, 4, R, 0, scale=0.5)   # empty sum: zeros
+    torch.cuda.synchronize()
+    want = C0.reshape(3, 4).copy()
+    want[:, :3] = 0.0
+    assert np.array_equal(dC.cpu().numpy().reshape(3, 4), want)

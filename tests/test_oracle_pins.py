@@ -455,3 +455,64 @@ def test_argument_checks(oracle):
         oracle.gemm_s8s8s32(2, 2, 3, A, 3, 2, B, 2, R, C, 2, R, OVW)      # bad order
     with pytest.raises(TypeError):
         oracle.gemm_u8s8s32(2, 2, 3, A, 3, R, B, 2, R, C, 2, R, OVW)      # wrong dtype
+
+
+# ---------------------------------------------------------------------------
+# dequantised variant (paper Section 7.3: C^r = s_A s_B C^q)
+# ---------------------------------------------------------------------------
+
+def run_dequant(oracle, A2d, B2d, scale, C0=None, mode=OVW, oa=R, ob=R, oc=R, pad=0):
+    m, k = A2d.shape
+    n = B2d.shape[1]
+    lda = (k if oa == R else m) + pad
+    ldb = (n if ob == R else k) + pad
+    ldc = (n if oc == R else m) + pad
+    A = W.embed(A2d, oa, lda, A2d.dtype.type(W.SENTINEL_BYTE))
+    B = W.embed(B2d, ob, ldb, B2d.dtype.type(W.SENTINEL_BYTE))
+    C = None if C0 is None else W.embed(C0.astype(np.float32), oc, ldc, np.float32(-77.0))
+    return oracle.gemm_dequant(A2d.dtype == np.uint8, B2d.dtype == np.uint8, m, n, k,
+                               A, lda, oa, B, ldb, ob, scale, C, ldc, oc, mode)
+
+
+def test_dequant_hand_worked_example(oracle):
+    g = _read_matrices(os.path.join(GOLDEN, "hand_worked_2x3x4.txt"))
+    A, B = g["A"].astype(np.int8), g["B"].astype(np.int8)
+    got = run_dequant(oracle, A, B, 0.125)
+    assert np.array_equal(got * 1000, g["DEQ_x1000"].astype(np.float64))
+    # scale 1: the integer result itself, also for the unsigned reading of A
+    assert np.array_equal(run_dequant(oracle, A, B, 1.0), g["AB"].astype(np.float64))
+    assert np.array_equal(run_dequant(oracle, A.view(np.uint8), B, 1.0), g["AuB"].astype(np.float64))
+    # accumulate: C0 + scale * S with exactly representable numbers
+    C0 = np.array([[1.5, -2.25, 0.0], [1024.0, -0.5, 3.0]], dtype=np.float32)
+    got = run_dequant(oracle, A, B, 0.5, C0, mode=ACC)
+    assert np.array_equal(got, C0.astype(np.float64) + 0.5 * g["AB"])
+
+
+@pytest.mark.parametrize("types", ["s8s8", "u8s8", "s8u8"])
+def test_dequant_matches_integer_oracle_times_scale(oracle, types):
+    rng = np.random.default_rng(31)
+    m, n, k = 17, 13, 200
+    ta = np.uint8 if types == "u8s8" else np.int8
+    tb = np.uint8 if types == "s8u8" else np.int8
+    A, B = rand(rng, (m, k), ta), rand(rng, (k, n), tb)
+    S, _, _ = run(oracle, A, B)                       # integer oracle, pinned above
+    for scale in (1.0, 2.0 ** -9, 0.1, 3.7e-4, -0.33):
+        s32 = float(np.float32(scale))                # the entry points take a float
+        got = run_dequant(oracle, A, B, scale, oa=CM, ob=CM, pad=3)
+        want = np.array([[s32 * int(S[i, j]) for j in range(n)] for i in range(m)])
+        assert np.array_equal(got, want)              # int32 * float is exact in double
+    C0 = rng.standard_normal((m, n)).astype(np.float32)
+    got = run_dequant(oracle, A, B, 0.25, C0, mode=ACC, oc=CM, pad=5)
+    assert np.array_equal(got, C0.astype(np.float64) + 0.25 * S)
+
+
+def test_dequant_closed_forms_and_wraparound(oracle):
+    k = 4608
+    A = np.full((3, k), 255, dtype=np.uint8)
+    B = np.full((k, 2), -128, dtype=np.int8)
+    got = run_dequant(oracle, A, B, 2.0 ** -10)
+    assert (got == -150405120 / 1024).all()           # 255 * (-128) * 4608, closed_forms.txt
+    # the scale applies to the wrapped int32 sum (reading of the paper's silence on overflow)
+    k = 131072
+    got = run_dequant(oracle, np.full((1, k), -128, np.int8), np.full((k, 1), -128, np.int8), 1.0)
+    assert got[0, 0] == -2.0 ** 31
