@@ -34,7 +34,8 @@ enum Kind {
   KIND_SIMPLE,    // one thread per C element, any layout
   KIND_STAGED,    // MFMA tiles, operands staged through registers: any alignment, any size
   KIND_DMA,       // MFMA tiles, operands streamed global -> LDS directly (aligned, k % 64 == 0)
-  KIND_DMA_K128   // 256 x 256 tiles, 128-deep k blocks: large aligned signed problems
+  KIND_DMA_K128,  // 256 x 256 tiles, 128-deep k blocks: large aligned problems
+  KIND_SLAB       // m <= 64: one workgroup per 16- or 32-column slab of B, all of k (splits = 1 or 2: slab width / 16)
 };
 
 struct Plan {
@@ -52,6 +53,9 @@ hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t 
 
 bool dma_k128_eligible(const Problem &p);
 hipError_t launch_dma_k128(const Problem &p, hipStream_t s);
+
+bool slab_eligible(const Problem &p, int nt);  // nt: slab width in blocks of 16 columns, 1 or 2
+hipError_t launch_slab(const Problem &p, int nt, hipStream_t s);
 
 #define MIP_DECLARE_DMA(BM, BN)                        \
   bool dma_eligible_##BM##x##BN(const Problem &p);     \

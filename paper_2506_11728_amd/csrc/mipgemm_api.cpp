@@ -47,11 +47,13 @@ const char *plan_name(const Plan &plan) {
     case KIND_STAGED: return staged[plan.shape];
     case KIND_DMA: return dma[plan.shape];
     case KIND_DMA_K128: return "mfma_dma256_k128";
+    case KIND_SLAB: return plan.splits == 2 ? "mfma_slab32" : "mfma_slab16";
     default: return "?";
   }
 }
 
 // MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
+// "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
 // 256, 128, 64, 64x256, 256x64.  A dma variant only applies to problems it is
 // eligible for; others fall back to the staged kernel of the same shape.
@@ -63,6 +65,12 @@ static bool forced_plan(const Problem &p, Plan *plan) {
   if (!std::strcmp(e, "dma256k128")) {
     if (!dma_k128_eligible(p)) return false;
     *plan = {KIND_DMA_K128, SHAPE_256, 1};
+    return true;
+  }
+  if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32")) {
+    const int nt = e[4] == '3' ? 2 : 1;
+    if (!slab_eligible(p, nt)) return false;
+    *plan = {KIND_SLAB, SHAPE_64, nt};
     return true;
   }
   const bool want_dma = !std::strncmp(e, "dma", 3);
@@ -106,7 +114,17 @@ Plan choose_plan(const Problem &p) {
     else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
-    if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    // A few rows of A against a k-contiguous B is one pass over B with nothing to
+    // share: a workgroup per 16-column slab does it in one launch, without atomics.
+    // (A row-major B would reach each slab in 16-byte pieces of its cache lines,
+    // which the tiled kernels, with their 64-byte pieces and split k, do better.)
+    // The same kernel serves short k, where the tiled kernels cannot split k
+    // and 64-column tiles leave most compute units idle.
+    const bool slab_ok = p.m <= 64 && slab_eligible(p, 1);
+    if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192) plan = {KIND_SLAB, SHAPE_64, 1};
+    else if (slab_ok && p.k < 1024 && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
+      plan = {KIND_SLAB, SHAPE_64, 1};
+    else if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
     // the register-staged kernel keeps its operands in flight in VGPRs, which a
     // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128
@@ -123,10 +141,13 @@ Plan choose_plan(const Problem &p) {
       const int64_t tiles = tile_count(p, plan.shape);
       const int64_t nkt = (p.k + 63) / 64;
       plan.splits = 1;
-      if (tiles < kComputeUnits / 2 && !p.out_float) {
-        const int64_t want = kComputeUnits / tiles;
+      // a stream over one long operand (short side of a few rows) is bound by memory
+      // latency: it wants two workgroups per compute unit in flight
+      const int64_t short_side = p.m < p.n ? p.m : p.n;
+      const int64_t target = short_side <= 16 ? 2 * kComputeUnits : kComputeUnits;
+      if (tiles < target / 2 && !p.out_float) {
+        const int64_t want = short_side <= 16 ? (target + tiles - 1) / tiles : target / tiles;
         const int64_t most = nkt / 8 > 1 ? nkt / 8 : 1;
-        const int64_t short_side = p.m < p.n ? p.m : p.n;
         const int64_t atomics_ok = short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4);
         int64_t sp = want < most ? want : most;
         if (sp > atomics_ok) sp = atomics_ok;
@@ -222,6 +243,7 @@ int run(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, i
     case mip::KIND_STAGED: e = mip::launch_staged(p, plan.shape, plan.splits, s); break;
     case mip::KIND_DMA: e = mip::launch_dma(p, plan.shape, plan.splits, s); break;
     case mip::KIND_DMA_K128: e = mip::launch_dma_k128(p, s); break;
+    case mip::KIND_SLAB: e = mip::launch_slab(p, plan.splits, s); break;
   }
   return static_cast<int>(e);
 }

@@ -117,6 +117,12 @@ def test_variant_choice(M):
     # short in one dimension: a tile that is short there too
     assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64"
     assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0) == "mfma_dma64x256"
+    # a few rows against a k-contiguous B, or a short k with few tiles: one workgroup per slab of B
+    assert name(16, 4096, 4096, 4096, 0, 4096, 1, 4096, 0) == "mfma_slab16"
+    assert name(1, 11008, 4096, 4096, 0, 4096, 1, 11008, 0) == "mfma_slab16"
+    assert name(64, 4096, 4096, 4096, 0, 4096, 1, 4096, 0) == "mfma_dma64"
+    assert name(64, 3136, 576, 576, 0, 3136, 0, 3136, 0, b_unsigned=True) == "mfma_slab16"
+    assert name(16, 4096, 4096, 4096, 0, 4096, 1, 4096, 0, aligned16=False) == "mfma_tile64"
     assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0, aligned16=False) == "mfma_tile64x256"
     assert name(4095, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile64"
     assert name(100000, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"

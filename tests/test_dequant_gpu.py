@@ -30,6 +30,7 @@ def _cases():
     out = []
     idx = 0
     shapes = [(256, 256, 256), (300, 200, 333), (64, 3136, 576), (1024, 768, 768), (16, 4096, 1024),
+              (40, 176, 640), (9, 64, 4096),
               (512, 768, 2048), (1000, 999, 1001), (7, 7, 3), (2048, 1568, 512), (768, 512, 384)]
     for (m, n, k) in shapes:
         for uns in (0, 1, 2):
@@ -47,7 +48,7 @@ def _cases():
     return out
 
 
-VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128"]
+VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128", "slab16", "slab32"]
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

@@ -316,3 +316,54 @@ def test_deep_k_kernel_unsigned_and_accumulate(gpu, oracle, case):
         assert name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB, case.ldc,
                     case.orderC, case.a_unsigned, case.b_unsigned, True) == "mfma_dma256_k128"
     check_case(gpu, oracle, case, "dma256k128")
+
+
+# ---------------------------------------------------------------------------
+# the skinny-m kernel: one workgroup per 16- or 32-column slab of B
+# ---------------------------------------------------------------------------
+
+def _slab_cases():
+    rng = np.random.default_rng(77)
+    shapes = [(1, 4096, 4096), (16, 4096, 4096), (64, 4096, 4096), (1, 11008, 4096),
+              (16, 4096, 11008), (64, 11008, 4096), (64, 3136, 576), (1, 16, 64), (64, 32, 64),
+              (3, 48, 128), (17, 80, 192), (33, 176, 1088), (48, 32, 2048), (5, 4112, 320)]
+    for _ in range(26):
+        shapes.append((int(rng.integers(1, 65)), 16 * int(rng.integers(1, 40)),
+                       64 * int(rng.integers(1, 24))))
+    out = []
+    for idx, (m, n, k) in enumerate(shapes):
+        uns = idx % 3
+        mode = (idx // 2) % 2
+        ob = (idx // 3) % 2
+        out.append(W.Case(
+            "slab_%dx%dx%d_u%d_m%d_b%d" % (m, n, k, uns, mode, ob), 8, idx, m, n, k,
+            a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=0, orderB=ob, orderC=0,
+            pad=16 * (idx % 4), mode=mode,
+            a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+            b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+            c_dist=("uniform", -1000, 1000), seed=21))
+    return out
+
+
+@pytest.mark.parametrize("variant", ["slab16", "slab32"])
+@pytest.mark.parametrize("case", _slab_cases(), ids=lambda c: c.name)
+def test_skinny_m_slab_kernel(gpu, oracle, case, variant):
+    width = 16 if variant == "slab16" else 32
+    if case.n % width == 0:
+        with VariantEnv(variant):
+            got = gpu.mipgemm_variant_name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
+                                           case.orderB, case.ldc, case.orderC, case.a_unsigned,
+                                           case.b_unsigned, True)
+        assert got == "mfma_" + variant
+    check_case(gpu, oracle, case, variant)
+
+
+def test_skinny_m_slab_kernel_wraps(gpu, oracle):
+    """All(-128) x all(-128) over k = 2^17: every sum is 2^31, which wraps to -2^31."""
+    m, n, k = 4, 32, 1 << 17
+    A = np.full(m * k, -128, dtype=np.int8)
+    B = np.full(k * n, -128, dtype=np.int8)
+    case = W.Case("slab_wrap", 8, 0, m, n, k)
+    for variant in ("slab16", "slab32"):
+        got = gpu_gemm(gpu, case, A, B, np.full(m * n, 7, dtype=np.int32), variant)
+        assert (got == -2 ** 31).all()

@@ -235,6 +235,12 @@ def config4() -> List[Case]:
         for m in DECODE_M:
             out.append(Case("c4_dec_%dx%dx%d" % (m, n, k), 4, idx, m, n, k,
                             a_dist=("normal", 24.0), b_dist=("normal", 24.0), seed=3)); idx += 1
+    # the same decode GEMMs with the weights stored n x k (k contiguous: column-major
+    # B), the layout a linear layer's weight usually has
+    for (n, k) in DECODE_NK:
+        for m in DECODE_M:
+            out.append(Case("c4_dec_%dx%dx%d_Bc" % (m, n, k), 4, idx, m, n, k, orderB=COL_MAJOR,
+                            a_dist=("normal", 24.0), b_dist=("normal", 24.0), seed=3)); idx += 1
     return out
 
 
