@@ -107,9 +107,17 @@ Plan choose_plan(const Problem &p) {
     // A short side (a few tokens, a few output channels) makes the problem a
     // stream over the long operand: wide tiles only when the long side alone
     // fills the chip, else 64 x 64 tiles, which give four times as many workgroups.
+    // With at most 16 rows the atomics of split k are cheap, and wide tiles (whole
+    // cache lines of a row-major operand) win as soon as k is long enough to cut
+    // into one range of 8 blocks or more per compute unit.
     Shape sh;
-    if (p.m <= 64 && p.n > 128) sh = tile_count(p, SHAPE_64X256) >= kComputeUnits ? SHAPE_64X256 : SHAPE_64;
-    else if (p.n <= 64 && p.m > 128) sh = tile_count(p, SHAPE_256X64) >= kComputeUnits ? SHAPE_256X64 : SHAPE_64;
+    const int64_t ranges = p.k / 512 > 1 ? p.k / 512 : 1;
+    auto enough = [&](Shape wide, int64_t short_side) {
+      const int64_t t = tile_count(p, wide);
+      return t >= kComputeUnits || (short_side <= 16 && !p.out_float && t * ranges >= kComputeUnits);
+    };
+    if (p.m <= 64 && p.n > 128) sh = enough(SHAPE_64X256, p.m) ? SHAPE_64X256 : SHAPE_64;
+    else if (p.n <= 64 && p.m > 128) sh = enough(SHAPE_256X64, p.n) ? SHAPE_256X64 : SHAPE_64;
     else if (tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
     else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
@@ -144,9 +152,12 @@ Plan choose_plan(const Problem &p) {
       // a stream over one long operand (short side of a few rows) is bound by memory
       // latency: it wants two workgroups per compute unit in flight
       const int64_t short_side = p.m < p.n ? p.m : p.n;
-      const int64_t target = short_side <= 16 ? 2 * kComputeUnits : kComputeUnits;
+      // (of the 64 x 64 tiles, that is: the wide ones fill a compute unit's LDS alone,
+      // and one workgroup too many would cost a second round)
+      const bool small_tile = plan.shape == SHAPE_64;
+      const int64_t target = short_side <= 16 && small_tile ? 2 * kComputeUnits : kComputeUnits;
       if (tiles < target / 2 && !p.out_float) {
-        const int64_t want = short_side <= 16 ? (target + tiles - 1) / tiles : target / tiles;
+        const int64_t want = short_side <= 16 && small_tile ? (target + tiles - 1) / tiles : target / tiles;
         const int64_t most = nkt / 8 > 1 ? nkt / 8 : 1;
         const int64_t atomics_ok = short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4);
         int64_t sp = want < most ? want : most;
