@@ -23,6 +23,7 @@ OVERWRITE, ACCUMULATE = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mip_gemm_oracle.c")
+_SRC_CONV = os.path.join(_HERE, "mip_conv_oracle.c")
 _LIB = os.path.join(_HERE, "libmip_oracle.so")
 _lock = threading.Lock()
 _lib = None
@@ -31,12 +32,12 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the oracle with the host C compiler (-O2, OpenMP over rows only)."""
     stale = (not os.path.exists(_LIB)
-             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_CONV)))
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-             "-Wall", "-Wextra", "-o", tmp, _SRC])
+             "-Wall", "-Wextra", "-o", tmp, _SRC, _SRC_CONV])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -55,6 +56,12 @@ def _load():
             lib.oracle_mip_gemm_dequant.argtypes = [ci, ci, i64, i64, i64, vp, i64, ci, vp, i64, ci,
                                                     ctypes.c_float, vp, i64, ci, ci, vp]
             lib.oracle_num_threads.restype = ci
+            lib.oracle_conv_out_extent.restype = i64
+            lib.oracle_conv_out_extent.argtypes = [i64, i64, i64, i64]
+            lib.oracle_conv_direct.restype = ci
+            lib.oracle_conv_direct.argtypes = [i64] * 9 + [vp, vp, vp, ci]
+            lib.oracle_im2col_u8.restype = ci
+            lib.oracle_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64]
             _lib = lib
     return _lib
 
@@ -141,3 +148,59 @@ def gemm_dequant(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return out
+
+
+# ---------------------------------------------------------------------------
+# convolution lowering (mip_conv_oracle.c; paper Section 7.2)
+# ---------------------------------------------------------------------------
+
+def conv_out_extent(extent, f, stride, pad):
+    """h_o (or w_o) for an input extent, filter extent, stride and padding; -1 if the filter does not fit."""
+    return int(_load().oracle_conv_out_extent(extent, f, stride, pad))
+
+
+def conv_direct(I, F, stride, pad, O=None, mode=OVERWRITE):
+    """O = CONV(F, I) from the definition.  I: uint8 (b, hi, wi, ci); F: int8 (co, hf, wf, ci);
+    returns int32 (b, ho, wo, co); with mode ACCUMULATE adds into the given O."""
+    I = np.ascontiguousarray(I)
+    F = np.ascontiguousarray(F)
+    if I.dtype != np.uint8 or F.dtype != np.int8 or I.ndim != 4 or F.ndim != 4:
+        raise TypeError("I must be uint8 (b, hi, wi, ci) and F int8 (co, hf, wf, ci)")
+    b, hi, wi, ci = I.shape
+    co, hf, wf, ci2 = F.shape
+    if ci2 != ci:
+        raise ValueError("channel counts differ")
+    ho, wo = conv_out_extent(hi, hf, stride, pad), conv_out_extent(wi, wf, stride, pad)
+    if ho < 1 or wo < 1:
+        raise ValueError("the filter does not fit the padded image")
+    if O is None:
+        if mode == ACCUMULATE:
+            raise ValueError("accumulate needs an O to add into")
+        O = np.empty((b, ho, wo, co), dtype=np.int32)
+    if O.dtype != np.int32 or O.shape != (b, ho, wo, co) or not O.flags.c_contiguous:
+        raise ValueError("O must be a contiguous int32 (b, ho, wo, co) array")
+    rc = _load().oracle_conv_direct(b, hi, wi, ci, co, hf, wf, stride, pad,
+                                    F.ctypes.data, I.ctypes.data, O.ctypes.data, mode)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return O
+
+
+def im2col_u8(I, hf, wf, stride, pad, ldm=None, fill=0x5A):
+    """The augmented matrix of I for an hf x wf filter: uint8 (n, ldm) array whose first
+    k = hf*wf*ci columns are the matrix (n = b*ho*wo rows); columns beyond k keep ``fill``."""
+    I = np.ascontiguousarray(I)
+    if I.dtype != np.uint8 or I.ndim != 4:
+        raise TypeError("I must be uint8 (b, hi, wi, ci)")
+    b, hi, wi, ci = I.shape
+    ho, wo = conv_out_extent(hi, hf, stride, pad), conv_out_extent(wi, wf, stride, pad)
+    if ho < 1 or wo < 1:
+        raise ValueError("the filter does not fit the padded image")
+    k = hf * wf * ci
+    ldm = k if ldm is None else ldm
+    M = np.full((b * ho * wo, ldm), fill, dtype=np.uint8)
+    rc = _load().oracle_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, I.ctypes.data,
+                                  M.ctypes.data, ldm)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return M
