@@ -240,6 +240,68 @@ def run_suite(M, args):
               flush=True)
 
 
+def run_conv_table(M):
+    """The convolutions of the conv-as-GEMM workload, timed as convolutions (HIP graph
+    replay, warm): the GEMM alone on a ready-made augmented matrix, the lowering written
+    out (im2col kernel + GEMM, the paper's route: it counts the transform in its
+    times), and the lowering gathered inside the GEMM kernel."""
+    import torch
+
+    def replay_us(fn, calls=16, replays=5):
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(calls):
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(replays):
+            graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / (calls * replays) * 1e3
+
+    print()
+    print("Convolution by lowering (Section 7.2), u8 activations x s8 filters -> s32, us per call:")
+    print()
+    print("| b | image | filters | (m, n, k) | GEMM alone | im2col + GEMM | gathered in the GEMM kernel "
+          "| path | GB/s of I + F + O |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for b in W.CONV_BATCHES:
+        for geo in W.CONV_GEOMETRY:
+            hi, ci, co, hf, stride, pad = geo
+            image, filt = W.conv_tensors(b, geo)
+            ho = (hi + 2 * pad - hf) // stride + 1
+            n, k = b * ho * ho, hf * hf * ci
+            dI, dF = torch.from_numpy(image).cuda(), torch.from_numpy(filt.view(np.uint8)).cuda()
+            dO = torch.zeros(n * co, dtype=torch.int32, device="cuda")
+            dM = torch.zeros(n * k, dtype=torch.uint8, device="cuda")
+            args = (b, hi, hi, ci, co, hf, hf, stride, pad)
+
+            def gemm_only():
+                M.mipgemm_s8u8s32(co, n, k, dF, k, W.ROW_MAJOR, dM, k, W.COL_MAJOR, dO, co,
+                                  W.COL_MAJOR, W.OVERWRITE)
+
+            def conv():
+                M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=dM,
+                                       workspace_bytes=n * k)
+
+            t_gemm = replay_us(gemm_only)
+            os.environ["MIPGEMM_CONV"] = "im2col"
+            try:
+                t_explicit = replay_us(conv)
+            finally:
+                del os.environ["MIPGEMM_CONV"]
+            t_implicit = replay_us(conv)
+            moved = image.size + filt.size + 4 * n * co
+            print("| %d | %dx%dx%d | %d of %dx%d | (%d, %d, %d) | %.1f | %.1f | %.1f | %s | %.0f |" % (
+                b, hi, hi, ci, co, hf, hf, co, n, k, t_gemm, t_explicit, t_implicit,
+                M.mipgemm_conv_variant_name(*args), moved / t_implicit / 1e3), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -258,6 +320,7 @@ def main():
         return
     if args.suite:
         run_suite(M, args)
+        run_conv_table(M)
         return
 
     case = pick_case(args)

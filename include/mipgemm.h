@@ -144,13 +144,84 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k,
                     void *stream, float scale);
 
 /*
+ * Convolution by lowering (paper Section 7.2: O = CONV(F, I); the input tensor is
+ * turned into an augmented matrix by IM2COL and the convolution into a GEMM of
+ * dimensions (m, n, k) = (c_o, b h_o w_o, c_i h_f w_f); the paper counts the
+ * transform in its GEMM times).
+ *
+ * Tensors are dense, innermost index last, in the order the paper gives their
+ * sizes: I is b x h_i x w_i x c_i (uint8 activations, taken at face value), F is
+ * c_o x h_f x w_f x c_i (int8), O is b x h_o x w_o x c_o (int32), with
+ * h_o = (h_i + 2 pad - h_f) / stride + 1 (integer division) and w_o likewise.
+ *     O(g, oy, ox, o) [+]= sum over (y, x, c) of
+ *                          F(o, y, x, c) * I(g, oy*stride + y - pad, ox*stride + x - pad, c)
+ * where positions outside the image contribute nothing (zero padding); the
+ * filter is not flipped; sums wrap modulo 2^32 as in the GEMM.  As a GEMM, F is A
+ * (c_o x k, row-major), the augmented matrix is B (k x n, k contiguous) and O is
+ * C (column-major with ldc = c_o), k index (y, x, c) with c fastest, n index
+ * (g, oy, ox) with ox fastest.
+ *
+ * mipgemm_conv_s8u8s32 gathers the augmented matrix on the fly inside the GEMM
+ * kernel when c_i is a multiple of 64 and F, I are 16-byte aligned: nothing is
+ * written but O and no workspace is needed.  Otherwise it writes the augmented
+ * matrix into `workspace` first (mipgemm_conv_workspace_size bytes) and runs
+ * mipgemm_s8u8s32 on it.  Pointers are device pointers owned by the caller;
+ * same execution and error conventions as the GEMM entry points.  Argument
+ * numbers: b=1 hi=2 wi=3 ci=4 co=5 hf=6 wf=7 stride=8 pad=9 F=10 I=11 O=12 mode=13
+ * workspace=14 workspace_bytes=15 stream=16.  Sizes must be positive (b and c_o may
+ * be 0: nothing is done), the filter must fit the padded image, and b*h_i*w_i*c_i,
+ * b*h_o*w_o and c_i*h_f*w_f must stay below 2^31.
+ */
+int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                         int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                         const int8_t *F, const uint8_t *I, int32_t *O,
+                         int mode,
+                         void *workspace, size_t workspace_bytes,
+                         void *stream);
+
+/*
+ * Bytes of workspace mipgemm_conv_s8u8s32 needs for these sizes when its pointers
+ * are 16-byte aligned: 0 when c_i is a multiple of 64, else room for the augmented
+ * matrix.  Returns 0 for invalid sizes.
+ */
+size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                   int64_t co, int64_t hf, int64_t wf,
+                                   int64_t stride, int64_t pad);
+
+/*
+ * The augmented matrix alone (IM2COL of Section 7.2): M has one row per output
+ * position n = (g, oy, ox) and k = h_f w_f c_i bytes per row, rows `ldm` bytes apart
+ * (ldm >= k); bytes of a row beyond k are not written.  As the B operand of a
+ * GEMM it is k x n, column-major, ldb = ldm.  Argument numbers: b=1 hi=2 wi=3
+ * ci=4 hf=5 wf=6 stride=7 pad=8 I=9 M=10 ldm=11 stream=12.
+ */
+int mipgemm_im2col_u8(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                      int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                      const uint8_t *I, uint8_t *M, int64_t ldm,
+                      void *stream);
+
+/*
+ * Name of the path mipgemm_conv_s8u8s32 takes for these sizes with 16-byte
+ * aligned pointers: "implicit:<kernel variant>" or "im2col+<kernel variant>".
+ * Host-only; for tests and benchmarks.  Returns a static string.
+ */
+const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                      int64_t co, int64_t hf, int64_t wf,
+                                      int64_t stride, int64_t pad);
+
+/*
  * Bytes of device workspace a call with these sizes and orders may use.
  * Returns 0 when none is needed (and for invalid sizes).
  */
 size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k,
                               int orderA, int orderB, int orderC);
 
-/* Static, human-readable text for a return value of the functions above. */
+/*
+ * Static, human-readable text for a return value of the functions above.  For a
+ * negative code the text gives the argument number and, in parentheses, the name
+ * that argument has in the GEMM entry points (the convolution entry points number
+ * their own arguments as their comments say).
+ */
 const char *mipgemm_strerror(int code);
 
 /*

@@ -44,7 +44,8 @@ def exported_symbols():
     return ["mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32",
             "mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32",
             "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
-            "mipgemm_mfma_ceiling"]
+            "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
+            "mipgemm_conv_variant_name", "mipgemm_im2col_u8"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -72,6 +73,16 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_variant_name.argtypes = ([ctypes.c_int64] * 3
                                                  + [ctypes.c_int64, ctypes.c_int] * 3
                                                  + [ctypes.c_int] * 3)
+            i64, vp = ctypes.c_int64, ctypes.c_void_p
+            lib.mipgemm_conv_s8u8s32.restype = ctypes.c_int
+            lib.mipgemm_conv_s8u8s32.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
+                                                             ctypes.c_size_t, vp]
+            lib.mipgemm_conv_workspace_size.restype = ctypes.c_size_t
+            lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
+            lib.mipgemm_conv_variant_name.restype = ctypes.c_char_p
+            lib.mipgemm_conv_variant_name.argtypes = [i64] * 9
+            lib.mipgemm_im2col_u8.restype = ctypes.c_int
+            lib.mipgemm_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64, vp]
             lib.mipgemm_mfma_ceiling.restype = ctypes.c_int
             lib.mipgemm_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                                  ctypes.POINTER(ctypes.c_double)]
@@ -146,6 +157,35 @@ def mipgemm_s8u8f32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mod
     """Same with an unsigned B."""
     return _call("mipgemm_s8u8f32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
                  mode, workspace, workspace_bytes, stream, check, scale)
+
+
+def mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode,
+                         workspace=None, workspace_bytes=0, stream=None, check=True):
+    """O = [O +] CONV(F, I) by lowering to the integer GEMM (see include/mipgemm.h)."""
+    rc = load_library().mipgemm_conv_s8u8s32(
+        b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
+        _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_workspace_size(b, hi, wi, ci, co, hf, wf, stride, pad) -> int:
+    return int(load_library().mipgemm_conv_workspace_size(b, hi, wi, ci, co, hf, wf, stride, pad))
+
+
+def mipgemm_conv_variant_name(b, hi, wi, ci, co, hf, wf, stride, pad) -> str:
+    return load_library().mipgemm_conv_variant_name(b, hi, wi, ci, co, hf, wf, stride,
+                                                    pad).decode()
+
+
+def mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, I, M, ldm, stream=None, check=True):
+    """The augmented matrix of the lowering alone: one row of hf*wf*ci bytes per output position."""
+    rc = load_library().mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, _ptr(I), _ptr(M),
+                                          ldm, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
 
 
 def mipgemm_workspace_size(m, n, k, orderA, orderB, orderC) -> int:

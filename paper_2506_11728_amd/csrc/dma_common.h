@@ -24,6 +24,17 @@ __device__ __forceinline__ void dma16(uint32_t voff, const uint8_t *sbase, uint3
       :);  // M0 is reserved: the compiler keeps nothing live in it across statements
 }
 
+// The same with a full 64-bit address per lane (lanes may point anywhere).
+__device__ __forceinline__ void dma16_at(const uint8_t *addr, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %1\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, off"
+      :
+      : "v"(addr), "s"(lds_addr)
+      :);
+}
+
 // "my loads of the next block have landed (N newer loads may still fly), my LDS
 // reads are complete; meet the other waves": after this the next stage is
 // visible to the whole workgroup and the stage read two steps ago may be refilled.

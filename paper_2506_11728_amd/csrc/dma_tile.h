@@ -17,6 +17,11 @@
 // 16; BM * lda and BN * ldb (or 64 * ld for the strided forms) below 2^31.
 // Rows past a ragged edge are fetched from a clamped, valid address and never
 // stored.  Everything else takes the register-staged tile kernel.
+//
+// CONV: A is the lowered matrix of a convolution (paper Section 7.2) that is never
+// written out: row i is an output position, and the 64 bytes of a k block are 64
+// channels of one filter tap (c_i a multiple of 64), read straight from the image
+// tensor; a tap that falls outside the image reads a block of zeros instead.
 #pragma once
 #include "dma_common.h"
 
@@ -36,11 +41,16 @@ struct DmaTileParams {
   int atomic;             // several workgroups add into the same tile (split k)
   int out_float;          // dequantised output: float(sum) * scale
   float scale;
+  ConvGeom conv;          // CONV kernels only
 };
 
+// what a tap outside the image contributes
+static __device__ __attribute__((aligned(16))) const uint8_t conv_zero_block[16] = {};
+
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
-template <int BM, int BN, bool A_KC, bool B_KC, int UNS>
+template <int BM, int BN, bool A_KC, bool B_KC, int UNS, bool CONV = false>
 __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
+  static_assert(!CONV || (A_KC && B_KC), "the lowered matrix and the filters are k-contiguous");
   using SA = Stage<BM, A_KC>;
   using SB = Stage<BN, B_KC>;
   constexpr int FM = BM / 64, FN = BN / 64;      // 32 x 32 blocks per wave, down and across
@@ -97,15 +107,63 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   const uint8_t *gA = P.A + (A_KC ? m0 * P.lda : m0) + kt_begin * stepA;
   const uint8_t *gB = P.B + (B_KC ? n0 * P.ldb : n0) + kt_begin * stepB;
 
+  // CONV: where the window of each of this lane's rows starts in the image (top-left
+  // tap; may lie outside), as pixel coordinates and as a byte offset that already
+  // includes the lane's 16-byte piece; and the tap / channel block the next loads fetch
+  int conv_iy[CONV ? LA : 1], conv_ix[CONV ? LA : 1], conv_at[CONV ? LA : 1];
+  int cur_y = 0, cur_x = 0, cur_c = 0, cur_at = 0;
+  if constexpr (CONV) {
+    const ConvGeom &G = P.conv;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      int a, c;
+      SA::chunk_of(i, tid, a, c);
+      int64_t row = m0 + a;
+      if (row >= P.m) row = P.m - 1;  // past the edge: repeat the last position, never stored
+      const int per_image = G.ho * G.wo;
+      const int g = (int)(row / per_image), r = (int)(row - (int64_t)g * per_image);
+      const int oy = r / G.wo, ox = r - oy * G.wo;
+      conv_iy[i] = oy * G.stride - G.pad;
+      conv_ix[i] = ox * G.stride - G.pad;
+      conv_at[i] = ((g * G.hi + conv_iy[i]) * G.wi + conv_ix[i]) * G.ci + ((c ^ SA::kswz(a)) << 4);
+    }
+    const int per_tap = G.ci / BK, tap = kt_begin / per_tap;
+    cur_c = (kt_begin - tap * per_tap) * BK;
+    cur_y = tap / G.wf;
+    cur_x = tap - cur_y * G.wf;
+    cur_at = (cur_y * G.wi + cur_x) * G.ci + cur_c;
+  }
+
   const uint32_t lds0 = lds_address(smem) + wave * 1024;
   // direct load q of a block: 0 .. LA-1 from A, then LB from B
   auto issue_one = [&](int stage, int q) {
     const uint32_t sa = lds0 + stage * STAGE_BYTES;
-    if (q < LA) dma16(offA[q], gA, sa + q * 4096);
-    else dma16(offB[q - LA], gB, sa + BM * BK + (q - LA) * 4096);
+    if (q < LA) {
+      if constexpr (CONV) {
+        const bool inside = (unsigned)(conv_iy[q] + cur_y) < (unsigned)P.conv.hi &&
+                            (unsigned)(conv_ix[q] + cur_x) < (unsigned)P.conv.wi;
+        dma16_at(inside ? P.A + (conv_at[q] + cur_at) : conv_zero_block, sa + q * 4096);
+      } else {
+        dma16(offA[q], gA, sa + q * 4096);
+      }
+    } else {
+      dma16(offB[q - LA], gB, sa + BM * BK + (q - LA) * 4096);
+    }
   };
   auto advance = [&]() {
-    gA += stepA;
+    if constexpr (CONV) {
+      cur_c += BK;
+      if (cur_c == P.conv.ci) {  // next filter tap
+        cur_c = 0;
+        if (++cur_x == P.conv.wf) {
+          cur_x = 0;
+          ++cur_y;
+        }
+      }
+      cur_at = (cur_y * P.conv.wi + cur_x) * P.conv.ci + cur_c;
+    } else {
+      gA += stepA;
+    }
     gB += stepB;
   };
 
@@ -237,6 +295,12 @@ template <int BM, int BN>
 bool dma_tile_eligible_for(const Problem &p) {
   if (p.k % BK || p.k < BK) return false;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  if (p.conv) {
+    const ConvGeom &g = *p.conv;
+    if (!a_kc || !b_kc || !p.a_unsigned || g.ci % BK) return false;
+    const int64_t images = (p.m + (int64_t)g.ho * g.wo - 1) / ((int64_t)g.ho * g.wo);
+    if (images * g.hi * g.wi * g.ci >= ((int64_t)1 << 31)) return false;  // 32-bit byte offsets
+  }
   const int64_t lda = a_kc ? p.a_sm : p.a_sk;
   const int64_t ldb = b_kc ? p.b_sn : p.b_sk;
   if (lda % 16 || ldb % 16) return false;
@@ -292,6 +356,12 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   else if (b_kc) MIP_PICK(false, true);
   else MIP_PICK(false, false);
 #undef MIP_PICK
+  if (p.conv) {
+    P.conv = *p.conv;
+    kern = dma_tile_kernel<BM, BN, true, true, 1, true>;
+  } else {
+    P.conv = ConvGeom{};
+  }
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -10,6 +10,17 @@ namespace mip {
 // column-major C is the row-major C^T = B^T A^T, so the host swaps the operand
 // roles and flips their orders; paper Section 3, closing paragraph), and each
 // 8-bit operand is described by two element strides, one of which is 1.
+// Geometry of a convolution whose lowered matrix (paper Section 7.2: IM2COL) stands
+// in for A: row i of A is output position (g, oy, ox) = i, its k index runs over
+// (y, x, c) with c fastest, and A(i, (y, x, c)) is pixel (g, oy*stride + y - pad,
+// ox*stride + x - pad, c) of the tensor at Problem::A, or 0 outside the image.
+struct ConvGeom {
+  int hi, wi, ci;  // image height, width, channels
+  int wf;          // filter width (its height is k / (wf * ci))
+  int ho, wo;      // output height, width
+  int stride, pad;
+};
+
 struct Problem {
   int64_t m, n, k;
   const void *A;  // A(i,p) at A[i*a_sm + p*a_sk]
@@ -23,6 +34,9 @@ struct Problem {
   // dequantised output (paper Section 7.3): C holds floats, float(sum) * scale
   int out_float;
   float scale;
+  // not null: A is never materialised, the kernel gathers it from the image tensor
+  // (only the direct-to-LDS tile kernels can; a_sm is then the nominal row length k)
+  const ConvGeom *conv = nullptr;
 };
 
 // Workgroup tile of the MFMA kernels (rows x columns of C).
@@ -66,6 +80,11 @@ MIP_DECLARE_DMA(64, 64)
 MIP_DECLARE_DMA(64, 256)
 MIP_DECLARE_DMA(256, 64)
 #undef MIP_DECLARE_DMA
+
+// The lowered matrix of a convolution written out: row n = (g, oy, ox) of M (pitch ldm
+// bytes) holds the k = hf * wf * ci bytes that ConvGeom describes.
+hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8_t *I, uint8_t *M,
+                         int64_t ldm, hipStream_t s);
 
 bool dma_eligible(const Problem &p, Shape shape);
 hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);

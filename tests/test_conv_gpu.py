@@ -1,0 +1,170 @@
+"""GPU parity of the convolution lowering (paper Section 7.2) against the CPU oracle,
+through the C ABI: the augmented matrix byte for byte, the convolution bit for bit,
+on the gathering ("implicit") path and on the written-out path."""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2506_11728_amd as M
+    M.load_library()
+    return M
+
+
+class Env:
+    def __init__(self, **kv):
+        self.want = kv
+
+    def __enter__(self):
+        self.old = {k: os.environ.pop(k, None) for k in self.want}
+        for k, v in self.want.items():
+            if v is not None:
+                os.environ[k] = str(v)
+
+    def __exit__(self, *a):
+        for k, v in self.old.items():
+            os.environ.pop(k, None)
+            if v is not None:
+                os.environ[k] = v
+
+
+def tensors(shape, seed):
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    rng = np.random.default_rng([seed] + list(shape))
+    I = rng.integers(0, 256, size=(b, hi, wi, ci), dtype=np.uint8)
+    F = np.clip(np.rint(rng.standard_normal((co, hf, wf, ci)) * 32), -128, 127).astype(np.int8)
+    return I, F
+
+
+# (b, hi, wi, ci, co, hf, wf, stride, pad): the ResNet-50-shaped layers of the conv workload at
+# small batch, plus strides, paddings, non-square images and filters, ragged tile edges
+CONV_SHAPES = [
+    (1, 56, 56, 64, 64, 3, 3, 1, 1), (2, 28, 28, 128, 128, 3, 3, 1, 1),
+    (3, 14, 14, 256, 256, 3, 3, 1, 1), (4, 7, 7, 512, 512, 3, 3, 1, 1),
+    (2, 7, 7, 512, 2048, 1, 1, 1, 0), (2, 28, 28, 128, 128, 3, 3, 2, 1),
+    (1, 17, 23, 64, 96, 3, 5, 2, 2), (2, 9, 13, 192, 40, 5, 3, 1, 0),
+    (1, 30, 30, 64, 256, 3, 3, 3, 1), (5, 12, 12, 64, 64, 2, 2, 2, 0),
+    (1, 8, 8, 128, 300, 3, 3, 1, 2)]
+
+
+def run_conv(M, shape, I, F, O0, mode, **env):
+    import torch
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    dI, dF = torch.from_numpy(I).cuda(), torch.from_numpy(F.view(np.uint8)).cuda()
+    dO = torch.from_numpy(O0.copy()).cuda()
+    with Env(**env):
+        need = M.mipgemm_conv_workspace_size(*shape)
+        ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda") if need else None
+        M.mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, mode,
+                               workspace=ws, workspace_bytes=need)
+    torch.cuda.synchronize()
+    if ws is not None:
+        assert (ws[need:].cpu().numpy() == 0x5A).all()      # nothing written past the workspace
+    return dO.cpu().numpy()
+
+
+@pytest.mark.parametrize("path", ["implicit", "im2col"])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_matches_the_direct_convolution(gpu, oracle, shape, mode, path):
+    print("conv", shape, "mode", mode, "path", path, flush=True)
+    I, F = tensors(shape, 1)
+    name = None
+    with Env(MIPGEMM_CONV=None if path == "implicit" else "im2col"):
+        name = gpu.mipgemm_conv_variant_name(*shape)
+    assert name.startswith("implicit:" if path == "implicit" else "im2col+"), name
+    ho = oracle.conv_out_extent(shape[1], shape[5], shape[7], shape[8])
+    wo = oracle.conv_out_extent(shape[2], shape[6], shape[7], shape[8])
+    rng = np.random.default_rng(3)
+    O0 = rng.integers(-1000, 1000, size=(shape[0], ho, wo, shape[4]), dtype=np.int32)
+    want = oracle.conv_direct(I, F, shape[7], shape[8], O=O0.copy() if mode else None, mode=mode)
+    got = run_conv(gpu, shape, I, F, O0, mode, MIPGEMM_CONV=None if path == "implicit" else "im2col")
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("variant,splits", [("dma256", None), ("dma128", None), ("dma64", 3),
+                                            ("dma64x256", None), ("dma256x64", 2), ("dma128", 5)])
+@pytest.mark.parametrize("shape", [(2, 28, 28, 128, 128, 3, 3, 1, 1), (1, 17, 23, 64, 96, 3, 5, 2, 2),
+                                   (4, 7, 7, 512, 512, 3, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_implicit_conv_under_every_tile_shape_and_split_k(gpu, oracle, shape, variant, splits):
+    print("conv", shape, variant, splits, flush=True)
+    I, F = tensors(shape, 2)
+    want = oracle.conv_direct(I, F, shape[7], shape[8])
+    with Env(MIPGEMM_VARIANT=variant, MIPGEMM_SPLITK=splits):
+        assert gpu.mipgemm_conv_variant_name(*shape) == "implicit:mfma_" + variant
+    got = run_conv(gpu, shape, I, F, np.full(want.shape, 77, dtype=np.int32), 0,
+                   MIPGEMM_VARIANT=variant, MIPGEMM_SPLITK=splits)
+    assert np.array_equal(got, want)
+
+
+def test_conv_first_layer_shape_takes_the_written_out_path(gpu, oracle):
+    shape = (2, 64, 48, 3, 64, 7, 7, 2, 3)                  # 3 channels: no 64-channel blocks to gather
+    assert gpu.mipgemm_conv_variant_name(*shape).startswith("im2col+")
+    I, F = tensors(shape, 4)
+    want = oracle.conv_direct(I, F, 2, 3)
+    got = run_conv(gpu, shape, I, F, np.zeros(want.shape, dtype=np.int32), 0)
+    assert np.array_equal(got, want)
+
+
+def test_conv_batch_32_layer_in_full(gpu, oracle):
+    """The (64, 100352, 576) GEMM of the conv workload, as the convolution it stands for."""
+    shape = (32, 56, 56, 64, 64, 3, 3, 1, 1)
+    assert gpu.mipgemm_conv_variant_name(*shape) == "implicit:mfma_dma256x64"
+    I, F = tensors(shape, 5)
+    want = oracle.conv_direct(I, F, 1, 1)
+    got = run_conv(gpu, shape, I, F, np.zeros(want.shape, dtype=np.int32), 0)
+    assert np.array_equal(got, want)
+
+
+IM2COL_SHAPES = [(2, 9, 8, 16, 3, 3, 1, 1), (1, 14, 14, 64, 3, 3, 2, 1), (3, 7, 7, 48, 1, 1, 1, 0),
+                 (1, 12, 10, 3, 7, 7, 2, 3), (2, 6, 5, 5, 2, 3, 1, 1), (1, 20, 20, 32, 5, 5, 3, 2),
+                 (1, 40, 40, 512, 3, 3, 1, 1)]
+
+
+@pytest.mark.parametrize("extra", [0, 16, 5])
+@pytest.mark.parametrize("shape", IM2COL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_im2col_matches_the_oracle(gpu, oracle, shape, extra):
+    import torch
+    print("im2col", shape, extra, flush=True)
+    b, hi, wi, ci, hf, wf, s, p = shape
+    rng = np.random.default_rng(list(shape))
+    I = rng.integers(1, 256, size=(b, hi, wi, ci), dtype=np.uint8)
+    ldm = hf * wf * ci + extra
+    want = oracle.im2col_u8(I, hf, wf, s, p, ldm=ldm, fill=0x5A)
+    dM = torch.full(want.shape, 0x5A, dtype=torch.uint8, device="cuda")
+    gpu.mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, s, p, torch.from_numpy(I).cuda(), dM, ldm)
+    torch.cuda.synchronize()
+    assert np.array_equal(dM.cpu().numpy(), want)            # row tails keep their sentinel
+
+
+def test_conv_errors_and_empty(gpu):
+    import torch
+    shape = (1, 8, 8, 3, 4, 3, 3, 1, 1)
+    need = gpu.mipgemm_conv_workspace_size(*shape)
+    assert need == 64 * 32                                   # 64 positions, 27 bytes rounded up to 32
+    dI = torch.zeros(8 * 8 * 3, dtype=torch.uint8, device="cuda")
+    dF = torch.zeros(4 * 27, dtype=torch.uint8, device="cuda")
+    dO = torch.full((64 * 4,), 9, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    call = gpu.mipgemm_conv_s8u8s32
+    assert call(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 0, check=False) == -14
+    assert call(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 0, ws, need - 1, check=False) == -15
+    assert call(b, hi, wi, ci, co, 11, wf, s, p, dF, dI, dO, 0, ws, need, check=False) == -6
+    assert call(b, hi, wi, ci, co, hf, wf, 0, p, dF, dI, dO, 0, ws, need, check=False) == -8
+    assert call(b, hi, wi, ci, co, hf, wf, s, -1, dF, dI, dO, 0, ws, need, check=False) == -9
+    assert call(b, hi, wi, ci, co, hf, wf, s, p, None, dI, dO, 0, ws, need, check=False) == -10
+    assert call(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 5, ws, need, check=False) == -13
+    assert call(0, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 0, check=False) == 0
+    torch.cuda.synchronize()
+    assert (dO.cpu().numpy() == 9).all()                     # none of these touched O
+    assert gpu.mipgemm_im2col_u8(1, 8, 8, 3, 3, 3, 1, 1, dI, ws, 26, check=False) == -11

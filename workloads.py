@@ -188,6 +188,20 @@ SQUARE_SIZES = (1024, 2048, 4096, 8192)
 CONV_LAYERS = ((64, 3136, 576), (128, 784, 1152), (256, 196, 2304),
                (512, 49, 4608), (2048, 49, 512))
 CONV_BATCHES = (1, 32)
+# The convolutions those GEMMs stand for (hi = wi, ci, co, hf = wf, stride, pad): 3 x 3
+# layers of the four stages and a 1 x 1 expansion, in the order of CONV_LAYERS.
+CONV_GEOMETRY = ((56, 64, 64, 3, 1, 1), (28, 128, 128, 3, 1, 1), (14, 256, 256, 3, 1, 1),
+                 (7, 512, 512, 3, 1, 1), (7, 512, 2048, 1, 1, 0))
+
+
+def conv_tensors(b, geometry, seed=2):
+    """Synthetic image tensor (uint8, b x hi x wi x ci) and filters (int8, co x hf x wf x ci)
+    with the value distributions of the conv-as-GEMM workload."""
+    hi, ci, co, hf, stride, pad = geometry
+    rng = np.random.Generator(np.random.PCG64([seed, b, hi, ci, co, hf]))
+    image = rng.integers(0, 256, size=(b, hi, hi, ci), dtype=np.uint8)
+    filt = np.clip(np.rint(rng.standard_normal((co, hf, hf, ci)) * 32.0), -128, 127).astype(np.int8)
+    return image, filt
 
 # tokens x out-features x in-features, encoder linear layers with 1024 tokens
 ENCODER_LAYERS = ((1024, 2304, 768), (1024, 768, 768), (1024, 3072, 768), (1024, 768, 3072))
