@@ -144,3 +144,58 @@ def test_binding_fails_loudly_without_library(M, monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libmipgemm.so")
     with pytest.raises(ImportError):
         b.load_library()
+
+
+def test_conv_argument_validation_codes(M):
+    """Every call below fails validation (or is empty), so nothing is launched: no GPU needed."""
+    def conv(b=2, hi=8, wi=8, ci=64, co=16, hf=3, wf=3, stride=1, pad=1, F=4096, I=4096, O=4096,
+             mode=0, ws=None, wsb=0):
+        return M.mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, ws, wsb,
+                                      0, check=False)
+    assert conv(b=-1) == -1
+    assert conv(hi=0) == -2
+    assert conv(wi=0) == -3
+    assert conv(ci=0) == -4
+    assert conv(co=-1) == -5
+    assert conv(hf=0) == -6
+    assert conv(hf=11) == -6                         # 11 > 8 + 2 * 1: the filter does not fit
+    assert conv(wf=11) == -7
+    assert conv(stride=0) == -8
+    assert conv(pad=-1) == -9
+    assert conv(F=0) == -10
+    assert conv(I=0) == -11
+    assert conv(O=0) == -12
+    assert conv(mode=2) == -13
+    assert conv(ci=3) == -14                         # 3 channels: the written-out route needs a workspace
+    assert conv(ci=3, ws=4096, wsb=10) == -15
+    assert conv(b=2**31) == -1
+    assert conv(b=70000, hi=256, wi=256, ci=64) == -1    # the image tensor must stay below 2^31 bytes
+    assert conv(b=0, I=0, O=0) == 0
+    assert conv(co=0, F=0, O=0) == 0
+
+    def im2col(b=2, hi=8, wi=8, ci=3, hf=3, wf=3, stride=1, pad=1, I=4096, Mat=4096, ldm=27):
+        return M.mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, I, Mat, ldm, 0, check=False)
+    assert im2col(hf=0) == -5
+    assert im2col(wf=12) == -6
+    assert im2col(stride=0) == -7
+    assert im2col(pad=-2) == -8
+    assert im2col(I=0) == -9
+    assert im2col(Mat=0) == -10
+    assert im2col(ldm=26) == -11
+    assert im2col(b=0, I=0, Mat=0) == 0
+
+
+def test_conv_path_choice_and_workspace(M):
+    name, ws = M.mipgemm_conv_variant_name, M.mipgemm_conv_workspace_size
+    # channel counts that are multiples of 64 are gathered inside the GEMM kernel: no workspace
+    assert name(32, 56, 56, 64, 64, 3, 3, 1, 1) == "implicit:mfma_dma256x64"
+    assert ws(32, 56, 56, 64, 64, 3, 3, 1, 1) == 0
+    assert name(32, 28, 28, 128, 128, 3, 3, 1, 1) == "implicit:mfma_dma128"
+    assert name(1, 7, 7, 512, 2048, 1, 1, 1, 0).startswith("implicit:")
+    # the 3-channel first layer is written out: n rows of k bytes rounded up to 16
+    assert name(2, 64, 48, 3, 64, 7, 7, 2, 3).startswith("im2col+")
+    assert ws(2, 64, 48, 3, 64, 7, 7, 2, 3) == 2 * 32 * 24 * 160
+    assert name(2, 8, 8, 96, 16, 3, 3, 1, 1).startswith("im2col+")      # 96 is not a multiple of 64
+    assert name(0, 8, 8, 64, 16, 3, 3, 1, 1) == "none"
+    assert name(2, 8, 8, 64, 16, 13, 3, 1, 1) == "invalid"
+    assert ws(2, 8, 8, 64, 16, 13, 3, 1, 1) == 0

@@ -194,6 +194,11 @@ CONV_GEOMETRY = ((56, 64, 64, 3, 1, 1), (28, 128, 128, 3, 1, 1), (14, 256, 256, 
                  (7, 512, 512, 3, 1, 1), (7, 512, 2048, 1, 1, 0))
 
 
+# the 7 x 7, stride-2 first layer of such a network on 224 x 224 RGB images: 3 channels, so
+# no 64-channel blocks to gather and a k (147) that no direct-to-LDS kernel takes
+CONV_FIRST_LAYER = (224, 3, 64, 7, 2, 3)
+
+
 def conv_tensors(b, geometry, seed=2):
     """Synthetic image tensor (uint8, b x hi x wi x ci) and filters (int8, co x hf x wf x ci)
     with the value distributions of the conv-as-GEMM workload."""
