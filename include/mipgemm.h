@@ -180,7 +180,21 @@ int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci,
                          void *stream);
 
 /*
- * Bytes of workspace mipgemm_conv_s8u8s32 needs for these sizes when its pointers
+ * The same convolution with a float O and the dequantising scale of Section 7.3
+ * fused into the write-back, exactly as in the f32 GEMM entry points:
+ * overwrite O = float(S) * scale, accumulate O = fma(float(S), scale, O), with S
+ * the int32 sum above, completed in integers before anything is converted.
+ * `scale` is argument 17 and must be finite.
+ */
+int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                         int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                         const int8_t *F, const uint8_t *I, float *O,
+                         int mode,
+                         void *workspace, size_t workspace_bytes,
+                         void *stream, float scale);
+
+/*
+ * Bytes of workspace mipgemm_conv_s8u8s32 / mipgemm_conv_s8u8f32 need for these sizes when its pointers
  * are 16-byte aligned: 0 when c_i is a multiple of 64, else room for the augmented
  * matrix.  Returns 0 for invalid sizes.
  */

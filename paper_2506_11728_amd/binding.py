@@ -45,7 +45,7 @@ def exported_symbols():
             "mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32",
             "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
             "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
-            "mipgemm_conv_variant_name", "mipgemm_im2col_u8"]
+            "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -77,6 +77,9 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_conv_s8u8s32.restype = ctypes.c_int
             lib.mipgemm_conv_s8u8s32.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
                                                              ctypes.c_size_t, vp]
+            lib.mipgemm_conv_s8u8f32.restype = ctypes.c_int
+            lib.mipgemm_conv_s8u8f32.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
+                                                             ctypes.c_size_t, vp, ctypes.c_float]
             lib.mipgemm_conv_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
             lib.mipgemm_conv_variant_name.restype = ctypes.c_char_p
@@ -165,6 +168,17 @@ def mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode,
     rc = load_library().mipgemm_conv_s8u8s32(
         b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
         _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_s8u8f32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode,
+                         workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """O (float) = [O +] scale * CONV(F, I): the lowered convolution with the scale fused in."""
+    rc = load_library().mipgemm_conv_s8u8f32(
+        b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
+        _ptr(workspace), workspace_bytes, _stream(stream), scale)
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc

@@ -392,14 +392,14 @@ int conv_sizes(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, bool h
 // the GEMM the convolution is lowered to, in the kernels' terms: the row-major C is O
 // seen as (b h_o w_o) x c_o, its A the augmented matrix, its B the filters (k contiguous)
 Problem conv_problem(const ConvCall &c, int64_t co, const void *F, const void *I, void *O, int mode,
-                     bool implicit, const void *M) {
+                     bool implicit, const void *M, int out_float = 0, float scale = 1.0f) {
   Problem p;
   p.m = c.rows; p.n = co; p.k = c.k;
   p.A = implicit ? I : M; p.a_sm = implicit ? c.k : c.ldm; p.a_sk = 1; p.a_unsigned = 1;
   p.B = F; p.b_sk = 1; p.b_sn = c.k; p.b_unsigned = 0;
   p.C = static_cast<int32_t *>(O); p.ldc = co;
   p.accumulate = mode == MIPGEMM_ACCUMULATE;
-  p.out_float = 0; p.scale = 1.0f;
+  p.out_float = out_float; p.scale = scale;
   p.conv = nullptr;
   return p;
 }
@@ -472,10 +472,10 @@ int mipgemm_im2col_u8(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t hf,
                                              static_cast<hipStream_t>(stream)));
 }
 
-int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
-                         int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
-                         int32_t *O, int mode, void *workspace, size_t workspace_bytes,
-                         void *stream) {
+static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                    int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad, const int8_t *F,
+                    const uint8_t *I, void *O, int mode, void *workspace, size_t workspace_bytes,
+                    void *stream) {
   ConvCall c;
   int rc = conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c);
   if (rc != 0) return rc;
@@ -483,10 +483,11 @@ int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t 
   if (!I && b > 0) return -11;
   if (!O && c.rows > 0 && co > 0) return -12;
   if (mode != MIPGEMM_OVERWRITE && mode != MIPGEMM_ACCUMULATE) return -13;
+  if (out_float && (!(scale == scale) || scale - scale != 0.0f)) return -17;  // NaN or infinity
   if (c.rows == 0 || co == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   mip::Plan plan;
-  Problem p = conv_problem(c, co, F, I, O, mode, true, nullptr);
+  Problem p = conv_problem(c, co, F, I, O, mode, true, nullptr, out_float, scale);
   if (conv_implicit_plan(c, p, &plan)) {
     p.conv = &c.geom;
     return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
@@ -498,8 +499,24 @@ int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t 
   if (e != hipSuccess) return static_cast<int>(e);
   // F is A (c_o x k, row-major), the matrix just written is B (k x n, column-major),
   // O is C (column-major, ldc = c_o)
-  return run(0, 1, 0, 1.0f, co, c.rows, c.k, F, c.k, MIPGEMM_ROW_MAJOR, workspace, c.ldm,
+  return run(0, 1, out_float, scale, co, c.rows, c.k, F, c.k, MIPGEMM_ROW_MAJOR, workspace, c.ldm,
              MIPGEMM_COL_MAJOR, O, co, MIPGEMM_COL_MAJOR, mode, nullptr, 0, stream);
+}
+
+int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
+                         int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
+                         int32_t *O, int mode, void *workspace, size_t workspace_bytes,
+                         void *stream) {
+  return run_conv(0, 1.0f, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream);
+}
+
+int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
+                         int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
+                         float *O, int mode, void *workspace, size_t workspace_bytes, void *stream,
+                         float scale) {
+  return run_conv(1, scale, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream);
 }
 
 const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, int orderA,

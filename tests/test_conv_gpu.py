@@ -168,3 +168,50 @@ def test_conv_errors_and_empty(gpu):
     torch.cuda.synchronize()
     assert (dO.cpu().numpy() == 9).all()                     # none of these touched O
     assert gpu.mipgemm_im2col_u8(1, 8, 8, 3, 3, 3, 1, 1, dI, ws, 26, check=False) == -11
+
+
+@pytest.mark.parametrize("path", ["implicit", "im2col"])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape,scale", [((2, 28, 28, 128, 128, 3, 3, 1, 1), 0.0123),
+                                         ((1, 17, 23, 64, 96, 3, 5, 2, 2), 2.0 ** -9),
+                                         ((4, 7, 7, 512, 512, 3, 3, 1, 1), -3.3e-5),
+                                         ((2, 12, 12, 3, 8, 5, 5, 1, 2), 0.5)],
+                         ids=lambda x: "x".join(map(str, x)) if isinstance(x, tuple) else None)
+def test_dequantised_conv(gpu, oracle, shape, scale, mode, path):
+    """Float output = scale * integer sum (+ old O): within the two roundings the header states of
+    the exact value, and for overwrite bit-equal to the same two IEEE operations done in numpy."""
+    import torch
+    print("conv f32", shape, scale, mode, path, flush=True)
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    I, F = tensors(shape, 6)
+    S = oracle.conv_direct(I, F, s, p).astype(np.float64)            # exact integers
+    rng = np.random.default_rng(8)
+    O0 = (rng.standard_normal(S.shape) * 50).astype(np.float32)
+    sc = float(np.float32(scale))
+    want = sc * S + (O0.astype(np.float64) if mode else 0.0)
+    dO = torch.from_numpy(O0.copy()).cuda()
+    env = {"MIPGEMM_CONV": None if path == "implicit" else "im2col"}
+    with Env(**env):
+        need = gpu.mipgemm_conv_workspace_size(*shape)
+        ws = torch.zeros(max(need, 16), dtype=torch.uint8, device="cuda")
+        gpu.mipgemm_conv_s8u8f32(b, hi, wi, ci, co, hf, wf, s, p,
+                                 torch.from_numpy(F.view(np.uint8)).cuda(),
+                                 torch.from_numpy(I).cuda(), dO, mode, workspace=ws,
+                                 workspace_bytes=need, scale=scale)
+    torch.cuda.synchronize()
+    got = dO.cpu().numpy().astype(np.float64)
+    bound = 2.0 ** -23 * (np.abs(want) + (np.abs(O0) if mode else 0.0))
+    assert (np.abs(got - want) <= bound).all()
+    if mode == 0:
+        assert np.array_equal(got.astype(np.float32), S.astype(np.float32) * np.float32(scale))
+
+
+def test_dequantised_conv_rejects_a_bad_scale(gpu):
+    import torch
+    z = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    o = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    rc = gpu.mipgemm_conv_s8u8f32(1, 4, 4, 64, 4, 3, 3, 1, 1, z, z, o, 0, scale=float("nan"),
+                                  check=False)
+    assert rc == -17
+    assert gpu.mipgemm_conv_s8u8f32(1, 4, 4, 64, 4, 3, 3, 1, 1, z, z, o, 3, scale=float("inf"),
+                                    check=False) == -13
