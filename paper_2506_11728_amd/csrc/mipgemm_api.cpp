@@ -142,7 +142,8 @@ Plan choose_plan(const Problem &p) {
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
     plan.splits = p.out_float ? 1 : forced_splits();  // float sums are not combined out of order
     if (plan.splits == 0) {
-      // Too few tiles to fill the chip: cut k into ranges of at least 512 until
+      // Too few tiles to fill the chip: cut k into ranges of at least 512 (128 for the
+      // register-staged kernel) until
       // there is about one workgroup per compute unit.  Every range adds its
       // partial sums into C with atomics (and an overwrite needs C zeroed first),
       // so short problems (few rows of C per byte of operand) may split further
@@ -159,8 +160,12 @@ Plan choose_plan(const Problem &p) {
       const int64_t target = short_side <= 16 && small_tile ? 2 * kComputeUnits : kComputeUnits;
       if (tiles < target / 2 && !p.out_float) {
         const int64_t want = short_side <= 16 && small_tile ? (target + tiles - 1) / tiles : target / tiles;
-        const int64_t most = nkt / 8 > 1 ? nkt / 8 : 1;
-        const int64_t atomics_ok = short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4);
+        // the register-staged kernel has a shallow pipeline with little to amortise:
+        // ranges of two k blocks already pay, and it tolerates twice the atomics
+        const bool staged = plan.kind == KIND_STAGED;
+        const int64_t shortest = staged ? 2 : 8;  // k blocks per range
+        const int64_t most = nkt / shortest > 1 ? nkt / shortest : 1;
+        const int64_t atomics_ok = (short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4)) * (staged ? 2 : 1);
         int64_t sp = want < most ? want : most;
         if (sp > atomics_ok) sp = atomics_ok;
         plan.splits = (int)sp;
