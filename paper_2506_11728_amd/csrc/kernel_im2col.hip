@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, i
         if (row < rows) {
           uint8_t *out = M + row * ldm + kk;
           if (WIDE_STORE && valid == 16) {
-            __builtin_nontemporal_store(piece[j].v, reinterpret_cast<v4i_copy *>(out));
+            *reinterpret_cast<v4i_copy *>(out) = piece[j].v;
           } else {
 #pragma unroll
             for (int e = 0; e < 16; ++e)
