@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--size", type=int, default=8192, help="m = n = k of the square workload")
     ap.add_argument("--case", type=str, default=None, help="name of a workload case to run instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
