@@ -27,7 +27,9 @@
  * mipgemm_workspace_size() bytes, or NULL / 0 when that size is 0.
  *
  * Execution.  Each call validates its arguments on the host, enqueues its
- * kernels on `stream` and returns without waiting.  The library holds no
+ * kernels on `stream` and returns without waiting.  Only kernels are enqueued
+ * (no memory-set or copy operations), so a call may be recorded into a HIP
+ * graph by stream capture and replayed.  The library holds no
  * mutable global state: calls from several threads are safe.
  *
  * Return value.  0 on success.  A negative value -i means that the i-th

@@ -367,3 +367,35 @@ def test_skinny_m_slab_kernel_wraps(gpu, oracle):
     for variant in ("slab16", "slab32"):
         got = gpu_gemm(gpu, case, A, B, np.full(m * n, 7, dtype=np.int32), variant)
         assert (got == -2 ** 31).all()
+
+
+def test_calls_replay_from_a_hip_graph(gpu, oracle):
+    """A captured call (here one that zero-fills C and then adds k ranges with atomics, and one
+    single-kernel call) gives the oracle's result on every replay, with C overwritten by other
+    work between the replays."""
+    import torch
+    for case in (W.Case("graph_splitk", 8, 0, 48, 256, 4096, seed=31),
+                 W.Case("graph_slab", 8, 1, 8, 3072, 512, orderB=W.COL_MAJOR, seed=31)):
+        ops = W.materialize(case)
+        want = oracle_result(oracle, case, ops)
+        dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+        dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+        dC = torch.from_numpy(ops.C).cuda()
+        fn = getattr(gpu, "mipgemm_" + case.entry)
+
+        def call():
+            fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+               dC, case.ldc, case.orderC, case.mode)
+
+        call()
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy(), want)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call()
+        for replay in range(4):
+            dC.fill_(replay - 7)                     # eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(dC.cpu().numpy(), want), "replay %d of %s" % (replay, case.name)
