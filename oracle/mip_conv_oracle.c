@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the convolution lowering that feeds the MIP GEMM.
+ * CPU oracle for the steps around the MIP GEMM: the convolution lowering that
+ * feeds it and the pre-packing of a weight matrix (end of the file).
  *
  * TEST INFRASTRUCTURE ONLY: the checker the GPU library is compared against;
  * the product never calls it, links it or falls back to it, and it shares no
@@ -126,5 +127,27 @@ int oracle_im2col_u8(int64_t b, int64_t hi, int64_t wi, int64_t ci,
                             row[(y * wf + x) * ci + c] = v;
                         }
             }
+    return 0;
+}
+
+/*
+ * Weight pre-packing: the k x n 8-bit matrix B, stored in either order, rewritten
+ * with k contiguous (column-major, pitch ldp >= k) -- the form in which the paper's
+ * packed buffer B_c feeds the micro-kernel (Section 4.1: packing makes the
+ * micro-kernel's accesses unit-stride, its cost amortised over the reuse of B_c;
+ * Section 5 notes that every MIP instruction wants k contiguous per operand
+ * register).  Pure data movement: P(p, j) = B(p, j).  Bytes of P beyond the k
+ * entries of a column are not written.  order: 0 row-major B(p,j) = B[p*ldb + j],
+ * 1 column-major B(p,j) = B[p + j*ldb].
+ */
+int oracle_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, int order,
+                  uint8_t *P, int64_t ldp)
+{
+    if (k < 0 || n < 0 || (order != 0 && order != 1)) return -1;
+    if (ldb < (order == 0 ? n : k) || ldp < k) return -1;
+    for (int64_t j = 0; j < n; ++j)
+        for (int64_t p = 0; p < k; ++p)
+            P[(size_t)(j * ldp + p)] = order == 0 ? B[(size_t)(p * ldb + j)]
+                                                  : B[(size_t)(p + j * ldb)];
     return 0;
 }

@@ -60,6 +60,8 @@ def _load():
             lib.oracle_conv_out_extent.argtypes = [i64, i64, i64, i64]
             lib.oracle_conv_direct.restype = ci
             lib.oracle_conv_direct.argtypes = [i64] * 9 + [vp, vp, vp, ci]
+            lib.oracle_pack_b.restype = ci
+            lib.oracle_pack_b.argtypes = [i64, i64, vp, i64, ci, vp, i64]
             lib.oracle_im2col_u8.restype = ci
             lib.oracle_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64]
             _lib = lib
@@ -204,3 +206,17 @@ def im2col_u8(I, hf, wf, stride, pad, ldm=None, fill=0x5A):
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return M
+
+
+def pack_b(k, n, B, ldb, orderB, ldp=None, fill=0x5A):
+    """The k x n 8-bit matrix in the flat buffer ``B`` rewritten with k contiguous: uint8 (n, ldp)
+    array whose row j holds column j of B in its first k bytes; bytes beyond keep ``fill``."""
+    B = np.ascontiguousarray(B).view(np.uint8).reshape(-1)
+    ldp = k if ldp is None else ldp
+    if B.size < _min_len(k, n, ldb, orderB):
+        raise ValueError("buffer shorter than the matrix it is said to hold")
+    P = np.full((n, ldp), fill, dtype=np.uint8)
+    rc = _load().oracle_pack_b(k, n, B.ctypes.data, ldb, orderB, P.ctypes.data, ldp)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return P

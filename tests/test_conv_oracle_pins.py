@@ -197,3 +197,41 @@ def test_rejects_a_filter_that_does_not_fit(oracle):
         oracle.conv_direct(I, F, 1, 0)
     with pytest.raises(ValueError):
         oracle.im2col_u8(I, 3, 3, 1, 0)
+
+
+# ---------------------------------------------------------------------------
+# weight pre-packing (oracle_pack_b): the same matrix with k contiguous
+# ---------------------------------------------------------------------------
+
+def test_pack_b_hand_worked(oracle):
+    # B = [[1, 2, 3], [4, 5, 6]] (k = 2, n = 3): the columns (1,4), (2,5), (3,6) become rows
+    Brow = np.array([1, 2, 3, 0x77, 4, 5, 6, 0x77], dtype=np.uint8)          # row-major, ldb = 4
+    assert oracle.pack_b(2, 3, Brow, 4, oracle.ROW_MAJOR).tolist() == [[1, 4], [2, 5], [3, 6]]
+    Bcol = np.array([1, 4, 0x77, 2, 5, 0x77, 3, 6, 0x77], dtype=np.uint8)    # column-major, ldb = 3
+    assert oracle.pack_b(2, 3, Bcol, 3, oracle.COL_MAJOR).tolist() == [[1, 4], [2, 5], [3, 6]]
+    P = oracle.pack_b(2, 3, Brow, 4, oracle.ROW_MAJOR, ldp=5, fill=0xEE)
+    assert P.tolist() == [[1, 4, 0xEE, 0xEE, 0xEE], [2, 5, 0xEE, 0xEE, 0xEE], [3, 6, 0xEE, 0xEE, 0xEE]]
+
+
+@pytest.mark.parametrize("k,n,order,pad", [(7, 5, 0, 0), (64, 64, 0, 3), (100, 37, 1, 5), (1, 9, 0, 0),
+                                           (130, 200, 0, 17), (33, 1, 1, 0)])
+def test_pack_b_is_the_numpy_transpose_and_leaves_the_product_unchanged(oracle, k, n, order, pad):
+    rng = np.random.default_rng([k, n, order, pad])
+    dense = rng.integers(-128, 128, size=(k, n), dtype=np.int8)
+    ldb = (n if order == 0 else k) + pad
+    flat = np.full(((k if order == 0 else n), ldb), 0x5A, dtype=np.uint8)
+    if order == 0:
+        flat[:, :n] = dense.view(np.uint8)
+    else:
+        flat[:, :k] = dense.T.view(np.uint8)
+    P = oracle.pack_b(k, n, flat.reshape(-1), ldb, order, ldp=k + 2)
+    assert np.array_equal(P[:, :k], dense.T.view(np.uint8)) and (P[:, k:] == 0x5A).all()
+    # the GEMM on the packed matrix (column-major, ldb = ldp) equals the GEMM on the original
+    m = 6
+    A = rng.integers(-128, 128, size=m * k, dtype=np.int8)
+    C1 = np.zeros(m * n, dtype=np.int32)
+    C2 = np.zeros(m * n, dtype=np.int32)
+    oracle.gemm(False, False, m, n, k, A, k, 0, flat.reshape(-1).view(np.int8), ldb, order, C1, n, 0, 0)
+    oracle.gemm(False, False, m, n, k, A, k, 0, P.reshape(-1).view(np.int8), k + 2, 1, C2, n, 0, 0)
+    assert np.array_equal(C1, C2)
+    assert np.array_equal(C1.reshape(m, n), A.reshape(m, k).astype(np.int64) @ dense.astype(np.int64))
