@@ -303,6 +303,35 @@ def run_conv_table(M):
                 M.mipgemm_conv_variant_name(*args), moved / t_implicit / 1e3), flush=True)
 
 
+def run_pack_table(M):
+    """Decode GEMMs on weights as stored (k x n, row-major) and on the same weights packed
+    once with k contiguous (mipgemm_pack_b), cold (operand sets rotated over > 600 MB)."""
+    import torch
+    print()
+    print("Weight pre-packing (Section 4.1 carried to constant weights), decode shapes, us per call, cold:")
+    print()
+    print("| m | n | k | row-major B as stored | packed once (k contiguous) | the packing itself (once) |")
+    print("|---|---|---|---|---|---|")
+    for (n, k) in W.DECODE_NK:
+        for m in W.DECODE_M:
+            plain = next(c for c in W.all_cases() if c.name == "c4_dec_%dx%dx%d" % (m, n, k))
+            packed = next(c for c in W.all_cases() if c.name == "c4_dec_%dx%dx%d_Bc" % (m, n, k))
+            t_plain = time_case_graph(M, plain, footprint=600 * 10 ** 6)
+            t_packed = time_case_graph(M, packed, footprint=600 * 10 ** 6)
+            dB = torch.zeros(k * n, dtype=torch.uint8, device="cuda")
+            dP = torch.empty_like(dB)
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            M.mipgemm_pack_b(k, n, dB, n, W.ROW_MAJOR, dP, k)
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(10):
+                M.mipgemm_pack_b(k, n, dB, n, W.ROW_MAJOR, dP, k)
+            ev1.record()
+            torch.cuda.synchronize()
+            print("| %d | %d | %d | %.1f | %.1f | %.1f |" % (m, n, k, t_plain, t_packed,
+                                                        ev0.elapsed_time(ev1) / 10 * 1e3), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -322,6 +351,7 @@ def main():
     if args.suite:
         run_suite(M, args)
         run_conv_table(M)
+        run_pack_table(M)
         return
 
     case = pick_case(args)

@@ -226,6 +226,25 @@ const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t
                                       int64_t stride, int64_t pad);
 
 /*
+ * Weight pre-packing (paper Section 4.1: B is packed into a buffer that the
+ * micro-kernel reads with unit stride, at a cost amortised over its reuse; for
+ * inference the weights are constant, so the packing can be done once, ahead of
+ * time).  Rewrites the k x n 8-bit matrix B, stored in either order, with k
+ * contiguous: P(p, j) = P[p + j*ldp], ldp >= k, i.e. the same matrix in
+ * MIPGEMM_COL_MAJOR order with ldb = ldp, which is how P is then passed as the B
+ * of the GEMM entry points.  The GEMMs accept either order directly; packing pays
+ * when a few rows of A (m <= 16) meet the same B many times, because the skinny-m
+ * kernel streams a k-contiguous B in whole cache-line runs.  Bytes of P beyond the
+ * k entries of a column are not written; B and P must not overlap (not checked);
+ * signedness does not matter (bytes are moved).  Argument numbers: k=1 n=2 B=3
+ * ldb=4 orderB=5 P=6 ldp=7 stream=8.
+ */
+int mipgemm_pack_b(int64_t k, int64_t n,
+                   const void *B, int64_t ldb, int orderB,
+                   void *P, int64_t ldp,
+                   void *stream);
+
+/*
  * Bytes of device workspace a call with these sizes and orders may use.
  * Returns 0 when none is needed (and for invalid sizes).
  */

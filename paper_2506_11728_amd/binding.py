@@ -45,7 +45,8 @@ def exported_symbols():
             "mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32",
             "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
             "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
-            "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32"]
+            "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32",
+            "mipgemm_pack_b"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -84,6 +85,8 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
             lib.mipgemm_conv_variant_name.restype = ctypes.c_char_p
             lib.mipgemm_conv_variant_name.argtypes = [i64] * 9
+            lib.mipgemm_pack_b.restype = ctypes.c_int
+            lib.mipgemm_pack_b.argtypes = [i64, i64, vp, i64, ctypes.c_int, vp, i64, vp]
             lib.mipgemm_im2col_u8.restype = ctypes.c_int
             lib.mipgemm_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64, vp]
             lib.mipgemm_mfma_ceiling.restype = ctypes.c_int
@@ -197,6 +200,14 @@ def mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, I, M, ldm, stream=None
     """The augmented matrix of the lowering alone: one row of hf*wf*ci bytes per output position."""
     rc = load_library().mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, _ptr(I), _ptr(M),
                                           ldm, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_pack_b(k, n, B, ldb, orderB, P, ldp, stream=None, check=True):
+    """The k x n matrix B rewritten with k contiguous (pass P as B with COL_MAJOR, ldb = ldp)."""
+    rc = load_library().mipgemm_pack_b(k, n, _ptr(B), ldb, orderB, _ptr(P), ldp, _stream(stream))
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc

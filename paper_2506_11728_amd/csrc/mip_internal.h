@@ -86,6 +86,11 @@ MIP_DECLARE_DMA(256, 64)
 hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8_t *I, uint8_t *M,
                          int64_t ldm, hipStream_t s);
 
+// The k x n matrix B (b_kc: already k-contiguous, pitch ldb; else row-major, pitch ldb)
+// rewritten k-contiguous with pitch ldp.
+hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
+                         int64_t ldp, hipStream_t s);
+
 bool dma_eligible(const Problem &p, Shape shape);
 hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);
 

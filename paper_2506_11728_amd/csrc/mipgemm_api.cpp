@@ -524,6 +524,23 @@ int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t 
                   workspace_bytes, stream);
 }
 
+int mipgemm_pack_b(int64_t k, int64_t n, const void *B, int64_t ldb, int orderB, void *P,
+                   int64_t ldp, void *stream) {
+  if (k < 0 || k > MIPGEMM_MAX_DIM) return -1;
+  if (n < 0 || n > MIPGEMM_MAX_DIM) return -2;
+  if (!B && k > 0 && n > 0) return -3;
+  if (!order_ok(orderB)) return -5;
+  {
+    const int64_t need = orderB == MIPGEMM_ROW_MAJOR ? n : k;
+    if (ldb < (need > 1 ? need : 1) || ldb > MIPGEMM_MAX_DIM) return -4;
+  }
+  if (!P && k > 0 && n > 0) return -6;
+  if (ldp < (k > 1 ? k : 1) || ldp > MIPGEMM_MAX_DIM) return -7;
+  return static_cast<int>(mip::launch_pack_b(k, n, static_cast<const uint8_t *>(B), ldb,
+                                             orderB == MIPGEMM_COL_MAJOR, static_cast<uint8_t *>(P),
+                                             ldp, static_cast<hipStream_t>(stream)));
+}
+
 const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, int orderA,
                                  int64_t ldb, int orderB, int64_t ldc, int orderC, int a_unsigned,
                                  int b_unsigned, int aligned16) {

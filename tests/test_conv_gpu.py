@@ -215,3 +215,59 @@ def test_dequantised_conv_rejects_a_bad_scale(gpu):
     assert rc == -17
     assert gpu.mipgemm_conv_s8u8f32(1, 4, 4, 64, 4, 3, 3, 1, 1, z, z, o, 3, scale=float("inf"),
                                     check=False) == -13
+
+
+# ---------------------------------------------------------------------------
+# weight pre-packing
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k,n,order,pad,ppad", [
+    (64, 64, 0, 0, 0), (4096, 4096, 0, 0, 0), (513, 4097, 0, 17, 3), (130, 200, 0, 16, 16),
+    (1, 9, 0, 0, 0), (200, 1, 0, 0, 5), (100, 37, 1, 5, 0), (4096, 1024, 1, 16, 32),
+    (77, 129, 1, 0, 3), (11008, 256, 0, 0, 0)])
+def test_pack_b_matches_the_oracle(gpu, oracle, k, n, order, pad, ppad):
+    import torch
+    print("pack", k, n, order, pad, ppad, flush=True)
+    rng = np.random.default_rng([k, n, order, pad])
+    ldb = (n if order == 0 else k) + pad
+    flat = rng.integers(0, 256, size=(k if order == 0 else n) * ldb, dtype=np.uint8)
+    ldp = k + ppad
+    want = oracle.pack_b(k, n, flat, ldb, order, ldp=ldp, fill=0x5A)
+    dP = torch.full((n * ldp,), 0x5A, dtype=torch.uint8, device="cuda")
+    gpu.mipgemm_pack_b(k, n, torch.from_numpy(flat).cuda(), ldb, order, dP, ldp)
+    torch.cuda.synchronize()
+    assert np.array_equal(dP.cpu().numpy().reshape(n, ldp), want)   # column tails keep their sentinel
+
+
+def test_packed_weights_give_the_same_gemm_through_the_skinny_kernel(gpu, oracle):
+    import torch
+    import workloads as W
+    case = W.Case("packed_decode", 8, 0, 16, 4096, 1024, seed=41)           # row-major B
+    ops = W.materialize(case)
+    want = ops.C.copy()
+    oracle.gemm(False, False, case.m, case.n, case.k, ops.A, case.lda, 0, ops.B, case.ldb, 0,
+                want, case.ldc, 0, 0)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dP = torch.empty(case.n * case.k, dtype=torch.uint8, device="cuda")
+    dC = torch.from_numpy(ops.C).cuda()
+    gpu.mipgemm_pack_b(case.k, case.n, dB, case.ldb, 0, dP, case.k)
+    assert gpu.mipgemm_variant_name(case.m, case.n, case.k, case.lda, 0, case.k, 1, case.ldc,
+                                    0) == "mfma_slab16"
+    gpu.mipgemm_s8s8s32(case.m, case.n, case.k, dA, case.lda, 0, dP, case.k, 1, dC, case.ldc, 0, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+
+
+def test_pack_b_errors(gpu):
+    import torch
+    z = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    f = gpu.mipgemm_pack_b
+    assert f(-1, 4, z, 4, 0, z, 4, check=False) == -1
+    assert f(4, -1, z, 4, 0, z, 4, check=False) == -2
+    assert f(4, 4, None, 4, 0, z, 4, check=False) == -3
+    assert f(4, 8, z, 7, 0, z, 4, check=False) == -4
+    assert f(4, 8, z, 8, 2, z, 4, check=False) == -5
+    assert f(4, 8, z, 8, 0, None, 4, check=False) == -6
+    assert f(4, 8, z, 8, 0, z, 3, check=False) == -7
+    assert f(0, 8, None, 8, 0, None, 1, check=False) == 0
