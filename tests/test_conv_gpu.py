@@ -1,6 +1,7 @@
-"""GPU parity of the convolution lowering (paper Section 7.2) against the CPU oracle,
-through the C ABI: the augmented matrix byte for byte, the convolution bit for bit,
-on the gathering ("implicit") path and on the written-out path."""
+"""GPU parity of the steps around the GEMM against the CPU oracle, through the C ABI: the
+convolution lowering (paper Section 7.2) -- the augmented matrix byte for byte, the
+convolution bit for bit on the gathering ("implicit") path and on the written-out path --
+and the pre-packing of a weight matrix (Section 4.1) byte for byte."""
 import os
 
 import numpy as np

@@ -1,4 +1,4 @@
-"""Pins of the convolution-lowering oracle (oracle/mip_conv_oracle.c), CPU only.
+"""Pins of the convolution-lowering and weight-packing oracle (oracle/mip_conv_oracle.c), CPU only.
 
 Each test checks the oracle against something other than itself: hand-worked
 values, brute force in Python integers, closed forms, the lowering identity
