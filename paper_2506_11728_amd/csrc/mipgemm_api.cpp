@@ -385,6 +385,7 @@ int conv_sizes(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, bool h
   const int64_t ho = (hi + 2 * pad - hf) / stride + 1, wo = (wi + 2 * pad - wf) / stride + 1;
   // products checked step by step so that none overflows 64 bits
   if (hi * wi >= lim || hi * wi * ci >= lim || (b > 0 && hi * wi * ci >= lim / b)) return -1;
+  if (ho >= lim || wo >= lim) return -(8 + shift);  // only an absurd padding gets here
   if (ho * wo >= lim || (b > 0 && ho * wo >= lim / b)) return -1;
   if (hf * wf >= lim || hf * wf * ci >= lim) return -4;
   out->geom = mip::ConvGeom{(int)hi, (int)wi, (int)ci, (int)wf, (int)ho, (int)wo, (int)stride, (int)pad};

@@ -170,6 +170,7 @@ def test_conv_argument_validation_codes(M):
     assert conv(ci=3, ws=4096, wsb=10) == -15
     assert conv(b=2**31) == -1
     assert conv(b=70000, hi=256, wi=256, ci=64) == -1    # the image tensor must stay below 2^31 bytes
+    assert conv(b=1, hi=2**31 - 1, wi=1, ci=1, pad=2**31 - 1, hf=1, wf=1) == -9   # output extent beyond 2^31
     assert conv(b=0, I=0, O=0) == 0
     assert conv(co=0, F=0, O=0) == 0
 
