@@ -332,6 +332,80 @@ def run_pack_table(M):
                                                         ev0.elapsed_time(ev1) / 10 * 1e3), flush=True)
 
 
+def run_encoder_table(M):
+    """The GEMMs of one transformer encoder block (the paper's second workload, Section 7.2),
+    captured into one HIP graph in the order of the paper's table and replayed: once with
+    the per-head attention products as separate calls (the paper's loop over heads), once
+    with each of the two as one strided-batch call."""
+    import torch
+    print()
+    print("One encoder block of a BERT-Large-type model (d = 1024, h = 16, f = 4096, b = 1), its GEMMs only,")
+    print("s8 x s8 -> s32, us (warm):")
+    print()
+    print("| l | M1-M3 (each) | M5 (one head) | M7 (one head) | M9 | F11 | F13 | M5, all heads in one call "
+          "| M7, all heads in one call | block, heads looped (38 calls) | block, heads batched (8 calls) "
+          "| TOPS (batched) |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+
+    def replay_us(fn, repeats, replays=6):
+        """fn captured `repeats` times into one graph (the launch of a graph has a cost of its own)"""
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(repeats):
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(replays):
+            graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / (replays * repeats) * 1e3
+
+    h = W.ENCODER_H
+    for l in W.ENCODER_TOKENS:
+        block = W.encoder_block(l)
+        each = [time_case_graph(M, case, calls=24) for (case, count) in block]
+        looped, batched, ops = [], [], 0
+        for (case, count) in block:
+            o = W.materialize(case)
+            per_head = count == h
+            # a head's operands are slices of the full activation matrices: h copies, back to back
+            dA = torch.from_numpy(np.tile(o.A.view(np.uint8), h if per_head else 1)).cuda()
+            dB = torch.from_numpy(np.tile(o.B.view(np.uint8), h if per_head else 1)).cuda()
+            dC = torch.zeros(o.C.size * (h if per_head else 1), dtype=torch.int32, device="cuda")
+            ops += count * case.ops
+            c = case
+            if per_head:
+                sa, sb, sc = o.A.size, o.B.size, o.C.size
+                for z in range(h):
+                    looped.append(lambda c=c, a=dA[z * sa:], b=dB[z * sb:], cc=dC[z * sc:]:
+                                  M.mipgemm_s8s8s32(c.m, c.n, c.k, a, c.lda, c.orderA, b, c.ldb,
+                                                    c.orderB, cc, c.ldc, c.orderC, c.mode))
+                batched.append(lambda c=c, a=dA, b=dB, cc=dC, sa=sa, sb=sb, sc=sc:
+                               M.mipgemm_s8s8s32_batched(c.m, c.n, c.k, a, c.lda, c.orderA, sa, b,
+                                                         c.ldb, c.orderB, sb, cc, c.ldc, c.orderC,
+                                                         sc, h, c.mode))
+            else:
+                for _ in range(count):
+                    call = (lambda c=c, a=dA, b=dB, cc=dC:
+                            M.mipgemm_s8s8s32(c.m, c.n, c.k, a, c.lda, c.orderA, b, c.ldb, c.orderB,
+                                              cc, c.ldc, c.orderC, c.mode))
+                    looped.append(call)
+                    batched.append(call)
+        m5, m7 = [b for b in batched if b not in looped]
+        t_m5 = replay_us(m5, 24)
+        t_m7 = replay_us(m7, 24)
+        t_looped = replay_us(lambda: [f() for f in looped], 4)
+        t_batched = replay_us(lambda: [f() for f in batched], 8)
+        print("| %d | %s | %.1f | %.1f | %.1f | %.1f | %.1f |" % (
+            l, " | ".join("%.1f" % t for t in each), t_m5, t_m7, t_looped, t_batched,
+            ops / t_batched / 1e6), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -352,6 +426,7 @@ def main():
         run_suite(M, args)
         run_conv_table(M)
         run_pack_table(M)
+        run_encoder_table(M)
         return
 
     case = pick_case(args)

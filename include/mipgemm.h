@@ -108,6 +108,28 @@ int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k,
                     void *stream);
 
 /*
+ * A batch of independent signed x signed GEMMs of one shape in one call: problem
+ * z = 0 .. batch-1 reads A + z*strideA and B + z*strideB and writes C + z*strideC
+ * (strides in elements, >= 0; a stride of 0 shares that operand between the
+ * problems; the C slices must not overlap, which is not checked).  This is the loop
+ * over heads and sequences around the attention products of the paper's encoder
+ * block (Section 7.2, the table of GEMM dimensions in the transformer encoder:
+ * K^T Q and V E_1 for every head i and sequence j), made one launch, because
+ * each of those products alone is far too small to occupy the device.  Everything
+ * else is as for mipgemm_s8s8s32.  batch <= 65535; batch == 0 does nothing.
+ * Argument numbers: m=1 n=2 k=3 A=4 lda=5 orderA=6 strideA=7 B=8 ldb=9 orderB=10
+ * strideB=11 C=12 ldc=13 orderC=14 strideC=15 batch=16 mode=17 workspace=18
+ * workspace_bytes=19 stream=20.
+ */
+int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k,
+                            const int8_t *A, int64_t lda, int orderA, int64_t strideA,
+                            const int8_t *B, int64_t ldb, int orderB, int64_t strideB,
+                            int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
  * Dequantised output, the step the paper's quantization scheme puts right after
  * the integer GEMM (Section 7.3: C^r = s_A s_B A^q B^q = s_A s_B C^q): the same
  * three GEMMs, but C holds floats and receives

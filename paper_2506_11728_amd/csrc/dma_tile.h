@@ -42,6 +42,7 @@ struct DmaTileParams {
   int out_float;          // dequantised output: float(sum) * scale
   float scale;
   ConvGeom conv;          // CONV kernels only
+  int64_t a_sb, b_sb, c_sb;  // byte / element offsets of problem z of a batch (blockIdx.z)
 };
 
 // what a tap outside the image contributes
@@ -67,6 +68,12 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
 
   int tm, tn;
   if (!tile_of_workgroup(P.tiles_m, P.tiles_n, &tm, &tn)) return;
+  if (!CONV) {  // problem of the batch
+    const int64_t z = blockIdx.z;
+    P.A += z * P.a_sb;
+    P.B += z * P.b_sb;
+    P.C += z * P.c_sb;
+  }
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
   const int kt_begin = blockIdx.y * P.kt_per_split;
   const int kt_end = kt_begin + P.kt_per_split < P.nkt ? kt_begin + P.kt_per_split : P.nkt;
@@ -297,7 +304,7 @@ bool dma_tile_eligible_for(const Problem &p) {
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   if (p.conv) {
     const ConvGeom &g = *p.conv;
-    if (!a_kc || !b_kc || !p.a_unsigned || g.ci % BK) return false;
+    if (!a_kc || !b_kc || !p.a_unsigned || g.ci % BK || p.batch != 1) return false;
     const int64_t images = (p.m + (int64_t)g.ho * g.wo - 1) / ((int64_t)g.ho * g.wo);
     if (images * g.hi * g.wi * g.ci >= ((int64_t)1 << 31)) return false;  // 32-bit byte offsets
   }
@@ -305,6 +312,7 @@ bool dma_tile_eligible_for(const Problem &p) {
   const int64_t ldb = b_kc ? p.b_sn : p.b_sk;
   if (lda % 16 || ldb % 16) return false;
   if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
+  if (p.batch > 1 && (p.a_sb % 16 || p.b_sb % 16)) return false;  // every problem's operands aligned
   if (!a_kc && p.m % 16) return false;
   if (!b_kc && p.n % 16) return false;
   const int64_t lim = (int64_t)1 << 31;
@@ -342,8 +350,11 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
     hipError_t e = launch_fill_zero(p, s);  // partial sums are added into C: start from zero
     if (e != hipSuccess) return e;
   }
+  P.a_sb = p.a_sb;
+  P.b_sb = p.b_sb;
+  P.c_sb = p.c_sb;
   const int ntiles = P.tiles_m * P.tiles_n;
-  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits);
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits, (unsigned)p.batch);
   const size_t lds = (size_t)DMA_STAGES * (BM + BN) * BK;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
   void (*kern)(DmaTileParams) = nullptr;

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
 }  // namespace
 
 bool dma_k128_eligible(const Problem &p) {
-  if (p.conv || p.m % DM || p.n % DN || p.k % KD2 || p.k < KD2) return false;
+  if (p.conv || p.batch != 1 || p.m % DM || p.n % DN || p.k % KD2 || p.k < KD2) return false;
   const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
   const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
   if (lda % 16 || ldb % 16) return false;

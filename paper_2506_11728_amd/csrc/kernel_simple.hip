@@ -6,7 +6,8 @@
 namespace mip {
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(int32_t *__restrict__ C, int64_t ldc,
-                                                       int64_t m, int64_t n) {
+                                                       int64_t m, int64_t n, int64_t c_sb) {
+  C += (int64_t)blockIdx.z * c_sb;
   int64_t j = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
   int64_t i = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
   if (i < m && j < n) C[i * ldc + j] = 0;
@@ -18,8 +19,9 @@ __global__ __launch_bounds__(256) void simple_kernel(Problem p) {
   const int64_t j = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
   const int64_t i = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
   if (i >= p.m || j >= p.n) return;
-  const uint8_t *a = static_cast<const uint8_t *>(p.A) + i * p.a_sm;
-  const uint8_t *b = static_cast<const uint8_t *>(p.B) + j * p.b_sn;
+  const int64_t z = blockIdx.z;  // problem of the batch
+  const uint8_t *a = static_cast<const uint8_t *>(p.A) + z * p.a_sb + i * p.a_sm;
+  const uint8_t *b = static_cast<const uint8_t *>(p.B) + z * p.b_sb + j * p.b_sn;
   uint32_t acc = 0;
   for (int64_t q = 0; q < p.k; ++q) {
     uint32_t av = a[q * p.a_sk], bv = b[q * p.b_sk];
@@ -27,7 +29,7 @@ __global__ __launch_bounds__(256) void simple_kernel(Problem p) {
     if (!p.b_unsigned) bv = (uint32_t)(int32_t)(int8_t)bv;
     acc += av * bv;
   }
-  uint32_t *c = reinterpret_cast<uint32_t *>(p.C) + i * p.ldc + j;
+  uint32_t *c = reinterpret_cast<uint32_t *>(p.C) + z * p.c_sb + i * p.ldc + j;
   if (!p.out_float) {
     *c = p.accumulate ? *c + acc : acc;
   } else {  // dequantised output (paper Section 7.3): float(sum) * scale
@@ -38,8 +40,8 @@ __global__ __launch_bounds__(256) void simple_kernel(Problem p) {
 }
 
 // 64 columns x 4 rows per block; the caller keeps rows <= 65535 * 4
-static dim3 grid_for(int64_t rows, int64_t n) {
-  return dim3((unsigned)((n + 63) / 64), (unsigned)((rows + 3) / 4), 1);
+static dim3 grid_for(int64_t rows, int64_t n, int64_t batch) {
+  return dim3((unsigned)((n + 63) / 64), (unsigned)((rows + 3) / 4), (unsigned)batch);
 }
 
 hipError_t launch_fill_zero(const Problem &p, hipStream_t s) {
@@ -48,9 +50,9 @@ hipError_t launch_fill_zero(const Problem &p, hipStream_t s) {
   const int64_t slab = 65535LL * 4;
   for (int64_t i0 = 0; i0 < p.m; i0 += slab) {
     int64_t rows = p.m - i0 < slab ? p.m - i0 : slab;
-    dim3 grid = grid_for(rows, p.n);
+    dim3 grid = grid_for(rows, p.n, p.batch);
     hipLaunchKernelGGL(fill_zero_kernel, grid, dim3(256), 0, s, p.C + i0 * p.ldc, p.ldc, rows,
-                       p.n);
+                       p.n, p.c_sb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -64,7 +66,7 @@ hipError_t launch_simple(const Problem &p, hipStream_t s) {
     q.m = p.m - i0 < slab ? p.m - i0 : slab;
     q.A = static_cast<const uint8_t *>(p.A) + i0 * p.a_sm;
     q.C = p.C + i0 * p.ldc;
-    dim3 grid = grid_for(q.m, q.n);
+    dim3 grid = grid_for(q.m, q.n, q.batch);
     hipLaunchKernelGGL(simple_kernel, grid, dim3(256), 0, s, q);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

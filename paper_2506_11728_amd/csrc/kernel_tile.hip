@@ -50,7 +50,13 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
       2 * STAGE_BYTES > 4 * STORE_PATCH_BYTES ? 2 * STAGE_BYTES : 4 * STORE_PATCH_BYTES;
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
 
-  const Problem &p = tp.p;
+  Problem p = tp.p;
+  {  // problem of the batch
+    const int64_t z = blockIdx.z;
+    p.A = static_cast<const uint8_t *>(p.A) + z * p.a_sb;
+    p.B = static_cast<const uint8_t *>(p.B) + z * p.b_sb;
+    p.C += z * p.c_sb;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
@@ -196,7 +202,7 @@ static hipError_t launch_cfg(const Problem &p, int splits, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   int ntiles = tp.tiles_m * tp.tiles_n;
-  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits);
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits, (unsigned)p.batch);
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   if (a_kc && b_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, true>), grid, dim3(NTHREADS), 0, s, tp);
   else if (a_kc) hipLaunchKernelGGL((tile_kernel<BM, BN, true, false>), grid, dim3(NTHREADS), 0, s, tp);

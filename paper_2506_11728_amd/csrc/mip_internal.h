@@ -34,6 +34,11 @@ struct Problem {
   // dequantised output (paper Section 7.3): C holds floats, float(sum) * scale
   int out_float;
   float scale;
+  // batch > 1: that many independent problems of the same shape; problem z reads A + z*a_sb,
+  // B + z*b_sb and writes C + z*c_sb (strides in elements).  Only the tile kernels, the
+  // zero fill and the simple kernel take a batch (grid.z).
+  int64_t batch = 1;
+  int64_t a_sb = 0, b_sb = 0, c_sb = 0;
   // not null: A is never materialised, the kernel gathers it from the image tensor
   // (only the direct-to-LDS tile kernels can; a_sm is then the nominal row length k)
   const ConvGeom *conv = nullptr;

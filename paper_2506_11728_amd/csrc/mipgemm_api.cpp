@@ -93,8 +93,10 @@ static int forced_splits() {
   return v > 0 ? v : 0;
 }
 
+// over all problems of a batch: what the chip sees is their sum
 static int64_t tile_count(const Problem &p, Shape s) {
-  return ((p.m + kShapeRows[s] - 1) / kShapeRows[s]) * ((p.n + kShapeCols[s] - 1) / kShapeCols[s]);
+  return ((p.m + kShapeRows[s] - 1) / kShapeRows[s]) * ((p.n + kShapeCols[s] - 1) / kShapeCols[s]) *
+         (p.batch > 1 ? p.batch : 1);
 }
 
 Plan choose_plan(const Problem &p) {
@@ -239,17 +241,29 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
   return 0;
 }
 
+struct Batch {
+  int64_t count = 1;
+  int64_t stride_a = 0, stride_b = 0, stride_c = 0;  // elements between consecutive problems
+};
+
 // out_float: C holds floats and receives float(sum) * scale (the f32 entry points)
 int run(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
         int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb, int orderB,
         void *C, int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
-        void *stream) {
+        void *stream, const Batch &batch = Batch()) {
   Problem p;
   int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB,
                                   C, ldc, orderC, mode, workspace, workspace_bytes, &p);
   if (rc != 0) return rc;
   p.out_float = out_float;
   p.scale = scale;
+  p.batch = batch.count;
+  // a column-major C has swapped the operand roles: the strides follow their operands
+  const bool swapped = orderC != MIPGEMM_ROW_MAJOR;
+  p.a_sb = swapped ? batch.stride_b : batch.stride_a;
+  p.b_sb = swapped ? batch.stride_a : batch.stride_b;
+  p.c_sb = batch.stride_c;
+  if (p.batch == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   const mip::Plan plan = mip::choose_plan(p);
@@ -288,6 +302,35 @@ int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t ld
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
   return run(0, 1, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
+}
+
+int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda,
+                            int orderA, int64_t strideA, const int8_t *B, int64_t ldb, int orderB,
+                            int64_t strideB, int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+  // the shared validation numbers its arguments as the single-problem entry points do:
+  // map them onto this prototype (strides and batch shift everything after orderA)
+  static const int renumber[17] = {0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 12, 13, 14, 17, 18, 19, 20};
+  Problem probe;
+  const int base = validate_and_normalise(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc,
+                                          orderC, mode, workspace, workspace_bytes, &probe);
+  int first_bad = base < 0 ? renumber[-base] : 0;  // the lowest-numbered invalid argument wins
+  auto also = [&](int number, bool bad) {
+    if (bad && (first_bad == 0 || number < first_bad)) first_bad = number;
+  };
+  also(7, strideA < 0);
+  also(11, strideB < 0);
+  also(15, strideC < 0);
+  also(16, batch < 0 || batch > 65535);
+  if (first_bad) return -first_bad;
+  Batch b;
+  b.count = batch;
+  b.stride_a = strideA;
+  b.stride_b = strideB;
+  b.stride_c = strideC;
+  return run(0, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+             workspace, workspace_bytes, stream, b);
 }
 
 // Dequantised output (paper Section 7.3).  Same arguments and numbering as the
@@ -345,8 +388,9 @@ const char *mipgemm_strerror(int code) {
       "invalid argument 12 (orderC)", "invalid argument 13 (mode)",
       "invalid argument 14 (workspace is null)",
       "invalid argument 15 (workspace_bytes too small)", "invalid argument 16 (stream)",
-      "invalid argument 17 (scale is not finite)"};
-  if (code <= 0 && code >= -17) return args[-code];
+      "invalid argument 17 (scale is not finite)", "invalid argument 18", "invalid argument 19",
+      "invalid argument 20"};
+  if (code <= 0 && code >= -20) return args[-code];
   if (code > 0) return hipGetErrorString(static_cast<hipError_t>(code));
   return "unknown mipgemm error code";
 }

@@ -200,3 +200,27 @@ def test_conv_path_choice_and_workspace(M):
     assert name(0, 8, 8, 64, 16, 3, 3, 1, 1) == "none"
     assert name(2, 8, 8, 64, 16, 13, 3, 1, 1) == "invalid"
     assert ws(2, 8, 8, 64, 16, 13, 3, 1, 1) == 0
+
+
+def test_batched_entry_point_validation(M):
+    def call_b(m=4, n=5, k=6, A=4096, lda=6, oa=0, sa=24, B=4096, ldb=5, ob=0, sb=30, C=4096, ldc=5,
+               oc=0, sc=20, batch=3, mode=0):
+        return M.mipgemm_s8s8s32_batched(m, n, k, A, lda, oa, sa, B, ldb, ob, sb, C, ldc, oc, sc,
+                                         batch, mode, None, 0, 0, check=False)
+    assert call_b(m=-1) == -1
+    assert call_b(lda=5) == -5
+    assert call_b(sa=-1) == -7
+    assert call_b(B=0) == -8
+    assert call_b(ob=3) == -10
+    assert call_b(sb=-1) == -11
+    assert call_b(C=0) == -12
+    assert call_b(ldc=4) == -13
+    assert call_b(oc=2) == -14
+    assert call_b(sc=-5) == -15
+    assert call_b(batch=-1) == -16
+    assert call_b(batch=65536) == -16
+    assert call_b(mode=7) == -17
+    assert call_b(sa=-1, lda=5) == -5                 # the lowest-numbered bad argument wins
+    assert call_b(batch=0) == 0                      # nothing to do, nothing launched
+    for code in (-18, -19, -20):
+        assert str(-code) in M.mipgemm_strerror(code)

@@ -399,3 +399,59 @@ def test_calls_replay_from_a_hip_graph(gpu, oracle):
             graph.replay()
             torch.cuda.synchronize()
             assert np.array_equal(dC.cpu().numpy(), want), "replay %d of %s" % (replay, case.name)
+
+
+# ---------------------------------------------------------------------------
+# strided batches: every problem of the batch against the oracle on its own slices
+# ---------------------------------------------------------------------------
+
+def _batched_cases():
+    # (m, n, k, orderA, orderB, orderC, pad, batch, share_a, mode)
+    return [
+        (256, 256, 64, 1, 0, 0, 0, 16, False, 0),      # K^T Q per head (M5 of the encoder block)
+        (64, 256, 256, 0, 0, 0, 0, 16, False, 0),      # V E_1 per head (M7)
+        (100, 37, 51, 0, 1, 0, 3, 3, False, 1),        # unaligned: the register-staged kernel
+        (48, 80, 4096, 0, 0, 0, 0, 2, False, 0),       # few tiles, long k: split k inside a batch
+        (130, 70, 128, 0, 0, 1, 16, 5, False, 1),      # column-major C: roles (and strides) swap
+        (64, 64, 192, 0, 1, 0, 0, 7, True, 0),         # one A for every problem (stride 0)
+        (1, 16, 64, 0, 1, 0, 0, 4, False, 0),
+    ]
+
+
+@pytest.mark.parametrize("variant", ["auto", "simple", "tile64", "dma64", "dma128"])
+@pytest.mark.parametrize("spec", _batched_cases(), ids=lambda s: "x".join(map(str, s)))
+def test_batched_gemm(gpu, oracle, spec, variant):
+    import torch
+    m, n, k, oa, ob, oc, pad, batch, share_a, mode = spec
+    print("batched", spec, variant, flush=True)
+    case = W.Case("batched", 8, 0, m, n, k, orderA=oa, orderB=ob, orderC=oc, pad=pad, mode=mode,
+                  c_dist=("uniform", -1000, 1000), seed=51)
+    sets = [W.materialize(W.Case("batched", 8, z, m, n, k, orderA=oa, orderB=ob, orderC=oc, pad=pad,
+                                 mode=mode, c_dist=("uniform", -1000, 1000), seed=51))
+            for z in range(batch)]
+    gap = 48                                             # sentinel bytes / words between the slices
+    sa = 0 if share_a else sets[0].A.size + gap
+    sb, sc = sets[0].B.size + gap, sets[0].C.size + gap
+    A = np.full(max(sa, sets[0].A.size) * (1 if share_a else batch), 0x5A, dtype=np.int8)
+    B = np.full(sb * batch, 0x5A, dtype=np.int8)
+    C = np.full(sc * batch, 0x5A5A5A5A, dtype=np.int32)
+    want = C.copy()
+    for z, o in enumerate(sets):
+        a = sets[0].A if share_a else o.A
+        if not share_a:
+            A[z * sa:z * sa + a.size] = a
+        elif z == 0:
+            A[:a.size] = a
+        B[z * sb:z * sb + o.B.size] = o.B
+        C[z * sc:z * sc + o.C.size] = o.C
+        w = o.C.copy()
+        oracle.gemm(False, False, m, n, k, a, case.lda, oa, o.B, case.ldb, ob, w, case.ldc, oc, mode)
+        want[z * sc:z * sc + w.size] = w
+    dA = torch.from_numpy(A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(C).cuda()
+    with VariantEnv(variant):
+        gpu.mipgemm_s8s8s32_batched(m, n, k, dA, case.lda, oa, sa, dB, case.ldb, ob, sb,
+                                    dC, case.ldc, oc, sc, batch, mode)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)        # the gaps between the slices included

@@ -290,8 +290,38 @@ def config5() -> List[Case]:
     return out
 
 
+# One encoder block of a BERT-Large-type model as the paper tabulates it (Section 7.2, table
+# "Dimensions of the GEMM operations in the transformer encoder"): d = 1024 embeddings,
+# h = 16 heads, hidden dimension f = 4d, l tokens, b = 1; weights are A, activations B.
+ENCODER_D, ENCODER_H = 1024, 16
+ENCODER_TOKENS = (256, 512, 1024)
+
+
+def encoder_block(l: int):
+    """(case, how many times it runs per block) for the GEMMs of one encoder block on l tokens:
+    M1-M3 the Q, K, V projections, M5 K^T Q and M7 V E_1 per head, M9 the output projection,
+    F11 and F13 the feed-forward pair."""
+    d, h, f = ENCODER_D, ENCODER_H, 4 * ENCODER_D
+    dk = d // h
+    dist = dict(a_dist=("normal", 24.0), b_dist=("normal", 24.0), seed=6)
+    return [
+        (Case("enc%d_M1-M3_%dx%dx%d" % (l, d, l, d), 6, 0, d, l, d, **dist), 3),
+        # (K^i)^T is the d/h x l slice of K seen column-major: l x d/h with lda = l
+        (Case("enc%d_M5_%dx%dx%d" % (l, l, l, dk), 6, 1, l, l, dk, orderA=COL_MAJOR, **dist), h),
+        (Case("enc%d_M7_%dx%dx%d" % (l, dk, l, l), 6, 2, dk, l, l, **dist), h),
+        (Case("enc%d_M9_%dx%dx%d" % (l, d, l, d), 6, 3, d, l, d, **dist), 1),
+        (Case("enc%d_F11_%dx%dx%d" % (l, f, l, d), 6, 4, f, l, d, **dist), 1),
+        (Case("enc%d_F13_%dx%dx%d" % (l, d, l, f), 6, 5, d, l, f, **dist), 1),
+    ]
+
+
+def config6() -> List[Case]:
+    """The encoder-block GEMMs at the shortest sequence the paper uses (parity cases)."""
+    return [case for (case, count) in encoder_block(ENCODER_TOKENS[0])]
+
+
 def all_cases() -> Iterator[Case]:
-    for group in (config1(), config2(), config3(), config4(), config5()):
+    for group in (config1(), config2(), config3(), config4(), config5(), config6()):
         yield from group
 
 
