@@ -455,3 +455,23 @@ def test_batched_gemm(gpu, oracle, spec, variant):
                                     dC, case.ldc, oc, sc, batch, mode)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)        # the gaps between the slices included
+
+
+def test_batched_empty_sums(gpu):
+    """k = 0 in a batch: overwrite zeroes every problem's m x n block and nothing else."""
+    import torch
+    m, n, batch, ldc, sc = 5, 7, 4, 9, 60
+    C = np.full(sc * batch, 0x5A5A5A5A, dtype=np.int32)
+    dC = torch.from_numpy(C.copy()).cuda()
+    z = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    gpu.mipgemm_s8s8s32_batched(m, n, 0, z, 1, 0, 0, z, n, 0, 0, dC, ldc, 0, sc, batch, W.OVERWRITE)
+    torch.cuda.synchronize()
+    want = C.copy()
+    for b in range(batch):
+        for i in range(m):
+            want[b * sc + i * ldc:b * sc + i * ldc + n] = 0
+    assert np.array_equal(dC.cpu().numpy(), want)
+    gpu.mipgemm_s8s8s32_batched(m, n, 0, z, 1, 0, 0, z, n, 0, 0, dC, ldc, 0, sc, batch, W.ACCUMULATE)
+    gpu.mipgemm_s8s8s32_batched(0, n, 8, z, 8, 0, 0, z, n, 0, 0, dC, ldc, 0, sc, batch, W.OVERWRITE)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
