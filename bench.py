@@ -303,6 +303,61 @@ def run_conv_table(M):
                 M.mipgemm_conv_variant_name(*args), moved / t_implicit / 1e3), flush=True)
 
 
+def run_network_table(M):
+    """Every convolution of a ResNet-50-type network (the paper's first workload) through the
+    lowering, all 53 captured into one HIP graph per batch size."""
+    import torch
+    print()
+    print("All 53 convolutions of a ResNet-50 v1.5-type network on 224 x 224 images (23 distinct layers),")
+    print("u8 activations x s8 filters -> s32, each layer on its own synthetic tensors:")
+    print()
+    print("| batch | us, all convolutions | of which the 7 x 7 stem (written-out route) | GMAC | TOPS |")
+    print("|---|---|---|---|---|")
+    layers = W.resnet50_conv_layers()
+    for b in W.CONV_BATCHES:
+        calls, macs, stem_call = [], 0, None
+        for name, geo, count in layers:
+            hi, ci, co, hf, stride, pad = geo
+            image, filt = W.conv_tensors(b, geo)
+            ho = (hi + 2 * pad - hf) // stride + 1
+            dI, dF = torch.from_numpy(image).cuda(), torch.from_numpy(filt.view(np.uint8)).cuda()
+            dO = torch.zeros(b * ho * ho * co, dtype=torch.int32, device="cuda")
+            args = (b, hi, hi, ci, co, hf, hf, stride, pad)
+            need = M.mipgemm_conv_workspace_size(*args)
+            ws = torch.zeros(need, dtype=torch.uint8, device="cuda") if need else None
+            call = (lambda args=args, dF=dF, dI=dI, dO=dO, ws=ws, need=need:
+                    M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=ws,
+                                           workspace_bytes=need))
+            calls += [call] * count
+            macs += count * b * ho * ho * co * ci * hf * hf
+            if name == "stem":
+                stem_call = call
+
+        def timed(fns, repeats):
+            for f in fns:
+                f()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(repeats):
+                    for f in fns:
+                        f()
+            graph.replay()
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(5):
+                graph.replay()
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / (5 * repeats) * 1e3
+
+        total = timed(calls, 2)
+        stem = timed([stem_call], 8)
+        print("| %d | %.0f | %.0f | %.2f | %.1f |" % (b, total, stem, macs / 1e9,
+                                                      2 * macs / total / 1e6), flush=True)
+
+
 def run_pack_table(M):
     """Decode GEMMs on weights as stored (k x n, row-major) and on the same weights packed
     once with k contiguous (mipgemm_pack_b), cold (operand sets rotated over > 600 MB)."""
@@ -439,6 +494,7 @@ def main():
     if args.suite:
         run_suite(M, args)
         run_conv_table(M)
+        run_network_table(M)
         run_pack_table(M)
         run_encoder_table(M)
         return

@@ -126,6 +126,24 @@ def test_conv_batch_32_layer_in_full(gpu, oracle):
     assert np.array_equal(got, want)
 
 
+def _network_layers():
+    import workloads as W
+    return [(name, geo) for (name, geo, count) in W.resnet50_conv_layers()]
+
+
+@pytest.mark.parametrize("name,geo", _network_layers(), ids=lambda x: x if isinstance(x, str) else None)
+def test_every_distinct_layer_of_the_network(gpu, oracle, name, geo):
+    """The 23 distinct convolutions of the ResNet-50-type network, one image, bit for bit."""
+    import workloads as W
+    hi, ci, co, hf, stride, pad = geo
+    shape = (1, hi, hi, ci, co, hf, hf, stride, pad)
+    print("layer", name, shape, flush=True)
+    image, filt = W.conv_tensors(1, geo)
+    want = oracle.conv_direct(image, filt, stride, pad)
+    got = run_conv(gpu, shape, image, filt, np.full(want.shape, -3, dtype=np.int32), 0)
+    assert np.array_equal(got, want)
+
+
 IM2COL_SHAPES = [(2, 9, 8, 16, 3, 3, 1, 1), (1, 14, 14, 64, 3, 3, 2, 1), (3, 7, 7, 48, 1, 1, 1, 0),
                  (1, 12, 10, 3, 7, 7, 2, 3), (2, 6, 5, 5, 2, 3, 1, 1), (1, 20, 20, 32, 5, 5, 3, 2),
                  (1, 40, 40, 512, 3, 3, 1, 1)]

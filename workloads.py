@@ -199,6 +199,30 @@ CONV_GEOMETRY = ((56, 64, 64, 3, 1, 1), (28, 128, 128, 3, 1, 1), (14, 256, 256, 
 CONV_FIRST_LAYER = (224, 3, 64, 7, 2, 3)
 
 
+def resnet50_conv_layers():
+    """Every convolution of a ResNet-50 v1.5-type network on 224 x 224 images, the paper's first
+    workload (Section 7.2: 49 convolutions in 16 bottleneck blocks plus the shortcut projections
+    and the stem), as (name, geometry, how many times it occurs) with geometry = (hi, ci, co, hf,
+    stride, pad); identical layers are merged as the paper merges them."""
+    layers = [("stem", (224, 3, 64, 7, 2, 3))]
+    size, cin = 56, 64                                   # after the stem's 3 x 3 / 2 pooling
+    for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+        for blk in range(blocks):
+            stride = 2 if (blk == 0 and stage > 1) else 1   # v1.5: the 3 x 3 carries the stride
+            tag = "s%db%d" % (stage, blk + 1)
+            layers.append((tag + "_1x1a", (size, cin, width, 1, 1, 0)))
+            layers.append((tag + "_3x3", (size, width, width, 3, stride, 1)))
+            out = size // stride
+            layers.append((tag + "_1x1b", (out, width, 4 * width, 1, 1, 0)))
+            if blk == 0:
+                layers.append((tag + "_proj", (size, cin, 4 * width, 1, stride, 0)))
+            size, cin = out, 4 * width
+    merged = {}
+    for name, geo in layers:
+        merged.setdefault(geo, [name, 0])[1] += 1
+    return [(v[0], geo, v[1]) for geo, v in merged.items()]
+
+
 def conv_tensors(b, geometry, seed=2):
     """Synthetic image tensor (uint8, b x hi x wi x ci) and filters (int8, co x hf x wf x ci)
     with the value distributions of the conv-as-GEMM workload."""
