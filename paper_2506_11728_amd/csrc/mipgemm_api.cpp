@@ -121,8 +121,11 @@ Plan choose_plan(const Problem &p) {
     };
     if (p.m <= 64 && p.n > 128) sh = enough(SHAPE_64X256, p.m) ? SHAPE_64X256 : SHAPE_64;
     else if (p.n <= 64 && p.m > 128) sh = enough(SHAPE_256X64, p.n) ? SHAPE_256X64 : SHAPE_64;
-    else if (tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
-    else if (tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
+    // A large tile buys operand reuse, which only a long k turns into time: with a short
+    // k the problem is a stream that ends in the write of C, and small tiles, several
+    // workgroups to a compute unit, overlap that write with the next tile's loads.
+    else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
+    else if (p.k >= 512 && tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
     // A few rows of A against a k-contiguous B is one pass over B with nothing to
