@@ -57,6 +57,10 @@ def load_library() -> ctypes.CDLL:
                 raise ImportError(
                     "libmipgemm.so is not built (%s); run `python -m paper_2506_11728_amd.build`. "
                     "There is no CPU fallback." % _LIB_PATH)
+            # PyTorch owns device memory and streams here and ships its own HIP runtime: it
+            # must be the one in the process before the library binds to it (loaded the other
+            # way round, the two runtimes disagree and launches fail with "no device")
+            import torch  # noqa: F401
             lib = ctypes.CDLL(_LIB_PATH)
             for name in ("mipgemm_s8s8s32", "mipgemm_u8s8s32", "mipgemm_s8u8s32"):
                 fn = getattr(lib, name)

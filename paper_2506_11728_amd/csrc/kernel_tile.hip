@@ -218,6 +218,8 @@ hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t 
     case SHAPE_64: return launch_cfg<64, 64>(p, splits, s);
     case SHAPE_64X256: return launch_cfg<64, 256>(p, splits, s);
     case SHAPE_256X64: return launch_cfg<256, 64>(p, splits, s);
+    case SHAPE_64X128: return launch_cfg<64, 128>(p, splits, s);
+    case SHAPE_128X64: return launch_cfg<128, 64>(p, splits, s);
     default: return hipErrorInvalidValue;
   }
 }

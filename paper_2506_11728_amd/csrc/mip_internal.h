@@ -45,7 +45,9 @@ struct Problem {
 };
 
 // Workgroup tile of the MFMA kernels (rows x columns of C).
-enum Shape { SHAPE_256, SHAPE_128, SHAPE_64, SHAPE_64X256, SHAPE_256X64, SHAPE_COUNT };
+enum Shape {
+  SHAPE_256, SHAPE_128, SHAPE_64, SHAPE_64X256, SHAPE_256X64, SHAPE_64X128, SHAPE_128X64, SHAPE_COUNT
+};
 
 enum Kind {
   KIND_NONE = 0,  // nothing to launch (m == 0 or n == 0, or k == 0 with accumulate)
@@ -84,6 +86,8 @@ MIP_DECLARE_DMA(128, 128)
 MIP_DECLARE_DMA(64, 64)
 MIP_DECLARE_DMA(64, 256)
 MIP_DECLARE_DMA(256, 64)
+MIP_DECLARE_DMA(64, 128)
+MIP_DECLARE_DMA(128, 64)
 #undef MIP_DECLARE_DMA
 
 // The lowered matrix of a convolution written out: row n = (g, oy, ox) of M (pitch ldm

@@ -17,6 +17,8 @@ bool dma_eligible(const Problem &p, Shape shape) {
     case SHAPE_64: return dma_eligible_64x64(p);
     case SHAPE_64X256: return dma_eligible_64x256(p);
     case SHAPE_256X64: return dma_eligible_256x64(p);
+    case SHAPE_64X128: return dma_eligible_64x128(p);
+    case SHAPE_128X64: return dma_eligible_128x64(p);
     default: return false;
   }
 }
@@ -28,19 +30,24 @@ hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s) 
     case SHAPE_64: return launch_dma_64x64(p, splits, s);
     case SHAPE_64X256: return launch_dma_64x256(p, splits, s);
     case SHAPE_256X64: return launch_dma_256x64(p, splits, s);
+    case SHAPE_64X128: return launch_dma_64x128(p, splits, s);
+    case SHAPE_128X64: return launch_dma_128x64(p, splits, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-static const char *const kShapeNames[SHAPE_COUNT] = {"256", "128", "64", "64x256", "256x64"};
-static const int64_t kShapeRows[SHAPE_COUNT] = {256, 128, 64, 64, 256};
-static const int64_t kShapeCols[SHAPE_COUNT] = {256, 128, 64, 256, 64};
+static const char *const kShapeNames[SHAPE_COUNT] = {"256", "128", "64", "64x256", "256x64",
+                                                     "64x128", "128x64"};
+static const int64_t kShapeRows[SHAPE_COUNT] = {256, 128, 64, 64, 256, 64, 128};
+static const int64_t kShapeCols[SHAPE_COUNT] = {256, 128, 64, 256, 64, 128, 64};
 
 const char *plan_name(const Plan &plan) {
   static const char *const staged[SHAPE_COUNT] = {"mfma_tile256", "mfma_tile128", "mfma_tile64",
-                                                  "mfma_tile64x256", "mfma_tile256x64"};
+                                                  "mfma_tile64x256", "mfma_tile256x64",
+                                                  "mfma_tile64x128", "mfma_tile128x64"};
   static const char *const dma[SHAPE_COUNT] = {"mfma_dma256", "mfma_dma128", "mfma_dma64",
-                                               "mfma_dma64x256", "mfma_dma256x64"};
+                                               "mfma_dma64x256", "mfma_dma256x64",
+                                               "mfma_dma64x128", "mfma_dma128x64"};
   switch (plan.kind) {
     case KIND_NONE: return "none";
     case KIND_FILL: return "fill_zero";
@@ -56,7 +63,7 @@ const char *plan_name(const Plan &plan) {
 // MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
 // "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
-// 256, 128, 64, 64x256, 256x64.  A dma variant only applies to problems it is
+// 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
 // eligible for; others fall back to the staged kernel of the same shape.
 // MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
 static bool forced_plan(const Problem &p, Plan *plan) {
@@ -124,7 +131,14 @@ Plan choose_plan(const Problem &p) {
     // A large tile buys operand reuse, which only a long k turns into time: with a short
     // k the problem is a stream that ends in the write of C, and small tiles, several
     // workgroups to a compute unit, overlap that write with the next tile's loads.
+    // Between 128 x 128 (too few tiles) and 64 x 64 (64 operations per operand byte,
+    // which the L2 caches cannot feed) sit the 8192-element tiles, long side along the
+    // longer dimension of C.
     else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
+    else if (p.k >= 512 && tile_count(p, SHAPE_128) >= kComputeUnits) sh = SHAPE_128;
+    else if (p.k >= 512 && tile_count(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128) >= kComputeUnits &&
+             dma_eligible(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128))
+      sh = p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128;  // (measured on the direct-to-LDS kernels only)
     else if (p.k >= 512 && tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
@@ -503,7 +517,8 @@ const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t
       MIP_NAME("mfma_dma256"), MIP_NAME("mfma_dma128"), MIP_NAME("mfma_dma64"),
       MIP_NAME("mfma_dma64x256"), MIP_NAME("mfma_dma256x64"), MIP_NAME("mfma_tile256"),
       MIP_NAME("mfma_tile128"), MIP_NAME("mfma_tile64"), MIP_NAME("mfma_tile64x256"),
-      MIP_NAME("mfma_tile256x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_slab16"),
+      MIP_NAME("mfma_tile256x64"), MIP_NAME("mfma_dma64x128"), MIP_NAME("mfma_dma128x64"),
+      MIP_NAME("mfma_tile64x128"), MIP_NAME("mfma_tile128x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_slab16"),
       MIP_NAME("mfma_slab32"), MIP_NAME("simple")};
 #undef MIP_NAME
   const char *base = mip::plan_name(plan);

@@ -129,7 +129,7 @@ def test_variant_choice(M):
     # column-major C swaps the operand roles
     assert name(64, 100352, 576, 576, 0, 100352, 0, 64, 1) == "mfma_dma256x64"
     # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
-    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma64x128"
     # k not a multiple of 64 does not
     assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
@@ -191,7 +191,7 @@ def test_conv_path_choice_and_workspace(M):
     # channel counts that are multiples of 64 are gathered inside the GEMM kernel: no workspace
     assert name(32, 56, 56, 64, 64, 3, 3, 1, 1) == "implicit:mfma_dma256x64"
     assert ws(32, 56, 56, 64, 64, 3, 3, 1, 1) == 0
-    assert name(32, 28, 28, 128, 128, 3, 3, 1, 1) == "implicit:mfma_dma128"
+    assert name(32, 28, 28, 128, 128, 3, 3, 1, 1) == "implicit:mfma_dma128x64"
     assert name(1, 7, 7, 512, 2048, 1, 1, 1, 0).startswith("implicit:")
     # the 3-channel first layer is written out: n rows of k bytes rounded up to 16
     assert name(2, 64, 48, 3, 64, 7, 7, 2, 3).startswith("im2col+")

@@ -92,7 +92,8 @@ def test_conv_matches_the_direct_convolution(gpu, oracle, shape, mode, path):
 
 
 @pytest.mark.parametrize("variant,splits", [("dma256", None), ("dma128", None), ("dma64", 3),
-                                            ("dma64x256", None), ("dma256x64", 2), ("dma128", 5)])
+                                            ("dma64x256", None), ("dma256x64", 2), ("dma128", 5),
+                                            ("dma128x64", None), ("dma64x128", 2)])
 @pytest.mark.parametrize("shape", [(2, 28, 28, 128, 128, 3, 3, 1, 1), (1, 17, 23, 64, 96, 3, 5, 2, 2),
                                    (4, 7, 7, 512, 512, 3, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))

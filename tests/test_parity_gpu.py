@@ -13,7 +13,8 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 
 VARIANTS = ["auto", "simple", "tile256", "tile128", "tile64", "tile64x256", "tile256x64",
-            "dma256", "dma128", "dma64", "dma64x256", "dma256x64"]
+            "dma256", "dma128", "dma64", "dma64x256", "dma256x64", "dma64x128", "dma128x64",
+            "tile64x128", "tile128x64"]
 
 
 @pytest.fixture(scope="module")
@@ -108,7 +109,7 @@ SPLIT_CASES = [c for c in W.all_cases() if c.k >= 513 and _ops_count(c) <= 2.5e9
 
 @pytest.mark.parametrize("variant,splits", [("tile64", 3), ("tile64x256", 7), ("tile256x64", 2),
                                             ("tile128", 5), ("tile64", 1000), ("dma64", 3),
-                                            ("dma64x256", 7), ("dma256x64", 2), ("dma128", 5),
+                                            ("dma64x256", 7), ("dma256x64", 2), ("dma128", 5), ("dma64x128", 3), ("tile128x64", 2),
                                             ("dma256", 2), ("dma64", 1000)])
 @pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: c.name)
 def test_split_k_is_exact(gpu, oracle, case, variant, splits):
