@@ -1,0 +1,193 @@
+// Which kernel serves which problem: eligibility, tile shape, k ranges.  Host only.
+#include <cstdlib>
+#include <cstring>
+
+#include "mip_internal.h"
+
+namespace mip {
+
+bool dma_eligible(const Problem &p, Shape shape) {
+  switch (shape) {
+    case SHAPE_256: return dma_eligible_256x256(p);
+    case SHAPE_128: return dma_eligible_128x128(p);
+    case SHAPE_64: return dma_eligible_64x64(p);
+    case SHAPE_64X256: return dma_eligible_64x256(p);
+    case SHAPE_256X64: return dma_eligible_256x64(p);
+    case SHAPE_64X128: return dma_eligible_64x128(p);
+    case SHAPE_128X64: return dma_eligible_128x64(p);
+    default: return false;
+  }
+}
+
+hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s) {
+  switch (shape) {
+    case SHAPE_256: return launch_dma_256x256(p, splits, s);
+    case SHAPE_128: return launch_dma_128x128(p, splits, s);
+    case SHAPE_64: return launch_dma_64x64(p, splits, s);
+    case SHAPE_64X256: return launch_dma_64x256(p, splits, s);
+    case SHAPE_256X64: return launch_dma_256x64(p, splits, s);
+    case SHAPE_64X128: return launch_dma_64x128(p, splits, s);
+    case SHAPE_128X64: return launch_dma_128x64(p, splits, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+static const char *const kShapeNames[SHAPE_COUNT] = {"256", "128", "64", "64x256", "256x64",
+                                                     "64x128", "128x64"};
+static const int64_t kShapeRows[SHAPE_COUNT] = {256, 128, 64, 64, 256, 64, 128};
+static const int64_t kShapeCols[SHAPE_COUNT] = {256, 128, 64, 256, 64, 128, 64};
+
+const char *plan_name(const Plan &plan) {
+  static const char *const staged[SHAPE_COUNT] = {"mfma_tile256", "mfma_tile128", "mfma_tile64",
+                                                  "mfma_tile64x256", "mfma_tile256x64",
+                                                  "mfma_tile64x128", "mfma_tile128x64"};
+  static const char *const dma[SHAPE_COUNT] = {"mfma_dma256", "mfma_dma128", "mfma_dma64",
+                                               "mfma_dma64x256", "mfma_dma256x64",
+                                               "mfma_dma64x128", "mfma_dma128x64"};
+  switch (plan.kind) {
+    case KIND_NONE: return "none";
+    case KIND_FILL: return "fill_zero";
+    case KIND_SIMPLE: return "simple";
+    case KIND_STAGED: return staged[plan.shape];
+    case KIND_DMA: return dma[plan.shape];
+    case KIND_DMA_K128: return "mfma_dma256_k128";
+    case KIND_SLAB: return plan.splits == 2 ? "mfma_slab32" : "mfma_slab16";
+    default: return "?";
+  }
+}
+
+// MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
+// "slab16" / "slab32" (the skinny-m kernel with that slab width),
+// "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
+// 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
+// eligible for; others fall back to the staged kernel of the same shape.
+// MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
+static bool forced_plan(const Problem &p, Plan *plan) {
+  const char *e = std::getenv("MIPGEMM_VARIANT");
+  if (!e || !*e) return false;
+  if (!std::strcmp(e, "simple")) { *plan = {KIND_SIMPLE, SHAPE_64, 1}; return true; }
+  if (!std::strcmp(e, "dma256k128")) {
+    if (!dma_k128_eligible(p)) return false;
+    *plan = {KIND_DMA_K128, SHAPE_256, 1};
+    return true;
+  }
+  if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32")) {
+    const int nt = e[4] == '3' ? 2 : 1;
+    if (!slab_eligible(p, nt)) return false;
+    *plan = {KIND_SLAB, SHAPE_64, nt};
+    return true;
+  }
+  const bool want_dma = !std::strncmp(e, "dma", 3);
+  if (!want_dma && std::strncmp(e, "tile", 4)) return false;
+  const char *shape = e + (want_dma ? 3 : 4);
+  for (int i = 0; i < SHAPE_COUNT; ++i)
+    if (!std::strcmp(shape, kShapeNames[i])) {
+      const Shape sh = static_cast<Shape>(i);
+      *plan = {want_dma && dma_eligible(p, sh) ? KIND_DMA : KIND_STAGED, sh, 1};
+      return true;
+    }
+  return false;
+}
+
+static int forced_splits() {
+  const char *e = std::getenv("MIPGEMM_SPLITK");
+  if (!e || !*e) return 0;
+  int v = std::atoi(e);
+  return v > 0 ? v : 0;
+}
+
+// over all problems of a batch: what the chip sees is their sum
+static int64_t tile_count(const Problem &p, Shape s) {
+  return ((p.m + kShapeRows[s] - 1) / kShapeRows[s]) * ((p.n + kShapeCols[s] - 1) / kShapeCols[s]) *
+         (p.batch > 1 ? p.batch : 1);
+}
+
+Plan choose_plan(const Problem &p) {
+  constexpr int64_t kComputeUnits = 256;
+  if (p.m == 0 || p.n == 0) return {KIND_NONE, SHAPE_64, 1};
+  if (p.k == 0) return {p.accumulate ? KIND_NONE : KIND_FILL, SHAPE_64, 1};
+  Plan plan;
+  if (!forced_plan(p, &plan)) {
+    // The largest tile that still gives most compute units a workgroup; a
+    // matrix that is short in one dimension takes a tile that is short there too.
+    // A short side (a few tokens, a few output channels) makes the problem a
+    // stream over the long operand: wide tiles only when the long side alone
+    // fills the chip, else 64 x 64 tiles, which give four times as many workgroups.
+    // With at most 16 rows the atomics of split k are cheap, and wide tiles (whole
+    // cache lines of a row-major operand) win as soon as k is long enough to cut
+    // into one range of 8 blocks or more per compute unit.
+    Shape sh;
+    const int64_t ranges = p.k / 512 > 1 ? p.k / 512 : 1;
+    auto enough = [&](Shape wide, int64_t short_side) {
+      const int64_t t = tile_count(p, wide);
+      return t >= kComputeUnits || (short_side <= 16 && !p.out_float && t * ranges >= kComputeUnits);
+    };
+    if (p.m <= 64 && p.n > 128) sh = enough(SHAPE_64X256, p.m) ? SHAPE_64X256 : SHAPE_64;
+    else if (p.n <= 64 && p.m > 128) sh = enough(SHAPE_256X64, p.n) ? SHAPE_256X64 : SHAPE_64;
+    // A large tile buys operand reuse, which only a long k turns into time: with a short
+    // k the problem is a stream that ends in the write of C, and small tiles, several
+    // workgroups to a compute unit, overlap that write with the next tile's loads.
+    // Between 128 x 128 (too few tiles) and 64 x 64 (64 operations per operand byte,
+    // which the L2 caches cannot feed) sit the 8192-element tiles, long side along the
+    // longer dimension of C.
+    else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
+    else if (p.k >= 512 && tile_count(p, SHAPE_128) >= kComputeUnits) sh = SHAPE_128;
+    else if (p.k >= 512 && tile_count(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128) >= kComputeUnits &&
+             dma_eligible(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128))
+      sh = p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128;  // (measured on the direct-to-LDS kernels only)
+    else if (p.k >= 512 && tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
+    else sh = SHAPE_64;
+    // deep k blocks pay off once the k loop is long enough to amortise their prologue
+    // A few rows of A against a k-contiguous B is one pass over B with nothing to
+    // share: a workgroup per 16-column slab does it in one launch, without atomics.
+    // (A row-major B would reach each slab in 16-byte pieces of its cache lines,
+    // which the tiled kernels, with their 64-byte pieces and split k, do better.)
+    // The same kernel serves short k, where the tiled kernels cannot split k
+    // and 64-column tiles leave most compute units idle.
+    const bool slab_ok = p.m <= 64 && slab_eligible(p, 1);
+    if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192) plan = {KIND_SLAB, SHAPE_64, 1};
+    else if (slab_ok && p.k < 1024 && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
+      plan = {KIND_SLAB, SHAPE_64, 1};
+    else if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
+    // the register-staged kernel keeps its operands in flight in VGPRs, which a
+    // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128
+    else plan = {KIND_STAGED, sh == SHAPE_256 ? SHAPE_128 : sh, 1};
+  }
+  if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
+    plan.splits = p.out_float ? 1 : forced_splits();  // float sums are not combined out of order
+    if (plan.splits == 0) {
+      // Too few tiles to fill the chip: cut k into ranges of at least 512 (128 for the
+      // register-staged kernel) until
+      // there is about one workgroup per compute unit.  Every range adds its
+      // partial sums into C with atomics (and an overwrite needs C zeroed first),
+      // so short problems (few rows of C per byte of operand) may split further
+      // than tall ones.
+      const int64_t tiles = tile_count(p, plan.shape);
+      const int64_t nkt = (p.k + 63) / 64;
+      plan.splits = 1;
+      // a stream over one long operand (short side of a few rows) is bound by memory
+      // latency: it wants two workgroups per compute unit in flight
+      const int64_t short_side = p.m < p.n ? p.m : p.n;
+      // (of the 64 x 64 tiles, that is: the wide ones fill a compute unit's LDS alone,
+      // and one workgroup too many would cost a second round)
+      const bool small_tile = plan.shape == SHAPE_64;
+      const int64_t target = short_side <= 16 && small_tile ? 2 * kComputeUnits : kComputeUnits;
+      if (tiles < target / 2 && !p.out_float) {
+        const int64_t want = short_side <= 16 && small_tile ? (target + tiles - 1) / tiles : target / tiles;
+        // the register-staged kernel has a shallow pipeline with little to amortise:
+        // ranges of two k blocks already pay, and it tolerates twice the atomics
+        const bool staged = plan.kind == KIND_STAGED;
+        const int64_t shortest = staged ? 2 : 8;  // k blocks per range
+        const int64_t most = nkt / shortest > 1 ? nkt / shortest : 1;
+        const int64_t atomics_ok = (short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4)) * (staged ? 2 : 1);
+        int64_t sp = want < most ? want : most;
+        if (sp > atomics_ok) sp = atomics_ok;
+        plan.splits = (int)sp;
+      }
+    }
+  }
+  return plan;
+}
+
+}  // namespace mip

@@ -1,0 +1,201 @@
+// C-ABI entry points of the steps around the GEMM: the convolution lowering (paper Section
+// 7.2) and the pre-packing of a weight matrix (Section 4.1).  Host only.
+#include <cstdlib>
+#include <cstring>
+
+#include "api_internal.h"
+
+using mip::Problem;
+using mip::order_ok;
+
+// ---------------------------------------------------------------------------
+// convolution by lowering (paper Section 7.2)
+// ---------------------------------------------------------------------------
+namespace {
+
+struct ConvCall {
+  mip::ConvGeom geom;
+  int64_t rows;  // b * h_o * w_o: the GEMM's n
+  int64_t k;     // h_f * w_f * c_i
+  int64_t ldm;   // row pitch of a written-out augmented matrix
+};
+
+// 0 and `out`, or the negative number of the first bad size argument; has_co is false for
+// the entry point that has no c_o (then hf .. pad are arguments 5 .. 8 instead of 6 .. 9)
+int conv_sizes(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, bool has_co, int64_t hf,
+               int64_t wf, int64_t stride, int64_t pad, ConvCall *out) {
+  const int64_t lim = (int64_t)1 << 31;
+  const int shift = has_co ? 1 : 0;
+  if (b < 0 || b >= lim) return -1;
+  if (hi < 1 || hi >= lim) return -2;
+  if (wi < 1 || wi >= lim) return -3;
+  if (ci < 1 || ci >= lim) return -4;
+  if (has_co && (co < 0 || co >= lim)) return -5;
+  if (hf < 1 || hf >= lim) return -(5 + shift);
+  if (wf < 1 || wf >= lim) return -(6 + shift);
+  if (stride < 1 || stride >= lim) return -(7 + shift);
+  if (pad < 0 || pad >= lim) return -(8 + shift);
+  if (hf > hi + 2 * pad) return -(5 + shift);  // the filter must fit the padded image
+  if (wf > wi + 2 * pad) return -(6 + shift);
+  const int64_t ho = (hi + 2 * pad - hf) / stride + 1, wo = (wi + 2 * pad - wf) / stride + 1;
+  // products checked step by step so that none overflows 64 bits
+  if (hi * wi >= lim || hi * wi * ci >= lim || (b > 0 && hi * wi * ci >= lim / b)) return -1;
+  if (ho >= lim || wo >= lim) return -(8 + shift);  // only an absurd padding gets here
+  if (ho * wo >= lim || (b > 0 && ho * wo >= lim / b)) return -1;
+  if (hf * wf >= lim || hf * wf * ci >= lim) return -4;
+  out->geom = mip::ConvGeom{(int)hi, (int)wi, (int)ci, (int)wf, (int)ho, (int)wo, (int)stride, (int)pad};
+  out->rows = b * ho * wo;
+  out->k = hf * wf * ci;
+  out->ldm = (out->k + 15) / 16 * 16;
+  return 0;
+}
+
+// the GEMM the convolution is lowered to, in the kernels' terms: the row-major C is O
+// seen as (b h_o w_o) x c_o, its A the augmented matrix, its B the filters (k contiguous)
+Problem conv_problem(const ConvCall &c, int64_t co, const void *F, const void *I, void *O, int mode,
+                     bool implicit, const void *M, int out_float = 0, float scale = 1.0f) {
+  Problem p;
+  p.m = c.rows; p.n = co; p.k = c.k;
+  p.A = implicit ? I : M; p.a_sm = implicit ? c.k : c.ldm; p.a_sk = 1; p.a_unsigned = 1;
+  p.B = F; p.b_sk = 1; p.b_sn = c.k; p.b_unsigned = 0;
+  p.C = static_cast<int32_t *>(O); p.ldc = co;
+  p.accumulate = mode == MIPGEMM_ACCUMULATE;
+  p.out_float = out_float; p.scale = scale;
+  p.conv = nullptr;
+  return p;
+}
+
+// whether the gathering kernel serves this convolution, and with which plan
+bool conv_implicit_plan(const ConvCall &c, Problem p, mip::Plan *plan) {
+  const char *e = std::getenv("MIPGEMM_CONV");  // "im2col" pins the written-out path (tests, tuning)
+  if (e && !std::strcmp(e, "im2col")) return false;
+  if (p.m == 0 || p.n == 0) return false;
+  p.conv = &c.geom;
+  *plan = mip::choose_plan(p);
+  return plan->kind == mip::KIND_DMA;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
+                                   int64_t hf, int64_t wf, int64_t stride, int64_t pad) {
+  ConvCall c;
+  if (conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c) != 0) return 0;
+  if (c.rows == 0 || co == 0) return 0;
+  const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
+  mip::Plan plan;
+  if (conv_implicit_plan(c, conv_problem(c, co, fake, fake, const_cast<void *>(fake),
+                                         MIPGEMM_OVERWRITE, true, nullptr), &plan))
+    return 0;
+  return static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
+}
+
+const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
+                                      int64_t hf, int64_t wf, int64_t stride, int64_t pad) {
+  ConvCall c;
+  if (conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c) != 0) return "invalid";
+  if (c.rows == 0 || co == 0) return "none";
+  const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
+  mip::Plan plan;
+  const bool implicit = conv_implicit_plan(
+      c, conv_problem(c, co, fake, fake, const_cast<void *>(fake), MIPGEMM_OVERWRITE, true, nullptr),
+      &plan);
+  if (!implicit)
+    plan = mip::choose_plan(conv_problem(c, co, fake, fake, const_cast<void *>(fake),
+                                         MIPGEMM_OVERWRITE, false, fake));
+  // static strings: every kernel variant name with either prefix
+#define MIP_NAME(x) {x, "implicit:" x, "im2col+" x}
+  static const char *const names[][3] = {
+      MIP_NAME("mfma_dma256"), MIP_NAME("mfma_dma128"), MIP_NAME("mfma_dma64"),
+      MIP_NAME("mfma_dma64x256"), MIP_NAME("mfma_dma256x64"), MIP_NAME("mfma_tile256"),
+      MIP_NAME("mfma_tile128"), MIP_NAME("mfma_tile64"), MIP_NAME("mfma_tile64x256"),
+      MIP_NAME("mfma_tile256x64"), MIP_NAME("mfma_dma64x128"), MIP_NAME("mfma_dma128x64"),
+      MIP_NAME("mfma_tile64x128"), MIP_NAME("mfma_tile128x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_slab16"),
+      MIP_NAME("mfma_slab32"), MIP_NAME("simple")};
+#undef MIP_NAME
+  const char *base = mip::plan_name(plan);
+  for (const auto &n : names)
+    if (!std::strcmp(n[0], base)) return n[implicit ? 1 : 2];
+  return implicit ? "implicit" : "im2col";
+}
+
+int mipgemm_im2col_u8(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t hf, int64_t wf,
+                      int64_t stride, int64_t pad, const uint8_t *I, uint8_t *M, int64_t ldm,
+                      void *stream) {
+  ConvCall c;
+  int rc = conv_sizes(b, hi, wi, ci, 0, false, hf, wf, stride, pad, &c);
+  if (rc != 0) return rc;
+  if (!I && b > 0) return -9;
+  if (!M && c.rows > 0) return -10;
+  if (ldm < c.k || ldm > MIPGEMM_MAX_DIM) return -11;
+  return static_cast<int>(mip::launch_im2col(c.geom, c.rows, c.k, I, M, ldm,
+                                             static_cast<hipStream_t>(stream)));
+}
+
+static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                    int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad, const int8_t *F,
+                    const uint8_t *I, void *O, int mode, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+  ConvCall c;
+  int rc = conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c);
+  if (rc != 0) return rc;
+  if (!F && co > 0) return -10;
+  if (!I && b > 0) return -11;
+  if (!O && c.rows > 0 && co > 0) return -12;
+  if (mode != MIPGEMM_OVERWRITE && mode != MIPGEMM_ACCUMULATE) return -13;
+  if (out_float && (!(scale == scale) || scale - scale != 0.0f)) return -17;  // NaN or infinity
+  if (c.rows == 0 || co == 0) return 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  mip::Plan plan;
+  Problem p = conv_problem(c, co, F, I, O, mode, true, nullptr, out_float, scale);
+  if (conv_implicit_plan(c, p, &plan)) {
+    p.conv = &c.geom;
+    return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
+  }
+  const size_t need = static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
+  if (!workspace) return -14;
+  if (workspace_bytes < need) return -15;
+  hipError_t e = mip::launch_im2col(c.geom, c.rows, c.k, I, static_cast<uint8_t *>(workspace), c.ldm, s);
+  if (e != hipSuccess) return static_cast<int>(e);
+  // F is A (c_o x k, row-major), the matrix just written is B (k x n, column-major),
+  // O is C (column-major, ldc = c_o)
+  return mip::run_gemm(0, 1, out_float, scale, co, c.rows, c.k, F, c.k, MIPGEMM_ROW_MAJOR, workspace, c.ldm,
+             MIPGEMM_COL_MAJOR, O, co, MIPGEMM_COL_MAJOR, mode, nullptr, 0, stream);
+}
+
+int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
+                         int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
+                         int32_t *O, int mode, void *workspace, size_t workspace_bytes,
+                         void *stream) {
+  return run_conv(0, 1.0f, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream);
+}
+
+int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
+                         int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
+                         float *O, int mode, void *workspace, size_t workspace_bytes, void *stream,
+                         float scale) {
+  return run_conv(1, scale, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream);
+}
+
+int mipgemm_pack_b(int64_t k, int64_t n, const void *B, int64_t ldb, int orderB, void *P,
+                   int64_t ldp, void *stream) {
+  if (k < 0 || k > MIPGEMM_MAX_DIM) return -1;
+  if (n < 0 || n > MIPGEMM_MAX_DIM) return -2;
+  if (!B && k > 0 && n > 0) return -3;
+  if (!order_ok(orderB)) return -5;
+  {
+    const int64_t need = orderB == MIPGEMM_ROW_MAJOR ? n : k;
+    if (ldb < (need > 1 ? need : 1) || ldb > MIPGEMM_MAX_DIM) return -4;
+  }
+  if (!P && k > 0 && n > 0) return -6;
+  if (ldp < (k > 1 ? k : 1) || ldp > MIPGEMM_MAX_DIM) return -7;
+  return static_cast<int>(mip::launch_pack_b(k, n, static_cast<const uint8_t *>(B), ldb,
+                                             orderB == MIPGEMM_COL_MAJOR, static_cast<uint8_t *>(P),
+                                             ldp, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"
