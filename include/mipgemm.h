@@ -130,6 +130,30 @@ int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k,
                             void *stream);
 
 /*
+ * The same strided batch with one unsigned operand, as mipgemm_u8s8s32 and
+ * mipgemm_s8u8s32 are to mipgemm_s8s8s32 (Section 5.2 for the u8 x s8 pair): in the
+ * encoder block the attention weights E_1 after the softmax are non-negative and
+ * can be quantized to uint8 (Section 7.3 takes activations at face value), so
+ * V E_1 per head is the s8 x u8 form.  Arguments, numbering, limits and errors
+ * are those of mipgemm_s8s8s32_batched.
+ */
+int mipgemm_u8s8s32_batched(int64_t m, int64_t n, int64_t k,
+                            const uint8_t *A, int64_t lda, int orderA, int64_t strideA,
+                            const int8_t *B, int64_t ldb, int orderB, int64_t strideB,
+                            int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+int mipgemm_s8u8s32_batched(int64_t m, int64_t n, int64_t k,
+                            const int8_t *A, int64_t lda, int orderA, int64_t strideA,
+                            const uint8_t *B, int64_t ldb, int orderB, int64_t strideB,
+                            int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode,
+                            void *workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
  * Dequantised output, the step the paper's quantization scheme puts right after
  * the integer GEMM (Section 7.3: C^r = s_A s_B A^q B^q = s_A s_B C^q): the same
  * three GEMMs, but C holds floats and receives

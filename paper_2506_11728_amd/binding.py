@@ -46,7 +46,8 @@ def exported_symbols():
             "mipgemm_workspace_size", "mipgemm_strerror", "mipgemm_variant_name",
             "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
             "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32",
-            "mipgemm_pack_b", "mipgemm_s8s8s32_batched"]
+            "mipgemm_pack_b", "mipgemm_s8s8s32_batched", "mipgemm_u8s8s32_batched",
+            "mipgemm_s8u8s32_batched"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -89,10 +90,11 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
             lib.mipgemm_conv_variant_name.restype = ctypes.c_char_p
             lib.mipgemm_conv_variant_name.argtypes = [i64] * 9
-            lib.mipgemm_s8s8s32_batched.restype = ctypes.c_int
-            lib.mipgemm_s8s8s32_batched.argtypes = (
-                [i64] * 3 + [vp, i64, ctypes.c_int, i64] * 3 + [i64, ctypes.c_int, vp,
-                                                               ctypes.c_size_t, vp])
+            for fn in (lib.mipgemm_s8s8s32_batched, lib.mipgemm_u8s8s32_batched,
+                       lib.mipgemm_s8u8s32_batched):
+                fn.restype = ctypes.c_int
+                fn.argtypes = ([i64] * 3 + [vp, i64, ctypes.c_int, i64] * 3
+                               + [i64, ctypes.c_int, vp, ctypes.c_size_t, vp])
             lib.mipgemm_pack_b.restype = ctypes.c_int
             lib.mipgemm_pack_b.argtypes = [i64, i64, vp, i64, ctypes.c_int, vp, i64, vp]
             lib.mipgemm_im2col_u8.restype = ctypes.c_int
@@ -213,17 +215,42 @@ def mipgemm_im2col_u8(b, hi, wi, ci, hf, wf, stride, pad, I, M, ldm, stream=None
     return rc
 
 
-def mipgemm_s8s8s32_batched(m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB,
-                            C, ldc, orderC, strideC, batch, mode,
-                            workspace=None, workspace_bytes=0, stream=None, check=True):
-    """`batch` independent GEMMs of one shape, problem z at A + z*strideA, B + z*strideB, C + z*strideC."""
-    rc = load_library().mipgemm_s8s8s32_batched(
+def _batched(entry, m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB,
+             C, ldc, orderC, strideC, batch, mode, workspace, workspace_bytes, stream, check):
+    rc = getattr(load_library(), entry)(
         m, n, k, _ptr(A), lda, orderA, strideA, _ptr(B), ldb, orderB, strideB,
         _ptr(C), ldc, orderC, strideC, batch, mode, _ptr(workspace), workspace_bytes,
         _stream(stream))
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc
+
+
+def mipgemm_s8s8s32_batched(m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB,
+                            C, ldc, orderC, strideC, batch, mode,
+                            workspace=None, workspace_bytes=0, stream=None, check=True):
+    """`batch` independent GEMMs of one shape, problem z at A + z*strideA, B + z*strideB, C + z*strideC."""
+    return _batched("mipgemm_s8s8s32_batched", m, n, k, A, lda, orderA, strideA, B, ldb, orderB,
+                    strideB, C, ldc, orderC, strideC, batch, mode, workspace, workspace_bytes,
+                    stream, check)
+
+
+def mipgemm_u8s8s32_batched(m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB,
+                            C, ldc, orderC, strideC, batch, mode,
+                            workspace=None, workspace_bytes=0, stream=None, check=True):
+    """The strided batch with A unsigned."""
+    return _batched("mipgemm_u8s8s32_batched", m, n, k, A, lda, orderA, strideA, B, ldb, orderB,
+                    strideB, C, ldc, orderC, strideC, batch, mode, workspace, workspace_bytes,
+                    stream, check)
+
+
+def mipgemm_s8u8s32_batched(m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB,
+                            C, ldc, orderC, strideC, batch, mode,
+                            workspace=None, workspace_bytes=0, stream=None, check=True):
+    """The strided batch with B unsigned."""
+    return _batched("mipgemm_s8u8s32_batched", m, n, k, A, lda, orderA, strideA, B, ldb, orderB,
+                    strideB, C, ldc, orderC, strideC, batch, mode, workspace, workspace_bytes,
+                    stream, check)
 
 
 def mipgemm_pack_b(k, n, B, ldb, orderB, P, ldp, stream=None, check=True):

@@ -124,16 +124,17 @@ int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t ld
              workspace_bytes, stream);
 }
 
-int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda,
-                            int orderA, int64_t strideA, const int8_t *B, int64_t ldb, int orderB,
-                            int64_t strideB, int32_t *C, int64_t ldc, int orderC, int64_t strideC,
-                            int64_t batch, int mode, void *workspace, size_t workspace_bytes,
-                            void *stream) {
+// Strided batch of equal-shape problems in one launch (one grid z-slice per problem).
+static int run_batched(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const void *A,
+                       int64_t lda, int orderA, int64_t strideA, const void *B, int64_t ldb,
+                       int orderB, int64_t strideB, int32_t *C, int64_t ldc, int orderC,
+                       int64_t strideC, int64_t batch, int mode, void *workspace,
+                       size_t workspace_bytes, void *stream) {
   // the shared validation numbers its arguments as the single-problem entry points do:
   // map them onto this prototype (strides and batch shift everything after orderA)
   static const int renumber[17] = {0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 12, 13, 14, 17, 18, 19, 20};
   Problem probe;
-  const int base = validate_and_normalise(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc,
+  const int base = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc,
                                           orderC, mode, workspace, workspace_bytes, &probe);
   int first_bad = base < 0 ? renumber[-base] : 0;  // the lowest-numbered invalid argument wins
   auto also = [&](int number, bool bad) {
@@ -149,8 +150,35 @@ int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k, const int8_t *A, in
   b.stride_a = strideA;
   b.stride_b = strideB;
   b.stride_c = strideC;
-  return mip::run_gemm(0, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+  return mip::run_gemm(a_unsigned, b_unsigned, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
              workspace, workspace_bytes, stream, b);
+}
+
+int mipgemm_s8s8s32_batched(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda,
+                            int orderA, int64_t strideA, const int8_t *B, int64_t ldb, int orderB,
+                            int64_t strideB, int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+  return run_batched(0, 0, m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB, C, ldc, orderC,
+                     strideC, batch, mode, workspace, workspace_bytes, stream);
+}
+
+int mipgemm_u8s8s32_batched(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda,
+                            int orderA, int64_t strideA, const int8_t *B, int64_t ldb, int orderB,
+                            int64_t strideB, int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+  return run_batched(1, 0, m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB, C, ldc, orderC,
+                     strideC, batch, mode, workspace, workspace_bytes, stream);
+}
+
+int mipgemm_s8u8s32_batched(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda,
+                            int orderA, int64_t strideA, const uint8_t *B, int64_t ldb, int orderB,
+                            int64_t strideB, int32_t *C, int64_t ldc, int orderC, int64_t strideC,
+                            int64_t batch, int mode, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+  return run_batched(0, 1, m, n, k, A, lda, orderA, strideA, B, ldb, orderB, strideB, C, ldc, orderC,
+                     strideC, batch, mode, workspace, workspace_bytes, stream);
 }
 
 // Dequantised output (paper Section 7.3).  Same arguments and numbering as the

@@ -202,11 +202,13 @@ def test_conv_path_choice_and_workspace(M):
     assert ws(2, 8, 8, 64, 16, 13, 3, 1, 1) == 0
 
 
-def test_batched_entry_point_validation(M):
+@pytest.mark.parametrize("entry", ["mipgemm_s8s8s32_batched", "mipgemm_u8s8s32_batched",
+                                   "mipgemm_s8u8s32_batched"])
+def test_batched_entry_point_validation(M, entry):
     def call_b(m=4, n=5, k=6, A=4096, lda=6, oa=0, sa=24, B=4096, ldb=5, ob=0, sb=30, C=4096, ldc=5,
                oc=0, sc=20, batch=3, mode=0):
-        return M.mipgemm_s8s8s32_batched(m, n, k, A, lda, oa, sa, B, ldb, ob, sb, C, ldc, oc, sc,
-                                         batch, mode, None, 0, 0, check=False)
+        return getattr(M, entry)(m, n, k, A, lda, oa, sa, B, ldb, ob, sb, C, ldc, oc, sc,
+                                 batch, mode, None, 0, 0, check=False)
     assert call_b(m=-1) == -1
     assert call_b(lda=5) == -5
     assert call_b(sa=-1) == -7

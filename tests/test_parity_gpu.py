@@ -419,12 +419,14 @@ def _batched_cases():
     ]
 
 
+@pytest.mark.parametrize("signs", ["s8s8", "u8s8", "s8u8"])
 @pytest.mark.parametrize("variant", ["auto", "simple", "tile64", "dma64", "dma128"])
 @pytest.mark.parametrize("spec", _batched_cases(), ids=lambda s: "x".join(map(str, s)))
-def test_batched_gemm(gpu, oracle, spec, variant):
+def test_batched_gemm(gpu, oracle, spec, variant, signs):
     import torch
     m, n, k, oa, ob, oc, pad, batch, share_a, mode = spec
-    print("batched", spec, variant, flush=True)
+    au, bu = signs[0] == "u", signs[2] == "u"
+    print("batched", spec, variant, signs, flush=True)
     case = W.Case("batched", 8, 0, m, n, k, orderA=oa, orderB=ob, orderC=oc, pad=pad, mode=mode,
                   c_dist=("uniform", -1000, 1000), seed=51)
     sets = [W.materialize(W.Case("batched", 8, z, m, n, k, orderA=oa, orderB=ob, orderC=oc, pad=pad,
@@ -446,14 +448,16 @@ def test_batched_gemm(gpu, oracle, spec, variant):
         B[z * sb:z * sb + o.B.size] = o.B
         C[z * sc:z * sc + o.C.size] = o.C
         w = o.C.copy()
-        oracle.gemm(False, False, m, n, k, a, case.lda, oa, o.B, case.ldb, ob, w, case.ldc, oc, mode)
+        # the same bytes, read as unsigned where the entry point says so
+        oracle.gemm(au, bu, m, n, k, a.view(np.uint8) if au else a, case.lda, oa,
+                    o.B.view(np.uint8) if bu else o.B, case.ldb, ob, w, case.ldc, oc, mode)
         want[z * sc:z * sc + w.size] = w
     dA = torch.from_numpy(A.view(np.uint8)).cuda()
     dB = torch.from_numpy(B.view(np.uint8)).cuda()
     dC = torch.from_numpy(C).cuda()
     with VariantEnv(variant):
-        gpu.mipgemm_s8s8s32_batched(m, n, k, dA, case.lda, oa, sa, dB, case.ldb, ob, sb,
-                                    dC, case.ldc, oc, sc, batch, mode)
+        getattr(gpu, "mipgemm_%ss32_batched" % signs)(m, n, k, dA, case.lda, oa, sa, dB, case.ldb, ob,
+                                                      sb, dC, case.ldc, oc, sc, batch, mode)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)        # the gaps between the slices included
 
