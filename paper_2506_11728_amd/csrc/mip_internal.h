@@ -100,6 +100,11 @@ hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8
 hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
                          int64_t ldp, hipStream_t s);
 
+// The convolution (p.conv set, image unsigned, filters k-contiguous with pitch k) with the
+// augmented matrix gathered from image row segments staged in LDS: any channel count.
+bool conv_rows_eligible(const Problem &p);
+hipError_t launch_conv_rows(const Problem &p, hipStream_t s);
+
 bool dma_eligible(const Problem &p, Shape shape);
 hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);
 

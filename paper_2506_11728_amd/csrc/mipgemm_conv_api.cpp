@@ -65,14 +65,24 @@ Problem conv_problem(const ConvCall &c, int64_t co, const void *F, const void *I
   return p;
 }
 
-// whether the gathering kernel serves this convolution, and with which plan
-bool conv_implicit_plan(const ConvCall &c, Problem p, mip::Plan *plan) {
-  const char *e = std::getenv("MIPGEMM_CONV");  // "im2col" pins the written-out path (tests, tuning)
-  if (e && !std::strcmp(e, "im2col")) return false;
-  if (p.m == 0 || p.n == 0) return false;
+// How a convolution is carried out.
+enum Route {
+  ROUTE_TILES,   // a direct-to-LDS tile kernel gathers the augmented matrix (channels in 16-byte runs)
+  ROUTE_ROWS,    // the row-segment kernel gathers it (any channel count, small k)
+  ROUTE_IM2COL   // the augmented matrix is written to the workspace, then a plain GEMM
+};
+
+// MIPGEMM_CONV pins a route for tests and tuning: "im2col" the written-out one, "rows" the
+// row-segment kernel where it can serve.
+Route conv_route(const ConvCall &c, Problem p, mip::Plan *plan) {
+  const char *e = std::getenv("MIPGEMM_CONV");
+  if (e && !std::strcmp(e, "im2col")) return ROUTE_IM2COL;
+  if (p.m == 0 || p.n == 0) return ROUTE_IM2COL;
   p.conv = &c.geom;
+  if (e && !std::strcmp(e, "rows") && mip::conv_rows_eligible(p)) return ROUTE_ROWS;
   *plan = mip::choose_plan(p);
-  return plan->kind == mip::KIND_DMA;
+  if (plan->kind == mip::KIND_DMA) return ROUTE_TILES;
+  return mip::conv_rows_eligible(p) ? ROUTE_ROWS : ROUTE_IM2COL;
 }
 
 }  // namespace
@@ -86,8 +96,8 @@ size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci
   if (c.rows == 0 || co == 0) return 0;
   const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
   mip::Plan plan;
-  if (conv_implicit_plan(c, conv_problem(c, co, fake, fake, const_cast<void *>(fake),
-                                         MIPGEMM_OVERWRITE, true, nullptr), &plan))
+  if (conv_route(c, conv_problem(c, co, fake, fake, const_cast<void *>(fake), MIPGEMM_OVERWRITE,
+                                 true, nullptr), &plan) != ROUTE_IM2COL)
     return 0;
   return static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
 }
@@ -99,9 +109,11 @@ const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t
   if (c.rows == 0 || co == 0) return "none";
   const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
   mip::Plan plan;
-  const bool implicit = conv_implicit_plan(
+  const Route route = conv_route(
       c, conv_problem(c, co, fake, fake, const_cast<void *>(fake), MIPGEMM_OVERWRITE, true, nullptr),
       &plan);
+  if (route == ROUTE_ROWS) return "implicit:rows";
+  const bool implicit = route == ROUTE_TILES;
   if (!implicit)
     plan = mip::choose_plan(conv_problem(c, co, fake, fake, const_cast<void *>(fake),
                                          MIPGEMM_OVERWRITE, false, fake));
@@ -150,10 +162,10 @@ static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t w
   hipStream_t s = static_cast<hipStream_t>(stream);
   mip::Plan plan;
   Problem p = conv_problem(c, co, F, I, O, mode, true, nullptr, out_float, scale);
-  if (conv_implicit_plan(c, p, &plan)) {
-    p.conv = &c.geom;
-    return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
-  }
+  const Route route = conv_route(c, p, &plan);
+  p.conv = &c.geom;
+  if (route == ROUTE_TILES) return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
+  if (route == ROUTE_ROWS) return static_cast<int>(mip::launch_conv_rows(p, s));
   const size_t need = static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
   if (!workspace) return -14;
   if (workspace_bytes < need) return -15;

@@ -166,8 +166,8 @@ def test_conv_argument_validation_codes(M):
     assert conv(I=0) == -11
     assert conv(O=0) == -12
     assert conv(mode=2) == -13
-    assert conv(ci=3) == -14                         # 3 channels: the written-out route needs a workspace
-    assert conv(ci=3, ws=4096, wsb=10) == -15
+    assert conv(ci=96) == -14                        # no kernel gathers these: the written-out route needs a workspace
+    assert conv(ci=96, ws=4096, wsb=10) == -15
     assert conv(b=2**31) == -1
     assert conv(b=70000, hi=256, wi=256, ci=64) == -1    # the image tensor must stay below 2^31 bytes
     assert conv(b=1, hi=2**31 - 1, wi=1, ci=1, pad=2**31 - 1, hf=1, wf=1) == -9   # output extent beyond 2^31
@@ -193,10 +193,13 @@ def test_conv_path_choice_and_workspace(M):
     assert ws(32, 56, 56, 64, 64, 3, 3, 1, 1) == 0
     assert name(32, 28, 28, 128, 128, 3, 3, 1, 1) == "implicit:mfma_dma128x64"
     assert name(1, 7, 7, 512, 2048, 1, 1, 1, 0).startswith("implicit:")
-    # the 3-channel first layer is written out: n rows of k bytes rounded up to 16
-    assert name(2, 64, 48, 3, 64, 7, 7, 2, 3).startswith("im2col+")
-    assert ws(2, 64, 48, 3, 64, 7, 7, 2, 3) == 2 * 32 * 24 * 160
-    assert name(2, 8, 8, 96, 16, 3, 3, 1, 1).startswith("im2col+")      # 96 is not a multiple of 64
+    # the 3-channel first layer is gathered too, from image row segments staged in LDS
+    assert name(2, 64, 48, 3, 64, 7, 7, 2, 3) == "implicit:rows"
+    assert ws(2, 64, 48, 3, 64, 7, 7, 2, 3) == 0
+    # 96 channels: not a multiple of 64, k too long for the row-segment kernel: the augmented
+    # matrix is written out, n rows of k bytes rounded up to 16
+    assert name(2, 8, 8, 96, 16, 3, 3, 1, 1).startswith("im2col+")
+    assert ws(2, 8, 8, 96, 16, 3, 3, 1, 1) == 2 * 8 * 8 * 864
     assert name(0, 8, 8, 64, 16, 3, 3, 1, 1) == "none"
     assert name(2, 8, 8, 64, 16, 13, 3, 1, 1) == "invalid"
     assert ws(2, 8, 8, 64, 16, 13, 3, 1, 1) == 0

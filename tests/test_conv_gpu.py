@@ -108,12 +108,47 @@ def test_implicit_conv_under_every_tile_shape_and_split_k(gpu, oracle, shape, va
     assert np.array_equal(got, want)
 
 
-def test_conv_first_layer_shape_takes_the_written_out_path(gpu, oracle):
-    shape = (2, 64, 48, 3, 64, 7, 7, 2, 3)                  # 3 channels: no 64-channel blocks to gather
-    assert gpu.mipgemm_conv_variant_name(*shape).startswith("im2col+")
+# channel counts without 16-byte runs (and a few with, pinned to the same kernel): the
+# row-segment kernel.  Several tiles per output row with a ragged last one, filter rows
+# shorter and longer than a fragment's 16 bytes, filters past one workgroup's 64, windows
+# that lie entirely in the padding, k from 4 to 245.
+ROWS_SHAPES = [
+    (2, 64, 48, 3, 64, 7, 7, 2, 3), (2, 20, 300, 3, 10, 3, 3, 1, 1), (1, 9, 9, 1, 65, 5, 5, 1, 2),
+    (3, 12, 40, 5, 130, 3, 4, 3, 0), (1, 16, 16, 17, 7, 2, 2, 2, 1), (2, 10, 10, 4, 33, 1, 1, 1, 0),
+    (1, 30, 260, 2, 64, 7, 1, 1, 3), (1, 5, 5, 3, 8, 3, 3, 1, 4), (1, 20, 20, 16, 40, 3, 3, 1, 1),
+    (2, 12, 12, 64, 64, 1, 1, 1, 0), (1, 40, 131, 5, 3, 7, 7, 1, 0)]
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", ROWS_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_through_the_row_segment_kernel(gpu, oracle, shape, mode):
+    print("conv rows", shape, "mode", mode, flush=True)
     I, F = tensors(shape, 4)
-    want = oracle.conv_direct(I, F, 2, 3)
+    with Env(MIPGEMM_CONV="rows"):
+        assert gpu.mipgemm_conv_variant_name(*shape) == "implicit:rows"
+        assert gpu.mipgemm_conv_workspace_size(*shape) == 0
+    ho = oracle.conv_out_extent(shape[1], shape[5], shape[7], shape[8])
+    wo = oracle.conv_out_extent(shape[2], shape[6], shape[7], shape[8])
+    rng = np.random.default_rng(9)
+    O0 = rng.integers(-1000, 1000, size=(shape[0], ho, wo, shape[4]), dtype=np.int32)
+    want = oracle.conv_direct(I, F, shape[7], shape[8], O=O0.copy() if mode else None, mode=mode)
+    got = run_conv(gpu, shape, I, F, O0, mode, MIPGEMM_CONV="rows")
+    assert np.array_equal(got, want)
+
+
+def test_conv_first_layer_of_the_network(gpu, oracle):
+    """224 x 224 x 3 images, 64 filters of 7 x 7, stride 2, padding 3: both routes that serve it."""
+    import workloads as W
+    hi, ci, co, hf, s, p = W.CONV_FIRST_LAYER
+    shape = (2, hi, hi, ci, co, hf, hf, s, p)
+    assert gpu.mipgemm_conv_variant_name(*shape) == "implicit:rows"
+    I, F = tensors(shape, 4)
+    want = oracle.conv_direct(I, F, s, p)
     got = run_conv(gpu, shape, I, F, np.zeros(want.shape, dtype=np.int32), 0)
+    assert np.array_equal(got, want)
+    with Env(MIPGEMM_CONV="im2col"):
+        assert gpu.mipgemm_conv_variant_name(*shape).startswith("im2col+")
+    got = run_conv(gpu, shape, I, F, np.zeros(want.shape, dtype=np.int32), 0, MIPGEMM_CONV="im2col")
     assert np.array_equal(got, want)
 
 
@@ -169,6 +204,12 @@ def test_im2col_matches_the_oracle(gpu, oracle, shape, extra):
 def test_conv_errors_and_empty(gpu):
     import torch
     shape = (1, 8, 8, 3, 4, 3, 3, 1, 1)
+    with Env(MIPGEMM_CONV="im2col"):
+        _conv_errors_and_empty(gpu, shape)
+
+
+def _conv_errors_and_empty(gpu, shape):
+    import torch
     need = gpu.mipgemm_conv_workspace_size(*shape)
     assert need == 64 * 32                                   # 64 positions, 27 bytes rounded up to 32
     dI = torch.zeros(8 * 8 * 3, dtype=torch.uint8, device="cuda")
