@@ -8,18 +8,23 @@
 // to the row of an output position are one contiguous run of an image row:
 //   bytes (ox*stride - pad) * c_i + r,  r = 0 .. w_f*c_i - 1,  of image row oy*stride + y - pad,
 // and a byte of that run lies inside the image exactly when its position in the
-// image row does (0 <= position < w_i * c_i), whatever its channel.  So a workgroup
-//   * stages, for 128 consecutive output positions of one output row, the h_f image
-//     row segments they touch into LDS (a few KB; zero where outside the image,
-//     every byte turned into the signed x - 128 on the way),
-//   * builds each wave's operand fragments (32 positions x 32 k) from those
-//     segments with LDS byte reads,
-//   * multiplies them with the filter fragments, which it laid out in LDS in
-//     register order once at its start (64 filters per workgroup, grid.y walks c_o),
-//   * and writes its 128 x 64 patch of O with the shared epilogue (unsigned
-//     correction 128 * sum_k F(o, k), overwrite / accumulate, optional scale to float).
-// A workgroup walks several tiles (stride gridDim.x) so that the filter fragments are
-// built once.  Bound by the write of O: the image is read once, from cache mostly.
+// image row does (0 <= position < w_i * c_i), whatever its channel.  So a workgroup takes
+// 128 consecutive output positions of one output row at a time (a tile), and
+//   * its four loader waves stage the h_f image row segments the tile touches into LDS
+//     (a few KB; zero where outside the image, every byte turned into the signed x - 128
+//     on the way), into one of two stages, one tile ahead of the computation;
+//   * its four compute waves build their operand fragments (32 positions x 32 k each)
+//     from those segments: 16 consecutive k are at most two runs of bytes, fetched as two
+//     16-byte LDS reads at whatever alignment and merged by a byte mask (filter rows
+//     shorter than 16 bytes: byte by byte),
+//   * multiply them with the filter fragments, laid out in LDS in register order once at
+//     the workgroup's start (64 filters per workgroup, grid.y walks c_o),
+//   * and write their 32 x 64 patches of O, starting the accumulators from the unsigned
+//     correction 128 * sum_k F(o, k) (overwrite / accumulate, optional scale to float).
+// A workgroup walks several tiles (stride gridDim.x), so the filter fragments are built
+// once, and the split into loader and compute waves keeps the image loads and the waits
+// for them out of the way of the stores of O.  Bound by the write of O in principle;
+// measured, instruction issue of the fragment building and the write-back still shows.
 #include "epilogue.h"
 #include "lds_layout.h"
 #include "mip_internal.h"
@@ -176,11 +181,12 @@ __global__ __launch_bounds__(NTHREADS_ROWS) void conv_rows_kernel(RowsParams P) 
     int words;     // words per staged segment
     const uint8_t *image;
   };
-  auto tile_at = [&](int64_t t) {
+  auto tile_at = [&](int t) {  // (fewer tiles than output positions, and those fit 31 bits)
     Tile T;
-    T.orow = t / P.tiles_per_row;
-    T.ox0 = (int)(t - T.orow * P.tiles_per_row) * TP;
-    const int g = (int)(T.orow / P.G.ho), oy = (int)(T.orow - (int64_t)g * P.G.ho);
+    const int orow = t / P.tiles_per_row;
+    T.orow = orow;
+    T.ox0 = (t - orow * P.tiles_per_row) * TP;
+    const int g = orow / P.G.ho, oy = orow - g * P.G.ho;
     T.iy0 = oy * P.G.stride - P.G.pad;
     T.pos0 = (T.ox0 * P.G.stride - P.G.pad) * P.G.ci;
     T.image = P.I + (int64_t)g * P.G.hi * row_len;
@@ -298,27 +304,34 @@ __global__ __launch_bounds__(NTHREADS_ROWS) void conv_rows_kernel(RowsParams P) 
   // stage with the next tile: their loads, and the waits for them, never stand behind
   // stores (a wave's memory counter is its own, and stores count in it), and the compute
   // waves never wait for loads.
-  Tile T = tile_at(blockIdx.x);  // the host launches no more workgroups than tiles
-  if (wave >= 4) stage_tile(T, smem);
-  __syncthreads();
-  int cur = 0;
-  for (int64_t t = blockIdx.x; t < P.tiles; t += gridDim.x) {
-    const bool more = t + gridDim.x < P.tiles;
-    const Tile N = more ? tile_at(t + gridDim.x) : T;
-    if (wave >= 4) {
-      if (more) stage_tile(N, smem + (cur ^ 1) * P.stage_bytes);
-    } else {
-      compute_tile(T, smem + cur * P.stage_bytes);
+  // The two kinds of waves run loops of their own, with the same number of barriers (whole
+  // waves take either branch, and a barrier counts waves wherever they wait): so each loop
+  // is scheduled, and its memory waits are placed, for what that kind of wave does.
+  const int ntiles = (int)P.tiles, step = (int)gridDim.x;
+  if (wave >= 4) {
+    stage_tile(tile_at(blockIdx.x), smem);  // the host launches no more workgroups than tiles
+    __syncthreads();
+    int cur = 0;
+    for (int t = blockIdx.x; t < ntiles; t += step) {
+      if (ntiles - t > step) stage_tile(tile_at(t + step), smem + (cur ^ 1) * P.stage_bytes);
+      __syncthreads();  // the next stage is filled, this one is free
+      cur ^= 1;
     }
-    __syncthreads();  // the next stage is filled, this one is free
-    T = N;
-    cur ^= 1;
+  } else {
+    __syncthreads();
+    int cur = 0;
+    for (int t = blockIdx.x; t < ntiles; t += step) {
+      compute_tile(tile_at(t), smem + cur * P.stage_bytes);
+      __syncthreads();
+      cur ^= 1;
+    }
   }
 }
 
 bool fill_params(const Problem &p, RowsParams *out) {
   if (!p.conv || !p.a_unsigned || p.b_unsigned || p.batch != 1) return false;
   if (p.b_sk != 1 || p.b_sn != p.k || p.m < 1 || p.n < 1 || p.k < 1) return false;
+  if (p.m >= ((int64_t)1 << 30)) return false;  // tile numbers are 32-bit in the kernel
   const ConvGeom &G = *p.conv;
   const int64_t wfci = (int64_t)G.wf * G.ci;
   if (p.k % wfci != 0 || p.k > 4096) return false;
