@@ -42,6 +42,10 @@ def parse_args():
                     help="run a plain 1 GiB device copy and exit (scales the HBM byte counters)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the register-resident MFMA rate probe")
+    ap.add_argument("--conv-layer", type=str, default=None,
+                    help="name of a layer of the convolution workload (see workloads.resnet50_conv_layers; "
+                         "e.g. stem) to run as a convolution instead; --batch sets the batch")
+    ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--suite", action="store_true",
                     help="time every workload case once and print a table instead of the JSON line")
     return ap.parse_args()
@@ -311,7 +315,7 @@ def run_network_table(M):
     print("All 53 convolutions of a ResNet-50 v1.5-type network on 224 x 224 images (23 distinct layers),")
     print("u8 activations x s8 filters -> s32, each layer on its own synthetic tensors:")
     print()
-    print("| batch | us, all convolutions | of which the 7 x 7 stem (written-out route) | GMAC | TOPS |")
+    print("| batch | us, all convolutions | of which the 7 x 7 stem (3 channels: row-segment kernel) | GMAC | TOPS |")
     print("|---|---|---|---|---|")
     layers = W.resnet50_conv_layers()
     for b in W.CONV_BATCHES:
@@ -475,6 +479,57 @@ def run_encoder_table(M):
             ops / t_batched / 1e6), flush=True)
 
 
+def run_conv_layer(M, args):
+    """One layer of the convolution workload through mipgemm_conv_s8u8s32: W untimed calls,
+    K timed ones between two events on the launch stream, one JSON line."""
+    import torch
+    geo = None
+    for name, g, _count in W.resnet50_conv_layers():
+        if name == args.conv_layer:
+            geo = g
+    if geo is None:
+        raise SystemExit("unknown layer %r" % args.conv_layer)
+    b = args.batch
+    hi, ci, co, hf, stride, pad = geo
+    image, filt = W.conv_tensors(b, geo)
+    ho = (hi + 2 * pad - hf) // stride + 1
+    n, k = b * ho * ho, hf * hf * ci
+    dI, dF = torch.from_numpy(image).cuda(), torch.from_numpy(filt.view(np.uint8)).cuda()
+    dO = torch.zeros(n * co, dtype=torch.int32, device="cuda")
+    geom = (b, hi, hi, ci, co, hf, hf, stride, pad)
+    need = M.mipgemm_conv_workspace_size(*geom)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda") if need else None
+    stream = torch.cuda.current_stream()
+
+    def step():
+        M.mipgemm_conv_s8u8s32(*geom, dF, dI, dO, W.OVERWRITE, workspace=ws, workspace_bytes=need,
+                               stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / args.steps
+    moved = image.size + filt.size + 4 * n * co
+    print(json.dumps({
+        "metric": "convolution by lowering, u8 x s8 -> s32", "value": 2.0 * n * k * co / (ms * 1e-3) / 1e12,
+        "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "dtype": "u8*s8->s32", "data": "synthetic",
+        "config": {"workload": "%s: b=%d image %dx%dx%d, %d filters %dx%d, stride %d, pad %d; "
+                               "(m, n, k) = (%d, %d, %d)" % (args.conv_layer, b, hi, hi, ci, co, hf, hf,
+                                                             stride, pad, co, n, k)},
+        "roofline": {"bound": "hbm", "achieved": moved / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": M.mipgemm_conv_variant_name(*geom), "kernel_ms": ms,
+                     "algorithmic_bytes": moved},
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -490,6 +545,9 @@ def main():
 
     if args.copy_calibration:
         copy_calibration()
+        return
+    if args.conv_layer:
+        run_conv_layer(M, args)
         return
     if args.suite:
         run_suite(M, args)
