@@ -209,11 +209,14 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k,
  * C (column-major with ldc = c_o), k index (y, x, c) with c fastest, n index
  * (g, oy, ox) with ox fastest.
  *
- * mipgemm_conv_s8u8s32 gathers the augmented matrix on the fly inside the GEMM
- * kernel when c_i is a multiple of 64 and F, I are 16-byte aligned: nothing is
- * written but O and no workspace is needed.  Otherwise it writes the augmented
- * matrix into `workspace` first (mipgemm_conv_workspace_size bytes) and runs
- * mipgemm_s8u8s32 on it.  Pointers are device pointers owned by the caller;
+ * mipgemm_conv_s8u8s32 gathers the augmented matrix on the fly inside the
+ * multiplying kernel, so that nothing is written but O and no workspace is
+ * needed, in two cases: c_i a multiple of 64 with F and I 16-byte aligned (the
+ * GEMM tile kernels take their operand addresses from the image), and any c_i
+ * with a short k (up to about 600, e.g. the 3-channel 7 x 7 first layer of a
+ * network: a kernel that stages image row segments on chip).  Otherwise it
+ * writes the augmented matrix into `workspace` first
+ * (mipgemm_conv_workspace_size bytes) and runs mipgemm_s8u8s32 on it.  Pointers are device pointers owned by the caller;
  * same execution and error conventions as the GEMM entry points.  Argument
  * numbers: b=1 hi=2 wi=3 ci=4 co=5 hf=6 wf=7 stride=8 pad=9 F=10 I=11 O=12 mode=13
  * workspace=14 workspace_bytes=15 stream=16.  Sizes must be positive (b and c_o may
@@ -243,8 +246,8 @@ int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci,
 
 /*
  * Bytes of workspace mipgemm_conv_s8u8s32 / mipgemm_conv_s8u8f32 need for these sizes when its pointers
- * are 16-byte aligned: 0 when c_i is a multiple of 64, else room for the augmented
- * matrix.  Returns 0 for invalid sizes.
+ * are 16-byte aligned: 0 when the augmented matrix is gathered on the fly (see
+ * above), else room for it.  Returns 0 for invalid sizes.
  */
 size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci,
                                    int64_t co, int64_t hf, int64_t wf,
