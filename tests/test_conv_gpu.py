@@ -332,3 +332,34 @@ def test_pack_b_errors(gpu):
     assert f(4, 8, z, 8, 0, None, 4, check=False) == -6
     assert f(4, 8, z, 8, 0, z, 3, check=False) == -7
     assert f(0, 8, None, 8, 0, None, 1, check=False) == 0
+
+
+@pytest.mark.parametrize("shape", [(2, 64, 48, 3, 64, 7, 7, 2, 3), (2, 28, 28, 128, 128, 3, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_convolution_replays_from_a_hip_graph(gpu, oracle, shape):
+    """A captured convolution (row-segment kernel; tile kernel that gathers) gives the oracle's
+    result on every replay, with O overwritten by other work between the replays."""
+    import torch
+    print("conv graph", shape, flush=True)
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    assert gpu.mipgemm_conv_workspace_size(*shape) == 0
+    I, F = tensors(shape, 11)
+    want = oracle.conv_direct(I, F, s, p)
+    dI, dF = torch.from_numpy(I).cuda(), torch.from_numpy(F.view(np.uint8)).cuda()
+    dO = torch.zeros(want.shape, dtype=torch.int32, device="cuda")
+
+    def call():
+        gpu.mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 0)
+
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(dO.cpu().numpy(), want)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for replay in range(4):
+        dO.fill_(replay - 7)                         # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(dO.cpu().numpy(), want), "replay %d" % replay

@@ -480,3 +480,50 @@ def test_batched_empty_sums(gpu):
     gpu.mipgemm_s8s8s32_batched(0, n, 8, z, 8, 0, 0, z, n, 0, 0, dC, ldc, 0, sc, batch, W.OVERWRITE)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)
+
+
+def test_calls_from_two_host_threads_on_two_streams(gpu, oracle):
+    """The library keeps no state between calls: two host threads, each with a stream of its
+    own, issue different problems (a split-k call with its zero fill, a skinny one, a square
+    one) many times over at once; every result is the oracle's."""
+    import threading
+    import torch
+    cases = [W.Case("mt_splitk", 8, 0, 48, 256, 4096, seed=41),
+             W.Case("mt_slab", 8, 1, 8, 3072, 512, orderB=W.COL_MAJOR, seed=41),
+             W.Case("mt_square", 8, 2, 512, 512, 512, a_unsigned=True, seed=41)]
+    work = []
+    for case in cases:
+        ops = W.materialize(case)
+        work.append((case, oracle_result(oracle, case, ops), ops))
+    failures = []
+
+    def worker(index):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()             # default priority
+            with torch.cuda.stream(stream):
+                bufs = [(torch.from_numpy(ops.A.view(np.uint8)).cuda(), torch.from_numpy(ops.B.view(np.uint8)).cuda(),
+                         torch.from_numpy(ops.C).cuda()) for _, _, ops in work]
+            stream.synchronize()
+            for it in range(40):
+                which = (it + index) % len(work)
+                case, want, ops = work[which]
+                dA, dB, dC = bufs[which]
+                with torch.cuda.stream(stream):
+                    dC.copy_(torch.from_numpy(ops.C), non_blocking=False)
+                getattr(gpu, "mipgemm_" + case.entry)(
+                    case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+                    dC, case.ldc, case.orderC, case.mode, stream=stream)
+                stream.synchronize()
+                if not np.array_equal(dC.cpu().numpy(), want):
+                    failures.append((index, it, case.name))
+        except Exception as e:                        # surfaced in the main thread below
+            failures.append((index, "exception", repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert failures == []
