@@ -23,8 +23,14 @@
  * contents.  With MIPGEMM_OVERWRITE the previous contents of C are never read.
  * C must not overlap A or B (not checked).  `stream` is a hipStream_t passed
  * as void* (NULL = the default stream).  `workspace` is device memory the call
- * may use until it completes on the stream; pass at least
- * mipgemm_workspace_size() bytes, or NULL / 0 when that size is 0.
+ * may use until it completes on the stream.  For the GEMM entry points it is
+ * optional (NULL / 0 is always accepted): with mipgemm_workspace_size() bytes,
+ * 16-byte aligned, large products whose operands cannot be streamed as they are
+ * stored (a pointer or leading dimension that is not a multiple of 16 bytes, k
+ * not a multiple of 64) are first packed into it, k contiguous and padded with
+ * zeros (the paper's Pack A / Pack B into aligned buffers A_c, B_c, Section
+ * 4.1), and run several times faster; without it they run on slower kernels
+ * that read the operands in place.  Results are the same bits either way.
  *
  * Execution.  Each call validates its arguments on the host, enqueues its
  * kernels on `stream` and returns without waiting.  Only kernels are enqueued
@@ -36,8 +42,9 @@
  * argument (counted from 1 in the order of the prototype) is invalid: a
  * negative size, a null pointer for an operand that is not empty, a leading
  * dimension that is too small, an unknown order or mode, a size above
- * MIPGEMM_MAX_DIM, or a workspace that is too small (reported on the
- * workspace_bytes argument).  A positive value is the hipError_t of a failed
+ * MIPGEMM_MAX_DIM, a null workspace with a non-zero workspace_bytes, or (in
+ * the convolution entry points, which need theirs) a workspace that is too
+ * small (reported on the workspace_bytes argument).  A positive value is the hipError_t of a failed
  * launch.  When a call fails validation nothing is enqueued and no memory is
  * touched.
  *
@@ -294,8 +301,14 @@ int mipgemm_pack_b(int64_t k, int64_t n,
                    void *stream);
 
 /*
- * Bytes of device workspace a call with these sizes and orders may use.
- * Returns 0 when none is needed (and for invalid sizes).
+ * Bytes of device workspace with which a GEMM call of these sizes and orders
+ * takes the packed route (see "Pointers" above), taking the tightest leading
+ * dimensions and 16-byte aligned pointers: 0 when such operands are streamed as
+ * they are, when the product is too small for packing to pay (m or n below 64,
+ * k below 256, m*n*k below 2^29), and for invalid sizes.  Operands with other leading
+ * dimensions or pointers need round_up(m*kp, 256) + round_up(n*kp, 256) bytes,
+ * kp = k rounded up to a multiple of 128 (of 64 when k < 1024); a call uses the packed route whenever
+ * it would pay and the workspace it is given is that large.
  */
 size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k,
                               int orderA, int orderB, int orderC);
@@ -311,7 +324,7 @@ const char *mipgemm_strerror(int code);
 /*
  * Name of the kernel variant the dispatcher picks for these sizes, orders,
  * leading dimensions and pointer alignments (all pointers taken as 16-byte
- * aligned when `aligned16` is non-zero).  Host-only, launches nothing; meant
+ * aligned when `aligned16` is non-zero), for a call without workspace.  Host-only, launches nothing; meant
  * for tests, benchmarks and profiles.  Returns a static string.
  */
 const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k,
@@ -319,6 +332,17 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k,
                                  int64_t ldb, int orderB,
                                  int64_t ldc, int orderC,
                                  int a_unsigned, int b_unsigned, int aligned16);
+
+/*
+ * The same for a call that is given a workspace of sufficient size: "packed+"
+ * and the kernel that multiplies the packed operands when the packed route is
+ * taken, else what mipgemm_variant_name returns.
+ */
+const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k,
+                                                int64_t lda, int orderA,
+                                                int64_t ldb, int orderB,
+                                                int64_t ldc, int orderC,
+                                                int a_unsigned, int b_unsigned, int aligned16);
 
 /*
  * Device characterisation for benchmarks: the throughput, in 10^12 operations

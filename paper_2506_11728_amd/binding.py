@@ -47,7 +47,7 @@ def exported_symbols():
             "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
             "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32",
             "mipgemm_pack_b", "mipgemm_s8s8s32_batched", "mipgemm_u8s8s32_batched",
-            "mipgemm_s8u8s32_batched"]
+            "mipgemm_s8u8s32_batched", "mipgemm_variant_name_with_workspace"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -75,10 +75,10 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_workspace_size.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
             lib.mipgemm_strerror.restype = ctypes.c_char_p
             lib.mipgemm_strerror.argtypes = [ctypes.c_int]
-            lib.mipgemm_variant_name.restype = ctypes.c_char_p
-            lib.mipgemm_variant_name.argtypes = ([ctypes.c_int64] * 3
-                                                 + [ctypes.c_int64, ctypes.c_int] * 3
-                                                 + [ctypes.c_int] * 3)
+            for fn in (lib.mipgemm_variant_name, lib.mipgemm_variant_name_with_workspace):
+                fn.restype = ctypes.c_char_p
+                fn.argtypes = ([ctypes.c_int64] * 3 + [ctypes.c_int64, ctypes.c_int] * 3
+                               + [ctypes.c_int] * 3)
             i64, vp = ctypes.c_int64, ctypes.c_void_p
             lib.mipgemm_conv_s8u8s32.restype = ctypes.c_int
             lib.mipgemm_conv_s8u8s32.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
@@ -272,6 +272,13 @@ def mipgemm_strerror(code: int) -> str:
 def mipgemm_variant_name(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
                          a_unsigned=False, b_unsigned=False, aligned16=True) -> str:
     return load_library().mipgemm_variant_name(
+        m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+        int(a_unsigned), int(b_unsigned), int(aligned16)).decode()
+
+
+def mipgemm_variant_name_with_workspace(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+                                        a_unsigned=False, b_unsigned=False, aligned16=True) -> str:
+    return load_library().mipgemm_variant_name_with_workspace(
         m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
         int(a_unsigned), int(b_unsigned), int(aligned16)).decode()
 

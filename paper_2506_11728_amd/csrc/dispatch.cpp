@@ -130,7 +130,13 @@ Plan choose_plan(const Problem &p) {
     // Between 128 x 128 (too few tiles) and 64 x 64 (64 operations per operand byte,
     // which the L2 caches cannot feed) sit the 8192-element tiles, long side along the
     // longer dimension of C.
-    else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192) sh = SHAPE_256;
+    // (One 256 x 256 workgroup fills a compute unit: a few tiles more than there are
+    // compute units cost a second round almost in full, which 128 x 128 tiles, two
+    // workgroups to a compute unit, do not.  Measured at k = 4096: 289 tiles 121 us
+    // against 110, 324 tiles 124 against 125, 400 tiles 132 against 150.)
+    else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192 &&
+             !(tile_count(p, SHAPE_256) > kComputeUnits && tile_count(p, SHAPE_256) <= 320))
+      sh = SHAPE_256;
     else if (p.k >= 512 && tile_count(p, SHAPE_128) >= kComputeUnits) sh = SHAPE_128;
     else if (p.k >= 512 && tile_count(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128) >= kComputeUnits &&
              dma_eligible(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128))
@@ -148,7 +154,7 @@ Plan choose_plan(const Problem &p) {
     if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192) plan = {KIND_SLAB, SHAPE_64, 1};
     else if (slab_ok && p.k < 1024 && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
-    else if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
     // the register-staged kernel keeps its operands in flight in VGPRs, which a
     // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128

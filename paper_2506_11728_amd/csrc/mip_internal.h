@@ -96,9 +96,10 @@ hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8
                          int64_t ldm, hipStream_t s);
 
 // The k x n matrix B (b_kc: already k-contiguous, pitch ldb; else row-major, pitch ldb)
-// rewritten k-contiguous with pitch ldp.
+// rewritten k-contiguous with pitch ldp; entries k .. kfill - 1 of every column are written
+// as zeros (kfill <= k: nothing beyond k is written).
 hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
-                         int64_t ldp, hipStream_t s);
+                         int64_t ldp, hipStream_t s, int64_t kfill = 0);
 
 // The convolution (p.conv set, image unsigned, filters k-contiguous with pitch k) with the
 // augmented matrix gathered from image row segments staged in LDS: any channel count.

@@ -34,9 +34,7 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
     if (ldc < (need > 1 ? need : 1) || ldc > MIPGEMM_MAX_DIM) return -11;
   }
   if (mode != MIPGEMM_OVERWRITE && mode != MIPGEMM_ACCUMULATE) return -13;
-  size_t need_ws = mipgemm_workspace_size(m, n, k, orderA, orderB, orderC);
-  if (need_ws > 0 && !workspace) return -14;
-  if (workspace_bytes < need_ws) return -15;
+  if (workspace_bytes > 0 && !workspace) return -14;  // the workspace itself is optional
 
   const int64_t a_sm = orderA == MIPGEMM_ROW_MAJOR ? lda : 1;
   const int64_t a_sk = orderA == MIPGEMM_ROW_MAJOR ? 1 : lda;
@@ -63,6 +61,27 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
   return 0;
 }
 
+// The packed route: operands that the direct-to-LDS kernels cannot stream (a base or a
+// leading dimension that is not a multiple of 16 bytes, k not a multiple of 64) are first
+// rewritten into the workspace.  Worth two more launches and one more pass over A and B once
+// the product is big enough and neither side is skinny.
+static int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
+// long k: a multiple of 128 for the kernel with 128-deep k blocks; short k: of 64
+static int64_t padded_k(int64_t k) { return k >= 1024 ? round_up(k, 128) : round_up(k, 64); }
+static size_t packed_bytes(int64_t m, int64_t n, int64_t k) {
+  return static_cast<size_t>(round_up(m * padded_k(k), 256) + round_up(n * padded_k(k), 256));
+}
+static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
+  // measured: 1000^3 gains (26 -> 15 us with a row-major B), 300 x 700 x 777 and
+  // 3000 x 5000 x 64 do not
+  return m >= 64 && n >= 64 && k >= 256 && (double)m * (double)n * (double)k >= 536870912.0;  // 2^29
+}
+static bool packing_pays(const Problem &p, const mip::Plan &plan) {
+  if (plan.kind != mip::KIND_STAGED && plan.kind != mip::KIND_SIMPLE) return false;
+  if (p.batch != 1 || p.conv) return false;
+  return packing_size_ok(p.m, p.n, p.k);
+}
+
 int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
         int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb, int orderB,
         void *C, int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
@@ -82,7 +101,24 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
   if (p.batch == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
-  const mip::Plan plan = mip::choose_plan(p);
+  mip::Plan plan = mip::choose_plan(p);
+  if (packing_pays(p, plan) && workspace && workspace_bytes >= packed_bytes(p.m, p.n, p.k)) {
+    // Pack A and Pack B (paper Section 4.1) into aligned, k-contiguous buffers with the k
+    // tail zeroed, so that the direct-to-LDS kernels can stream them
+    const int64_t kp = padded_k(p.k);
+    uint8_t *Ap = static_cast<uint8_t *>(workspace);
+    uint8_t *Bp = Ap + round_up(p.m * kp, 256);
+    e = mip::launch_pack_b(p.k, p.m, static_cast<const uint8_t *>(p.A), p.a_sk == 1 ? p.a_sm : p.a_sk,
+                           p.a_sk == 1, Ap, kp, s, kp);
+    if (e != hipSuccess) return static_cast<int>(e);
+    e = mip::launch_pack_b(p.k, p.n, static_cast<const uint8_t *>(p.B), p.b_sk == 1 ? p.b_sn : p.b_sk,
+                           p.b_sk == 1, Bp, kp, s, kp);
+    if (e != hipSuccess) return static_cast<int>(e);
+    p.A = Ap; p.a_sm = kp; p.a_sk = 1;
+    p.B = Bp; p.b_sn = kp; p.b_sk = 1;
+    p.k = kp;
+    plan = mip::choose_plan(p);
+  }
   switch (plan.kind) {
     case mip::KIND_NONE: break;
     case mip::KIND_FILL: e = mip::launch_fill_zero(p, s); break;
@@ -219,10 +255,18 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t ld
                  workspace_bytes, stream, scale);
 }
 
-size_t mipgemm_workspace_size(int64_t, int64_t, int64_t, int, int, int) {
-  // No kernel stages anything outside A, B and C: operands go straight from
-  // their own storage through LDS into the matrix cores.
-  return 0;
+size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k, int orderA, int orderB, int orderC) {
+  // Operands that are 16-byte aligned with k a multiple of 64 go straight from their own
+  // storage through LDS into the matrix cores; the others are packed first when that pays.
+  if (m < 0 || n < 0 || k < 0 || m > MIPGEMM_MAX_DIM || n > MIPGEMM_MAX_DIM || k > MIPGEMM_MAX_DIM)
+    return 0;
+  if (!mip::order_ok(orderA) || !mip::order_ok(orderB) || !mip::order_ok(orderC)) return 0;
+  if (!mip::packing_size_ok(m, n, k)) return 0;
+  // the tightest leading dimensions of these orders, on 16-byte aligned pointers
+  const bool a_ok = (orderA == MIPGEMM_ROW_MAJOR ? k : m) % 16 == 0;
+  const bool b_ok = (orderB == MIPGEMM_ROW_MAJOR ? n : k) % 16 == 0;
+  if (a_ok && b_ok && k % 64 == 0) return 0;
+  return mip::packed_bytes(m, n, k);
 }
 
 const char *mipgemm_strerror(int code) {
@@ -254,6 +298,37 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, i
                                   orderC, MIPGEMM_OVERWRITE, nullptr, 0, &p);
   if (rc != 0) return "invalid";
   return mip::plan_name(mip::choose_plan(p));
+}
+
+const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k, int64_t lda,
+                                                int orderA, int64_t ldb, int orderB, int64_t ldc,
+                                                int orderC, int a_unsigned, int b_unsigned,
+                                                int aligned16) {
+  Problem p;
+  const void *fake = reinterpret_cast<const void *>(aligned16 ? uintptr_t(4096) : uintptr_t(4097));
+  int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, fake, lda, orderA, fake, ldb,
+                                  orderB, reinterpret_cast<int32_t *>(uintptr_t(4096)), ldc,
+                                  orderC, MIPGEMM_OVERWRITE, nullptr, 0, &p);
+  if (rc != 0) return "invalid";
+  const mip::Plan plan = mip::choose_plan(p);
+  if (!mip::packing_pays(p, plan)) return mip::plan_name(plan);
+  // the plan for the packed operands: aligned, k-contiguous, k padded
+  const int64_t kp = mip::padded_k(p.k);
+  p.A = p.B = reinterpret_cast<const void *>(uintptr_t(4096));
+  p.a_sm = p.b_sn = kp;
+  p.a_sk = p.b_sk = 1;
+  p.k = kp;
+#define MIP_NAME(x) {x, "packed+" x}
+  static const char *const names[][2] = {
+      MIP_NAME("mfma_dma256"), MIP_NAME("mfma_dma128"), MIP_NAME("mfma_dma64"),
+      MIP_NAME("mfma_dma64x256"), MIP_NAME("mfma_dma256x64"), MIP_NAME("mfma_dma64x128"),
+      MIP_NAME("mfma_dma128x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_slab16"),
+      MIP_NAME("mfma_slab32")};
+#undef MIP_NAME
+  const char *base = mip::plan_name(mip::choose_plan(p));
+  for (const auto &nm : names)
+    if (!std::strcmp(nm[0], base)) return nm[1];
+  return "packed";
 }
 
 }  // extern "C"

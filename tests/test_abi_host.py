@@ -106,7 +106,10 @@ def test_variant_choice(M):
     name = M.mipgemm_variant_name
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256_k128"
     assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
-    assert name(4096, 4096, 1024, 1024, 0, 4096, 0, 4096, 0) == "mfma_dma256"
+    assert name(4096, 4096, 1024, 1024, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
+    assert name(4096, 4096, 1088, 1088, 0, 4096, 0, 4096, 0) == "mfma_dma256"        # k % 128 != 0
+    assert name(4352, 4352, 4096, 4096, 0, 4352, 0, 4352, 0) == "mfma_dma128"        # 289 tiles of 256 x 256: a second round for 33
+    assert name(4608, 4608, 4096, 4096, 0, 4608, 0, 4608, 0) == "mfma_dma256_k128"
     # unaligned operands cannot use the direct-to-LDS kernels
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128"
     # a ragged row edge can, but not with the deep-k kernel; an unsigned operand can

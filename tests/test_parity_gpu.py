@@ -527,3 +527,87 @@ def test_calls_from_two_host_threads_on_two_streams(gpu, oracle):
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads)
     assert failures == []
+
+
+# ---------------------------------------------------------------------------
+# the packed route: operands the direct-to-LDS kernels cannot stream, given a workspace
+# ---------------------------------------------------------------------------
+
+def _packed_bytes(m, n, k):
+    kp = (k + 127) // 128 * 128 if k >= 1024 else (k + 63) // 64 * 64
+    up = lambda x: (x + 255) // 256 * 256
+    return up(m * kp) + up(n * kp)
+
+
+def _packed_cases():
+    # (m, n, k, orderA, orderB, orderC, pad, a_unsigned, b_unsigned, mode)
+    out = []
+    for oa, ob, oc in ((0, 0, 0), (0, 1, 0), (1, 0, 0), (1, 1, 0), (0, 0, 1), (1, 0, 1)):
+        out.append((1000, 999, 1001, oa, ob, oc, 0, False, False, oa ^ ob))
+    out += [(1000, 999, 1001, 0, 0, 0, 3, True, False, 1), (1000, 999, 1001, 1, 1, 1, 5, False, True, 0),
+            (1300, 1700, 257, 0, 0, 0, 0, False, False, 0),    # m not a multiple of the tile, short odd k
+            (130, 4100, 1010, 1, 0, 0, 1, True, False, 0),
+            (3000, 5000, 320, 0, 0, 0, 0, False, False, 1),    # k already fine, ldb = 5000 is not
+            (515, 520, 2049, 0, 1, 0, 0, False, True, 0),      # long k: padded to a multiple of 128
+            (2000, 3000, 1999, 0, 0, 0, 0, False, False, 0)]
+    return out
+
+
+@pytest.mark.parametrize("spec", _packed_cases(), ids=lambda s: "x".join(map(lambda v: str(int(v)), s)))
+def test_packed_route_with_a_workspace(gpu, oracle, spec):
+    import torch
+    m, n, k, oa, ob, oc, pad, au, bu, mode = spec
+    print("packed", spec, flush=True)
+    case = W.Case("packed_" + "_".join(str(int(v)) for v in spec), 8, 0, m, n, k,
+                  a_unsigned=au, b_unsigned=bu, orderA=oa, orderB=ob,
+                  orderC=oc, pad=pad, mode=mode, c_dist=("uniform", -1000, 1000), seed=61)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    name = gpu.mipgemm_variant_name_with_workspace(m, n, k, case.lda, oa, case.ldb, ob, case.ldc, oc,
+                                                   au, bu, True)
+    assert name.startswith("packed+mfma_"), name
+    need = _packed_bytes(*((m, n, k) if oc == 0 else (n, m, k)))
+    if pad == 0:
+        assert gpu.mipgemm_workspace_size(m, n, k, oa, ob, oc) == need
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    fn = getattr(gpu, "mipgemm_" + case.entry)
+    for given in (need, need - 1):                   # one byte short: the in-place kernels, same bits
+        dC = torch.from_numpy(ops.C).cuda()
+        ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+        fn(m, n, k, dA, case.lda, oa, dB, case.ldb, ob, dC, case.ldc, oc, mode,
+           workspace=ws, workspace_bytes=given)
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy(), want), "workspace_bytes %d" % given
+        assert (ws[need:].cpu().numpy() == 0x5A).all()           # nothing written past the workspace
+        if given < need:
+            assert (ws.cpu().numpy() == 0x5A).all()              # and nothing at all when it is too small
+
+
+def test_packed_route_for_unaligned_pointers_and_float_output(gpu, oracle):
+    """Aligned sizes on pointers that are not: packed too.  And the dequantising entry point."""
+    import torch
+    m, n, k = 1024, 768, 1024
+    case = W.Case("packed_ptr", 8, 1, m, n, k, seed=62)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    assert gpu.mipgemm_variant_name_with_workspace(m, n, k, k, 0, n, 0, n, 0, False, False, False) \
+        .startswith("packed+")
+    assert gpu.mipgemm_workspace_size(m, n, k, 0, 0, 0) == 0     # by the sizes alone nothing to pack
+    need = _packed_bytes(m, n, k)
+    holdA = torch.zeros(ops.A.size + 16, dtype=torch.uint8, device="cuda")
+    holdB = torch.zeros(ops.B.size + 16, dtype=torch.uint8, device="cuda")
+    dA, dB = holdA[1:1 + ops.A.size], holdB[3:3 + ops.B.size]    # 1 and 3 bytes off
+    dA.copy_(torch.from_numpy(ops.A.view(np.uint8)))
+    dB.copy_(torch.from_numpy(ops.B.view(np.uint8)))
+    dC = torch.from_numpy(ops.C).cuda()
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    gpu.mipgemm_s8s8s32(m, n, k, dA, k, 0, dB, n, 0, dC, n, 0, 0, workspace=ws, workspace_bytes=need)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+    assert ws.cpu().numpy().any()                                 # the packed operands are there
+    dF = torch.zeros(m * n, dtype=torch.float32, device="cuda")
+    gpu.mipgemm_s8s8f32(m, n, k, dA, k, 0, dB, n, 0, dF, n, 0, 0, workspace=ws, workspace_bytes=need,
+                        scale=0.25)
+    torch.cuda.synchronize()
+    assert np.array_equal(dF.cpu().numpy(), want.astype(np.float32) * np.float32(0.25))
