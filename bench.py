@@ -177,11 +177,14 @@ def time_case_graph(M, case, calls=24, replays=6, footprint=0):
     hC = torch.from_numpy(ops.C)
     bufs = [(hA.cuda(), hB.cuda(), hC.cuda()) for _ in range(sets)]
     fn = getattr(M, "mipgemm_" + case.entry)
+    # the workspace the header recommends (operands that have to be packed first)
+    need = M.mipgemm_workspace_size(case.m, case.n, case.k, case.orderA, case.orderB, case.orderC)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda") if need else None
 
     def call(i):
         dA, dB, dC = bufs[i % sets]
         fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
-           dC, case.ldc, case.orderC, case.mode)
+           dC, case.ldc, case.orderC, case.mode, workspace=ws, workspace_bytes=need)
 
     call(0)
     torch.cuda.synchronize()
@@ -221,9 +224,10 @@ def run_suite(M, args):
         cold = warm if big else time_case_graph(M, case, calls=calls, footprint=600 * 10 ** 6)
         t_mfma = case.ops / (INT8_MFMA_PEAK_TOPS * 1e12)
         t_hbm = case.algorithmic_bytes / (HBM_PEAK_GBS * 1e9)
-        variant = M.mipgemm_variant_name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
-                                         case.orderB, case.ldc, case.orderC, case.a_unsigned,
-                                         case.b_unsigned, True)
+        need = M.mipgemm_workspace_size(case.m, case.n, case.k, case.orderA, case.orderB, case.orderC)
+        name_of = M.mipgemm_variant_name_with_workspace if need else M.mipgemm_variant_name
+        variant = name_of(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB,
+                          case.ldc, case.orderC, case.a_unsigned, case.b_unsigned, True)
         print("| %s | %s | %d | %d | %d | %s | %.1f | %.1f | %.1f | %.0f | %.0f | %s | %.3f |" % (
             case.name, case.entry, case.m, case.n, case.k, variant, warm, cold,
             case.ops / cold / 1e6, case.algorithmic_bytes / warm / 1e3,
@@ -242,6 +246,58 @@ def run_suite(M, args):
         b = time_case(M, case, args.steps, args.warmup, dequant=True)
         print("| %s | %s | %.1f | %.1f |" % (name, case.entry.replace("s32", "f32"), a * 1e3, b * 1e3),
               flush=True)
+
+
+def run_packed_table(M):
+    """Large products on operands that cannot be streamed as they are stored (odd sizes:
+    no 16-byte alignment, k not a multiple of 64): the kernels that read them in place
+    against the packed route (Pack A / Pack B into the workspace, Section 4.1), HIP graph
+    replay, warm."""
+    import torch
+    rng = np.random.default_rng(5)
+    print()
+    print("Unaligned operands, s8 x s8 -> s32, row-major C, us per call without and with the workspace:")
+    print()
+    print("| m | n | k | A | B | kernel in place | us | TOPS | with workspace | us | TOPS |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    for (m, n, k) in ((1000, 999, 1001), (2000, 3000, 1999), (4095, 4097, 4099), (8191, 8193, 8195)):
+        hA = torch.from_numpy(rng.integers(-128, 128, size=m * k, dtype=np.int8).view(np.uint8))
+        hB = torch.from_numpy(rng.integers(-128, 128, size=k * n, dtype=np.int8).view(np.uint8))
+        dA, dB = hA.cuda(), hB.cuda()
+        dC = torch.zeros(m * n, dtype=torch.int32, device="cuda")
+        for oa, ob in ((W.ROW_MAJOR, W.ROW_MAJOR), (W.ROW_MAJOR, W.COL_MAJOR), (W.COL_MAJOR, W.ROW_MAJOR)):
+            lda = k if oa == W.ROW_MAJOR else m
+            ldb = n if ob == W.ROW_MAJOR else k
+            need = M.mipgemm_workspace_size(m, n, k, oa, ob, W.ROW_MAJOR)
+            ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+            times = []
+            for given in (0, need):
+                def call():
+                    M.mipgemm_s8s8s32(m, n, k, dA, lda, oa, dB, ldb, ob, dC, n, W.ROW_MAJOR, W.OVERWRITE,
+                                      workspace=ws if given else None, workspace_bytes=given)
+                call()
+                torch.cuda.synchronize()
+                calls = 4
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for _ in range(calls):
+                        call()
+                graph.replay()
+                torch.cuda.synchronize()
+                ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ev0.record()
+                for _ in range(3):
+                    graph.replay()
+                ev1.record()
+                torch.cuda.synchronize()
+                times.append(ev0.elapsed_time(ev1) / (calls * 3) * 1e3)
+            names = (M.mipgemm_variant_name(m, n, k, lda, oa, ldb, ob, n, W.ROW_MAJOR),
+                     M.mipgemm_variant_name_with_workspace(m, n, k, lda, oa, ldb, ob, n, W.ROW_MAJOR))
+            ops = 2.0 * m * n * k
+            print("| %d | %d | %d | %s | %s | %s | %.1f | %.0f | %s | %.1f | %.0f |" % (
+                m, n, k, "row" if oa == W.ROW_MAJOR else "col", "row" if ob == W.ROW_MAJOR else "col",
+                names[0], times[0], ops / times[0] / 1e6, names[1], times[1], ops / times[1] / 1e6),
+                flush=True)
 
 
 def run_conv_table(M):
@@ -551,6 +607,7 @@ def main():
         return
     if args.suite:
         run_suite(M, args)
+        run_packed_table(M)
         run_conv_table(M)
         run_network_table(M)
         run_pack_table(M)
