@@ -24,15 +24,28 @@ constexpr int PT = 64;      // tile edge
 constexpr int PITCH = 80;   // LDS row pitch: a multiple of 16 that staggers the banks
 
 // B(p, j) = B[p * ldb + j]  ->  P[j * ldp + p]
-// Entries k .. kfill - 1 of every packed column are written as zeros (kfill == k: none).
-__global__ __launch_bounds__(256) void pack_transpose_kernel(int64_t k, int64_t kfill, int64_t n,
-                                                             const uint8_t *B, int64_t ldb,
-                                                             uint8_t *P, int64_t ldp,
-                                                             int wide_load, int wide_store,
-                                                             int tiles_n) {
-  __shared__ __attribute__((aligned(16))) uint8_t tile[PT * PITCH];
+// One packing job: the k x n matrix at B (k_contiguous: column j at B + j * ldb; else row
+// p at B + p * ldb) to P, column j at P + j * ldp, entries k .. kfill - 1 of every packed
+// column written as zeros (kfill == k: none).
+struct PackJob {
+  int64_t k, kfill, n;
+  const uint8_t *B;
+  int64_t ldb;
+  uint8_t *P;
+  int64_t ldp;
+  int k_contiguous, wide_load, wide_store;
+  int tiles_n;      // transposing job: 64 x 64 tiles along n
+  unsigned blocks;  // workgroups this job is given
+};
+
+// block: this workgroup's number within the job
+__device__ __forceinline__ void pack_transpose_body(const PackJob &J, unsigned block, uint8_t *tile) {
+  const int64_t k = J.k, kfill = J.kfill, n = J.n, ldb = J.ldb, ldp = J.ldp;
+  const uint8_t *B = J.B;
+  uint8_t *P = J.P;
+  const int wide_load = J.wide_load, wide_store = J.wide_store, tiles_n = J.tiles_n;
   const int t = threadIdx.x;
-  const int64_t p0 = (int64_t)(blockIdx.x / tiles_n) * PT, n0 = (int64_t)(blockIdx.x % tiles_n) * PT;
+  const int64_t p0 = (int64_t)(block / tiles_n) * PT, n0 = (int64_t)(block % tiles_n) * PT;
   {
     const int p = t >> 2, c = (t & 3) * 16;  // k row of the tile, first of 16 columns
     const int64_t row = p0 + p, col = n0 + c;
@@ -73,12 +86,14 @@ __global__ __launch_bounds__(256) void pack_transpose_kernel(int64_t k, int64_t 
 
 // B already k-contiguous: column j moves from B + j * ldb to P + j * ldp
 // wide_load / wide_store: the source / the destination is 16-byte aligned, pitch included
-__global__ __launch_bounds__(256) void pack_copy_kernel(int64_t k, int64_t kfill, int64_t n,
-                                                        const uint8_t *B, int64_t ldb, uint8_t *P,
-                                                        int64_t ldp, int wide_load, int wide_store) {
+__device__ __forceinline__ void pack_copy_body(const PackJob &J, unsigned block) {
+  const int64_t k = J.k, kfill = J.kfill, n = J.n, ldb = J.ldb, ldp = J.ldp;
+  const uint8_t *B = J.B;
+  uint8_t *P = J.P;
+  const int wide_load = J.wide_load, wide_store = J.wide_store;
   const int64_t pieces = (kfill + 15) / 16;
   const int64_t total = pieces * n;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+  for (int64_t i = (int64_t)block * 256 + threadIdx.x; i < total; i += (int64_t)J.blocks * 256) {
     const int64_t j = i / pieces, p = (i - j * pieces) * 16;
     const uint8_t *src = B + j * ldb + p;
     uint8_t *dst = P + j * ldp + p;
@@ -98,28 +113,65 @@ __global__ __launch_bounds__(256) void pack_copy_kernel(int64_t k, int64_t kfill
   }
 }
 
+// One or two jobs in one launch: the first a.blocks workgroups work on a, the rest on b
+// (Pack A and Pack B of a GEMM are independent of each other).
+__global__ __launch_bounds__(256) void pack_kernel(PackJob a, PackJob b) {
+  __shared__ __attribute__((aligned(16))) uint8_t tile[PT * PITCH];
+  const bool first = blockIdx.x < a.blocks;  // workgroup-uniform
+  const PackJob &J = first ? a : b;
+  const unsigned block = first ? blockIdx.x : blockIdx.x - a.blocks;
+  if (J.k_contiguous) pack_copy_body(J, block);
+  else pack_transpose_body(J, block, tile);
+}
+
 bool aligned16(const void *p, int64_t ld) {
   return reinterpret_cast<uintptr_t>(p) % 16 == 0 && ld % 16 == 0;
+}
+
+// false: the job is too large for one launch
+bool make_job(int64_t k, int64_t kfill, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc,
+              uint8_t *P, int64_t ldp, PackJob *out) {
+  PackJob J;
+  J.k = k; J.kfill = kfill < k ? k : kfill; J.n = n;
+  J.B = B; J.ldb = ldb; J.P = P; J.ldp = ldp;
+  J.k_contiguous = b_kc;
+  J.wide_load = aligned16(B, ldb);
+  J.wide_store = aligned16(P, ldp);
+  J.tiles_n = 1;
+  if (J.kfill == 0 || n == 0) {
+    J.blocks = 0;
+  } else if (b_kc) {
+    int64_t blocks = ((J.kfill + 15) / 16 * n + 255) / 256;
+    J.blocks = (unsigned)(blocks > 256 * 64 ? 256 * 64 : blocks);
+  } else {
+    const int64_t tiles_k = (J.kfill + PT - 1) / PT, tiles_n = (n + PT - 1) / PT;
+    if (tiles_k * tiles_n > 0x3fffffff) return false;
+    J.tiles_n = (int)tiles_n;
+    J.blocks = (unsigned)(tiles_k * tiles_n);
+  }
+  *out = J;
+  return true;
 }
 
 }  // namespace
 
 hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
                          int64_t ldp, hipStream_t s, int64_t kfill) {
-  if (kfill < k) kfill = k;
-  if (kfill == 0 || n == 0) return hipSuccess;
-  if (b_kc) {
-    int64_t blocks = ((kfill + 15) / 16 * n + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;
-    hipLaunchKernelGGL(pack_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k, kfill, n, B, ldb,
-                       P, ldp, (int)aligned16(B, ldb), (int)aligned16(P, ldp));
-  } else {
-    const int64_t tiles_k = (kfill + PT - 1) / PT, tiles_n = (n + PT - 1) / PT;
-    if (tiles_k * tiles_n > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(pack_transpose_kernel, dim3((unsigned)(tiles_k * tiles_n)), dim3(256), 0, s,
-                       k, kfill, n, B, ldb, P, ldp, (int)aligned16(B, ldb), (int)aligned16(P, ldp),
-                       (int)tiles_n);
-  }
+  PackJob J, none = {};
+  if (!make_job(k, kfill, n, B, ldb, b_kc, P, ldp, &J)) return hipErrorInvalidValue;
+  if (J.blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(pack_kernel, dim3(J.blocks), dim3(256), 0, s, J, none);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_pair(int64_t k, int64_t kfill, int64_t m, const uint8_t *A, int64_t lda,
+                            bool a_kc, uint8_t *Ap, int64_t n, const uint8_t *B, int64_t ldb,
+                            bool b_kc, uint8_t *Bp, int64_t ldp, hipStream_t s) {
+  PackJob a, b;
+  if (!make_job(k, kfill, m, A, lda, a_kc, Ap, ldp, &a) || !make_job(k, kfill, n, B, ldb, b_kc, Bp, ldp, &b))
+    return hipErrorInvalidValue;
+  if (a.blocks + b.blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(pack_kernel, dim3(a.blocks + b.blocks), dim3(256), 0, s, a, b);
   return hipGetLastError();
 }
 

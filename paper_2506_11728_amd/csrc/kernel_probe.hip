@@ -90,9 +90,9 @@ extern "C" int mipgemm_mfma_ceiling(int pattern, int iterations, void *stream, d
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     if (e == hipSuccess) e = hipGetLastError();
   }
-  if (e0) hipEventDestroy(e0);
-  if (e1) hipEventDestroy(e1);
-  if (sink) hipFree(sink);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (sink) (void)hipFree(sink);
   if (e != hipSuccess) return (int)e;
   // one wave per SIMD, 4 SIMDs per compute unit, 2 * 128 * 128 * 64 operations per wave and iteration
   *tops = (double)cus * 4.0 * iterations * 2.0 * 128 * 128 * 64 / (ms * 1e-3) / 1e12;

@@ -106,6 +106,13 @@ hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bo
 bool conv_rows_eligible(const Problem &p);
 hipError_t launch_conv_rows(const Problem &p, hipStream_t s);
 
+// Both operands of a GEMM packed in one launch: A (m rows of k, a_kc: k-contiguous with pitch
+// lda, else k rows of m with pitch lda) to Ap and B (n columns of k, likewise) to Bp, both
+// k-contiguous with pitch ldp, entries k .. kfill - 1 zeroed.
+hipError_t launch_pack_pair(int64_t k, int64_t kfill, int64_t m, const uint8_t *A, int64_t lda,
+                            bool a_kc, uint8_t *Ap, int64_t n, const uint8_t *B, int64_t ldb,
+                            bool b_kc, uint8_t *Bp, int64_t ldp, hipStream_t s);
+
 bool dma_eligible(const Problem &p, Shape shape);
 hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);
 

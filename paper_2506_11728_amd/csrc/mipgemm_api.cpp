@@ -108,11 +108,10 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
     const int64_t kp = padded_k(p.k);
     uint8_t *Ap = static_cast<uint8_t *>(workspace);
     uint8_t *Bp = Ap + round_up(p.m * kp, 256);
-    e = mip::launch_pack_b(p.k, p.m, static_cast<const uint8_t *>(p.A), p.a_sk == 1 ? p.a_sm : p.a_sk,
-                           p.a_sk == 1, Ap, kp, s, kp);
-    if (e != hipSuccess) return static_cast<int>(e);
-    e = mip::launch_pack_b(p.k, p.n, static_cast<const uint8_t *>(p.B), p.b_sk == 1 ? p.b_sn : p.b_sk,
-                           p.b_sk == 1, Bp, kp, s, kp);
+    e = mip::launch_pack_pair(p.k, kp, p.m, static_cast<const uint8_t *>(p.A),
+                              p.a_sk == 1 ? p.a_sm : p.a_sk, p.a_sk == 1, Ap, p.n,
+                              static_cast<const uint8_t *>(p.B), p.b_sk == 1 ? p.b_sn : p.b_sk,
+                              p.b_sk == 1, Bp, kp, s);
     if (e != hipSuccess) return static_cast<int>(e);
     p.A = Ap; p.a_sm = kp; p.a_sk = 1;
     p.B = Bp; p.b_sn = kp; p.b_sk = 1;
