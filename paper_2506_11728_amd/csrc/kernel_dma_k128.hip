@@ -5,7 +5,10 @@
 //
 // Preconditions, checked on the host (dma_k128_eligible): m and n multiples of
 // 256, k a multiple of 128, 16-byte aligned operand bases and leading
-// dimensions, 256 * ld below 2^31.
+// dimensions, 256 * ld below 2^31.  RAGGED form: any m and n, on k-contiguous
+// operands whose buffers are readable up to the next multiple of 256 rows (the
+// packed operands of the library's own packing step); whole tiles are loaded and
+// multiplied, the write-back stops at the edge of C.
 #include "dma_common.h"
 
 namespace mip {
@@ -18,6 +21,7 @@ struct DmaParams {
   const uint8_t *A, *B;
   int32_t *C;
   int64_t lda, ldb, ldc;  // the one stride of each operand that is not 1
+  int64_t m, n;           // rows and columns of C (RAGGED form only)
   int tiles_m, tiles_n;
   int nkt;                // k / 128
   int accumulate;         // C += instead of C =
@@ -37,7 +41,7 @@ constexpr int STAGE2_BYTES = (DM + DN) * KD2;          // 64 KiB
 constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
-template <bool A_KC, bool B_KC, int UNS>
+template <bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   using SA = Stage<DM, A_KC, KD2>;
   using SB = Stage<DN, B_KC, KD2>;
@@ -169,22 +173,28 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   // the last step has no barrier of its own: wait until no wave reads the stages any more
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
-  store_blocks_via_lds<4, 4>(acc, P.C + (m0 + wm * 128) * P.ldc + n0 + wn * 128, P.ldc,
-                             P.accumulate != 0, lane,
-                             reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES),
-                             Finish{P.scale, P.out_float});
+  const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;  // the wave's 128 x 128 patch
+  if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
+    store_blocks_via_lds<4, 4>(acc, P.C + mw * P.ldc + nw, P.ldc, P.accumulate != 0, lane,
+                               reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES),
+                               Finish{P.scale, P.out_float});
+  else if (mw < P.m && nw < P.n)
+    store_blocks<4, 4, false>(acc, P.C + mw * P.ldc + nw, P.ldc, P.m - mw, P.n - nw,
+                              P.accumulate != 0, lane, Finish{P.scale, P.out_float});
 }
 
 }  // namespace
 
 bool dma_k128_eligible(const Problem &p) {
-  if (p.conv || p.batch != 1 || p.m % DM || p.n % DN || p.k % KD2 || p.k < KD2) return false;
+  if (p.conv || p.batch != 1 || p.k % KD2 || p.k < KD2) return false;
+  // ragged m or n: only on k-contiguous operands padded to whole tiles of rows
+  if ((p.m % DM || p.n % DN) && !(p.rows_padded_to_256 && p.a_sk == 1 && p.b_sk == 1)) return false;
   const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
   const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
   if (lda % 16 || ldb % 16) return false;
   if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
   if (256 * lda >= ((int64_t)1 << 31) || 256 * ldb >= ((int64_t)1 << 31)) return false;
-  if ((p.m / DM) * (p.n / DN) > ((int64_t)1 << 30)) return false;
+  if (((p.m + DM - 1) / DM) * ((p.n + DN - 1) / DN) > ((int64_t)1 << 30)) return false;
   return true;
 }
 
@@ -196,8 +206,10 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
   P.lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
   P.ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
   P.ldc = p.ldc;
-  P.tiles_m = (int)(p.m / DM);
-  P.tiles_n = (int)(p.n / DN);
+  P.m = p.m;
+  P.n = p.n;
+  P.tiles_m = (int)((p.m + DM - 1) / DM);
+  P.tiles_n = (int)((p.n + DN - 1) / DN);
   P.nkt = (int)(p.k / KD2);
   P.accumulate = p.accumulate;
   P.out_float = p.out_float;
@@ -211,7 +223,10 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
 #define MIP_PICK(AK, BKC)                                                        \
   kern = uns == 0 ? dma128_kernel<AK, BKC, 0>                                    \
                   : (uns == 1 ? dma128_kernel<AK, BKC, 1> : dma128_kernel<AK, BKC, 2>)
-  if (a_kc && b_kc) MIP_PICK(true, true);
+  if (p.m % DM || p.n % DN)
+    kern = uns == 0 ? dma128_kernel<true, true, 0, true>
+                    : (uns == 1 ? dma128_kernel<true, true, 1, true> : dma128_kernel<true, true, 2, true>);
+  else if (a_kc && b_kc) MIP_PICK(true, true);
   else if (a_kc) MIP_PICK(true, false);
   else if (b_kc) MIP_PICK(false, true);
   else MIP_PICK(false, false);

@@ -39,6 +39,9 @@ struct Problem {
   // zero fill and the simple kernel take a batch (grid.z).
   int64_t batch = 1;
   int64_t a_sb = 0, b_sb = 0, c_sb = 0;
+  // A and B are the library's own packed buffers: k-contiguous, and readable (with whatever
+  // contents) up to the next multiple of 256 rows, so that whole tiles may be fetched
+  bool rows_padded_to_256 = false;
   // not null: A is never materialised, the kernel gathers it from the image tensor
   // (only the direct-to-LDS tile kernels can; a_sm is then the nominal row length k)
   const ConvGeom *conv = nullptr;

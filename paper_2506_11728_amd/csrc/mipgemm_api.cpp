@@ -68,8 +68,9 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
 static int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 // long k: a multiple of 128 for the kernel with 128-deep k blocks; short k: of 64
 static int64_t padded_k(int64_t k) { return k >= 1024 ? round_up(k, 128) : round_up(k, 64); }
+// rows in whole tiles of 256, so that the kernel for large problems may fetch whole tiles
 static size_t packed_bytes(int64_t m, int64_t n, int64_t k) {
-  return static_cast<size_t>(round_up(m * padded_k(k), 256) + round_up(n * padded_k(k), 256));
+  return static_cast<size_t>((round_up(m, 256) + round_up(n, 256)) * padded_k(k));
 }
 static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
   // measured: 1000^3 gains (26 -> 15 us with a row-major B), 300 x 700 x 777 and
@@ -107,7 +108,7 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
     // tail zeroed, so that the direct-to-LDS kernels can stream them
     const int64_t kp = padded_k(p.k);
     uint8_t *Ap = static_cast<uint8_t *>(workspace);
-    uint8_t *Bp = Ap + round_up(p.m * kp, 256);
+    uint8_t *Bp = Ap + round_up(p.m, 256) * kp;
     e = mip::launch_pack_pair(p.k, kp, p.m, static_cast<const uint8_t *>(p.A),
                               p.a_sk == 1 ? p.a_sm : p.a_sk, p.a_sk == 1, Ap, p.n,
                               static_cast<const uint8_t *>(p.B), p.b_sk == 1 ? p.b_sn : p.b_sk,
@@ -116,6 +117,7 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
     p.A = Ap; p.a_sm = kp; p.a_sk = 1;
     p.B = Bp; p.b_sn = kp; p.b_sk = 1;
     p.k = kp;
+    p.rows_padded_to_256 = true;
     plan = mip::choose_plan(p);
   }
   switch (plan.kind) {
@@ -317,6 +319,7 @@ const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k,
   p.a_sm = p.b_sn = kp;
   p.a_sk = p.b_sk = 1;
   p.k = kp;
+  p.rows_padded_to_256 = true;
 #define MIP_NAME(x) {x, "packed+" x}
   static const char *const names[][2] = {
       MIP_NAME("mfma_dma256"), MIP_NAME("mfma_dma128"), MIP_NAME("mfma_dma64"),

@@ -536,7 +536,7 @@ def test_calls_from_two_host_threads_on_two_streams(gpu, oracle):
 def _packed_bytes(m, n, k):
     kp = (k + 127) // 128 * 128 if k >= 1024 else (k + 63) // 64 * 64
     up = lambda x: (x + 255) // 256 * 256
-    return up(m * kp) + up(n * kp)
+    return (up(m) + up(n)) * kp
 
 
 def _packed_cases():
@@ -549,7 +549,9 @@ def _packed_cases():
             (130, 4100, 1010, 1, 0, 0, 1, True, False, 0),
             (3000, 5000, 320, 0, 0, 0, 0, False, False, 1),    # k already fine, ldb = 5000 is not
             (515, 520, 2049, 0, 1, 0, 0, False, True, 0),      # long k: padded to a multiple of 128
-            (2000, 3000, 1999, 0, 0, 0, 0, False, False, 0)]
+            (2000, 3000, 1999, 0, 0, 0, 0, False, False, 0),
+            # 14 x 14 ragged tiles of 256 x 256: the kernel with 128-deep k blocks on padded rows
+            (3500, 3400, 1025, 1, 0, 0, 0, True, False, 1)]
     return out
 
 
@@ -566,6 +568,8 @@ def test_packed_route_with_a_workspace(gpu, oracle, spec):
     name = gpu.mipgemm_variant_name_with_workspace(m, n, k, case.lda, oa, case.ldb, ob, case.ldc, oc,
                                                    au, bu, True)
     assert name.startswith("packed+mfma_"), name
+    if (m, n, k) == (3500, 3400, 1025):
+        assert name == "packed+mfma_dma256_k128"
     need = _packed_bytes(*((m, n, k) if oc == 0 else (n, m, k)))
     if pad == 0:
         assert gpu.mipgemm_workspace_size(m, n, k, oa, ob, oc) == need
