@@ -615,3 +615,9 @@ def test_packed_route_for_unaligned_pointers_and_float_output(gpu, oracle):
                         scale=0.25)
     torch.cuda.synchronize()
     assert np.array_equal(dF.cpu().numpy(), want.astype(np.float32) * np.float32(0.25))
+    # a workspace that is itself off by a byte: the packed operands are then read in place
+    ws1 = torch.zeros(need + 16, dtype=torch.uint8, device="cuda")
+    dC.fill_(-5)
+    gpu.mipgemm_s8s8s32(m, n, k, dA, k, 0, dB, n, 0, dC, n, 0, 0, workspace=ws1[1:], workspace_bytes=need)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
