@@ -355,7 +355,12 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   P.c_sb = p.c_sb;
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits, (unsigned)p.batch);
-  const size_t lds = (size_t)DMA_STAGES * (BM + BN) * BK;
+  // a workgroup with fewer k blocks than stages never touches the later stages: leave them
+  // out, so that more workgroups of a short-k problem fit a compute unit (the write-back
+  // patches, one per wave, must still fit)
+  const int stages = P.kt_per_split < DMA_STAGES ? P.kt_per_split : DMA_STAGES;
+  size_t lds = (size_t)stages * (BM + BN) * BK;
+  if (lds < 4 * (size_t)STORE_PATCH_BYTES) lds = 4 * (size_t)STORE_PATCH_BYTES;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
   void (*kern)(DmaTileParams) = nullptr;
 #define MIP_PICK(AK, BKC)                                                          \
