@@ -589,7 +589,7 @@ def run_conv_layer(M, args):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (got --gpus %d)"
+        print("bench.py measures one GPU: the library has no multi-GPU path (got --gpus %d)"
               % args.gpus, file=sys.stderr)
         raise SystemExit(2)
 
