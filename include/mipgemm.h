@@ -304,8 +304,8 @@ int mipgemm_pack_b(int64_t k, int64_t n,
  * Bytes of device workspace with which a GEMM call of these sizes and orders
  * takes the packed route (see "Pointers" above), taking the tightest leading
  * dimensions and 16-byte aligned pointers: 0 when such operands are streamed as
- * they are, when the product is too small for packing to pay (m or n below 64,
- * k below 256, m*n*k below 2^29), and for invalid sizes.  Operands with other leading
+ * they are, when the shape is one for which packing does not pay (m or n below
+ * 96, k below 192, m*n*k below 2^22), and for invalid sizes.  Operands with other leading
  * dimensions or pointers need (round_up(m, 256) + round_up(n, 256)) * kp bytes,
  * kp = k rounded up to a multiple of 128 (of 64 when k < 1024); a call uses the packed route whenever
  * it would pay and the workspace it is given is that large.

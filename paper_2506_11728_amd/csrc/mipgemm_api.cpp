@@ -73,13 +73,20 @@ static size_t packed_bytes(int64_t m, int64_t n, int64_t k) {
   return static_cast<size_t>((round_up(m, 256) + round_up(n, 256)) * padded_k(k));
 }
 static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
-  // measured: 1000^3 gains (26 -> 15 us with a row-major B), 300 x 700 x 777 and
-  // 3000 x 5000 x 64 do not
-  return m >= 64 && n >= 64 && k >= 256 && (double)m * (double)n * (double)k >= 536870912.0;  // 2^29
+  // measured (us, worst to best layout, in place -> packed): 200^3 8.4-7.7 -> 7.5-7.3,
+  // 800^3 19-11 -> 9.8-9.4, 100 x 100 x 10001 35-18 -> 15, 128 x 3001 x 513 12.6-10.3 -> 9.6-8.8;
+  // but 64 x 1000 x 1000 8.8-7.8 -> 10, 1000^2 x 100 7.8-6.6 -> 8.3, 16 x 11009 x 4099 38-28 -> 45-31
+  return m >= 96 && n >= 96 && k >= 192 && (double)m * (double)n * (double)k >= 4194304.0;  // 2^22
 }
+// MIPGEMM_PACK pins the decision for tests and tuning: "always" packs whatever the
+// direct-to-LDS kernels cannot stream, however small; "never" leaves everything in place.
 static bool packing_pays(const Problem &p, const mip::Plan &plan) {
   if (plan.kind != mip::KIND_STAGED && plan.kind != mip::KIND_SIMPLE) return false;
-  if (p.batch != 1 || p.conv) return false;
+  if (p.batch != 1 || p.conv || p.m < 1 || p.n < 1 || p.k < 1) return false;
+  if (const char *e = std::getenv("MIPGEMM_PACK")) {
+    if (!std::strcmp(e, "always")) return true;
+    if (!std::strcmp(e, "never")) return false;
+  }
   return packing_size_ok(p.m, p.n, p.k);
 }
 

@@ -621,3 +621,37 @@ def test_packed_route_for_unaligned_pointers_and_float_output(gpu, oracle):
     gpu.mipgemm_s8s8s32(m, n, k, dA, k, 0, dB, n, 0, dC, n, 0, 0, workspace=ws1[1:], workspace_bytes=need)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("spec", [(65, 70, 100, 0, 0, 0, 0, False, False, 0), (7, 7, 3, 1, 0, 0, 17, True, False, 1),
+                                  (1, 4097, 513, 0, 0, 0, 17, False, False, 0), (100, 37, 51, 1, 1, 1, 3, False, True, 1),
+                                  (300, 200, 333, 0, 1, 0, 17, True, False, 1), (4095, 3, 2049, 0, 0, 1, 0, False, False, 0)],
+                         ids=lambda s: "x".join(map(lambda v: str(int(v)), s)))
+def test_packed_route_forced_on_small_and_skinny_shapes(gpu, oracle, spec):
+    """MIPGEMM_PACK=always takes the packed route whatever the size: ragged everything."""
+    import torch
+    m, n, k, oa, ob, oc, pad, au, bu, mode = spec
+    print("packed forced", spec, flush=True)
+    case = W.Case("packedf_" + "_".join(str(int(v)) for v in spec), 8, 0, m, n, k,
+                  a_unsigned=au, b_unsigned=bu, orderA=oa, orderB=ob, orderC=oc, pad=pad, mode=mode,
+                  c_dist=("uniform", -1000, 1000), seed=63)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    need = _packed_bytes(m, n, k)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+    ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    with VariantEnv("auto"):
+        os.environ["MIPGEMM_PACK"] = "always"
+        try:
+            assert gpu.mipgemm_variant_name_with_workspace(m, n, k, case.lda, oa, case.ldb, ob, case.ldc,
+                                                           oc, au, bu, True).startswith("packed")
+            getattr(gpu, "mipgemm_" + case.entry)(m, n, k, dA, case.lda, oa, dB, case.ldb, ob, dC,
+                                                  case.ldc, oc, mode, workspace=ws, workspace_bytes=need)
+        finally:
+            del os.environ["MIPGEMM_PACK"]
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+    assert (ws[need:].cpu().numpy() == 0x5A).all()
+    assert not (ws[:need].cpu().numpy() == 0x5A).all()           # the packed operands were written
