@@ -72,7 +72,12 @@ static int64_t padded_k(int64_t k) { return k >= 1024 ? round_up(k, 128) : round
 static size_t packed_bytes(int64_t m, int64_t n, int64_t k) {
   return static_cast<size_t>((round_up(m, 256) + round_up(n, 256)) * padded_k(k));
 }
+// sizes whose packed operands would not fit 2^62 bytes are never packed: no overflow in the sums
+static bool packable(int64_t m, int64_t n, int64_t k) {
+  return ((double)m + (double)n + 512.0) * ((double)k + 128.0) < 4.0e18;
+}
 static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
+  if (!packable(m, n, k)) return false;
   // measured (us, worst to best layout, in place -> packed): 200^3 8.4-7.7 -> 7.5-7.3,
   // 800^3 19-11 -> 9.8-9.4, 100 x 100 x 10001 35-18 -> 15, 128 x 3001 x 513 12.6-10.3 -> 9.6-8.8;
   // but 64 x 1000 x 1000 8.8-7.8 -> 10, 1000^2 x 100 7.8-6.6 -> 8.3, 16 x 11009 x 4099 38-28 -> 45-31
@@ -82,7 +87,7 @@ static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
 // direct-to-LDS kernels cannot stream, however small; "never" leaves everything in place.
 static bool packing_pays(const Problem &p, const mip::Plan &plan) {
   if (plan.kind != mip::KIND_STAGED && plan.kind != mip::KIND_SIMPLE) return false;
-  if (p.batch != 1 || p.conv || p.m < 1 || p.n < 1 || p.k < 1) return false;
+  if (p.batch != 1 || p.conv || p.m < 1 || p.n < 1 || p.k < 1 || !packable(p.m, p.n, p.k)) return false;
   if (const char *e = std::getenv("MIPGEMM_PACK")) {
     if (!std::strcmp(e, "always")) return true;
     if (!std::strcmp(e, "never")) return false;

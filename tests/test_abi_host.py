@@ -100,6 +100,15 @@ def test_strerror_and_workspace(M):
         assert str(-code) in M.mipgemm_strerror(code)
     assert "unknown" in M.mipgemm_strerror(-99)
     assert M.mipgemm_workspace_size(8192, 8192, 8192, 0, 0, 0) == 0
+    # odd sizes that are worth packing: rows in whole tiles of 256, k padded to 64 (128 from 1024 on)
+    assert M.mipgemm_workspace_size(1000, 999, 1001, 0, 0, 0) == (1024 + 1024) * 1024
+    assert M.mipgemm_workspace_size(1000, 999, 1001, 1, 1, 1) == (1024 + 1024) * 1024
+    assert M.mipgemm_workspace_size(300, 200, 333, 0, 0, 0) == (512 + 256) * 384
+    assert M.mipgemm_workspace_size(4096, 4096, 4100, 0, 0, 0) == (4096 + 4096) * 4224
+    assert M.mipgemm_workspace_size(64, 1000, 1001, 0, 0, 0) == 0          # skinny: packing does not pay
+    assert M.mipgemm_workspace_size(3000, 5000, 65, 0, 0, 0) == 0          # short k: neither
+    assert M.mipgemm_workspace_size(2**31 - 1, 2**31 - 1, 2**31 - 1, 0, 0, 0) == 0   # nothing overflows
+    assert M.mipgemm_workspace_size(-1, 5, 5, 0, 0, 0) == 0 and M.mipgemm_workspace_size(5, 5, 5, 0, 3, 0) == 0
 
 
 def test_variant_choice(M):
