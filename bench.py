@@ -338,17 +338,22 @@ def run_conv_table(M):
             n, k = b * ho * ho, hf * hf * ci
             dI, dF = torch.from_numpy(image).cuda(), torch.from_numpy(filt.view(np.uint8)).cuda()
             dO = torch.zeros(n * co, dtype=torch.int32, device="cuda")
-            ldm = (k + 15) // 16 * 16                      # the pitch the library writes the matrix with
-            dM = torch.zeros(n * ldm, dtype=torch.uint8, device="cuda")
+            ldm = (k + 15) // 16 * 16
+            dM = torch.zeros(n * ldm, dtype=torch.uint8, device="cuda")      # a ready-made matrix
             args = (b, hi, hi, ci, co, hf, hf, stride, pad)
+            os.environ["MIPGEMM_CONV"] = "im2col"
+            try:
+                need = M.mipgemm_conv_workspace_size(*args)                # of the written-out route
+            finally:
+                del os.environ["MIPGEMM_CONV"]
+            dW = torch.zeros(need, dtype=torch.uint8, device="cuda")
 
             def gemm_only():
                 M.mipgemm_s8u8s32(co, n, k, dF, k, W.ROW_MAJOR, dM, ldm, W.COL_MAJOR, dO, co,
                                   W.COL_MAJOR, W.OVERWRITE)
 
             def conv():
-                M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=dM,
-                                       workspace_bytes=n * ldm)
+                M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=dW, workspace_bytes=need)
 
             t_gemm = replay_us(gemm_only)
             os.environ["MIPGEMM_CONV"] = "im2col"

@@ -223,7 +223,8 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k,
  * with a short k (up to about 600, e.g. the 3-channel 7 x 7 first layer of a
  * network: a kernel that stages image row segments on chip).  Otherwise it
  * writes the augmented matrix into `workspace` first
- * (mipgemm_conv_workspace_size bytes) and runs mipgemm_s8u8s32 on it.  Pointers are device pointers owned by the caller;
+ * (mipgemm_conv_workspace_size bytes; rows padded with zeros to whole k blocks,
+ * the filters re-pitched the same way behind it) and multiplies the two.  Pointers are device pointers owned by the caller;
  * same execution and error conventions as the GEMM entry points.  Argument
  * numbers: b=1 hi=2 wi=3 ci=4 co=5 hf=6 wf=7 stride=8 pad=9 F=10 I=11 O=12 mode=13
  * workspace=14 workspace_bytes=15 stream=16.  Sizes must be positive (b and c_o may

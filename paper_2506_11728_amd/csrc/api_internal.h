@@ -20,6 +20,9 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
                            int orderB, void *C, int64_t ldc, int orderC, int mode,
                            void *workspace, size_t workspace_bytes, Problem *out);
 
+// Enqueues the kernels of a plan.
+hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s);
+
 // Validates, plans and launches one GEMM call.  out_float: C holds floats and receives
 // float(sum) * scale (the f32 entry points).
 int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,

@@ -29,12 +29,13 @@ union Piece {  // 16 bytes of a row of M
 
 // WIDE_LOAD: c_i % 16 == 0 and the image is 16-byte aligned.  WIDE_STORE: ldm % 16 == 0
 // and M is 16-byte aligned.
+// kfill >= k: bytes k .. kfill - 1 of every row are written as zeros (kfill == k: none).
 template <bool WIDE_LOAD, bool WIDE_STORE>
-__global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, int k,
+__global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, int k, int kfill,
                                                      const uint8_t *I, uint8_t *M, int64_t ldm) {
   // threads_per_row threads share a row; a workgroup takes 256 / threads_per_row rows at a
   // time, ROWS_IN_FLIGHT times over, each thread keeping its position inside the row
-  const int pieces_per_row = (k + 15) / 16;
+  const int pieces_per_row = (kfill + 15) / 16;
   const int threads_per_row = pieces_per_row < 256 ? pieces_per_row : 256;
   const int rows_per_pass = 256 / threads_per_row;
   const int r_local = threadIdx.x / threads_per_row;
@@ -60,7 +61,8 @@ __global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, i
     }
     for (int u = u_first; u < pieces_per_row; u += threads_per_row) {
       const int kk = u * 16;
-      const int valid = k - kk < 16 ? k - kk : 16;  // bytes of this piece that belong to the row
+      const int valid = k - kk < 16 ? k - kk : 16;  // bytes of this piece that belong to the row (may be <= 0)
+      const int written = kfill - kk < 16 ? kfill - kk : 16;  // bytes of it that are stored
       const int tap = kk / G.ci, c = kk - tap * G.ci;
       const int y = tap / G.wf, x = tap - y * G.wf;
       Piece piece[ROWS_IN_FLIGHT];
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, i
         const uint8_t *base = I + image[j];
         if (WIDE_LOAD) {
           const int iy = iy0[j] + y, ix = ix0[j] + x;
-          const bool inside = (unsigned)iy < (unsigned)G.hi && (unsigned)ix < (unsigned)G.wi;
+          const bool inside = valid > 0 && (unsigned)iy < (unsigned)G.hi && (unsigned)ix < (unsigned)G.wi;
           piece[j].v = v4i_copy{0, 0, 0, 0};
           if (inside)
             piece[j].v = *reinterpret_cast<const v4i_copy *>(base + ((int64_t)iy * G.wi + ix) * G.ci + c);
@@ -96,12 +98,12 @@ __global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, i
         const int64_t row = row0 + (int64_t)j * rows_per_pass;
         if (row < rows) {
           uint8_t *out = M + row * ldm + kk;
-          if (WIDE_STORE && valid == 16) {
+          if (WIDE_STORE && written == 16) {
             *reinterpret_cast<v4i_copy *>(out) = piece[j].v;
           } else {
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-              if (e < valid) out[e] = piece[j].b[e];
+              if (e < written) out[e] = piece[j].b[e];
           }
         }
       }
@@ -112,19 +114,20 @@ __global__ __launch_bounds__(256) void im2col_kernel(ConvGeom G, int64_t rows, i
 }  // namespace
 
 hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8_t *I, uint8_t *M,
-                         int64_t ldm, hipStream_t s) {
+                         int64_t ldm, hipStream_t s, int64_t kfill) {
+  if (kfill < k) kfill = k;
   if (rows == 0 || k == 0) return hipSuccess;
   const bool wide_load = g.ci % 16 == 0 && reinterpret_cast<uintptr_t>(I) % 16 == 0;
   const bool wide_store = ldm % 16 == 0 && reinterpret_cast<uintptr_t>(M) % 16 == 0;
-  const int64_t pieces = (k + 15) / 16;
+  const int64_t pieces = (kfill + 15) / 16;
   const int threads_per_row = pieces < 256 ? (int)pieces : 256;
   const int64_t rows_per_block = (int64_t)(256 / threads_per_row) * ROWS_IN_FLIGHT;
   int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
   if (blocks > 256 * 64) blocks = 256 * 64;  // the row loop strides over the rest
-  void (*kern)(ConvGeom, int64_t, int, const uint8_t *, uint8_t *, int64_t) =
+  void (*kern)(ConvGeom, int64_t, int, int, const uint8_t *, uint8_t *, int64_t) =
       wide_load ? (wide_store ? im2col_kernel<true, true> : im2col_kernel<true, false>)
                 : (wide_store ? im2col_kernel<false, true> : im2col_kernel<false, false>);
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, g, rows, (int)k, I, M, ldm);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, s, g, rows, (int)k, (int)kfill, I, M, ldm);
   return hipGetLastError();
 }
 

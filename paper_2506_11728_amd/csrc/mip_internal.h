@@ -96,7 +96,7 @@ MIP_DECLARE_DMA(128, 64)
 // The lowered matrix of a convolution written out: row n = (g, oy, ox) of M (pitch ldm
 // bytes) holds the k = hf * wf * ci bytes that ConvGeom describes.
 hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8_t *I, uint8_t *M,
-                         int64_t ldm, hipStream_t s);
+                         int64_t ldm, hipStream_t s, int64_t kfill = 0);  // bytes k .. kfill - 1 zeroed
 
 // The k x n matrix B (b_kc: already k-contiguous, pitch ldb; else row-major, pitch ldb)
 // rewritten k-contiguous with pitch ldp; entries k .. kfill - 1 of every column are written

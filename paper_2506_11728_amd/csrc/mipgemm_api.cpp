@@ -132,16 +132,20 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
     p.rows_padded_to_256 = true;
     plan = mip::choose_plan(p);
   }
+  return static_cast<int>(launch_plan(p, plan, s));
+}
+
+hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s) {
   switch (plan.kind) {
-    case mip::KIND_NONE: break;
-    case mip::KIND_FILL: e = mip::launch_fill_zero(p, s); break;
-    case mip::KIND_SIMPLE: e = mip::launch_simple(p, s); break;
-    case mip::KIND_STAGED: e = mip::launch_staged(p, plan.shape, plan.splits, s); break;
-    case mip::KIND_DMA: e = mip::launch_dma(p, plan.shape, plan.splits, s); break;
-    case mip::KIND_DMA_K128: e = mip::launch_dma_k128(p, s); break;
-    case mip::KIND_SLAB: e = mip::launch_slab(p, plan.splits, s); break;
+    case KIND_NONE: return hipSuccess;
+    case KIND_FILL: return launch_fill_zero(p, s);
+    case KIND_SIMPLE: return launch_simple(p, s);
+    case KIND_STAGED: return launch_staged(p, plan.shape, plan.splits, s);
+    case KIND_DMA: return launch_dma(p, plan.shape, plan.splits, s);
+    case KIND_DMA_K128: return launch_dma_k128(p, s);
+    case KIND_SLAB: return launch_slab(p, plan.splits, s);
   }
-  return static_cast<int>(e);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace mip

@@ -17,8 +17,16 @@ struct ConvCall {
   mip::ConvGeom geom;
   int64_t rows;  // b * h_o * w_o: the GEMM's n
   int64_t k;     // h_f * w_f * c_i
-  int64_t ldm;   // row pitch of a written-out augmented matrix
+  int64_t kp;    // row pitch of a written-out augmented matrix: k padded (with zeros) to whole k blocks
 };
+
+int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
+
+// The written-out route's workspace: the augmented matrix, rows in whole tiles of 256 (only
+// the real ones are written) with pitch kp, then the filters re-pitched to kp the same way.
+size_t written_out_bytes(const ConvCall &c, int64_t co) {
+  return static_cast<size_t>((round_up(c.rows, 256) + round_up(co, 256)) * c.kp);
+}
 
 // 0 and `out`, or the negative number of the first bad size argument; has_co is false for
 // the entry point that has no c_o (then hf .. pad are arguments 5 .. 8 instead of 6 .. 9)
@@ -46,7 +54,7 @@ int conv_sizes(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, bool h
   out->geom = mip::ConvGeom{(int)hi, (int)wi, (int)ci, (int)wf, (int)ho, (int)wo, (int)stride, (int)pad};
   out->rows = b * ho * wo;
   out->k = hf * wf * ci;
-  out->ldm = (out->k + 15) / 16 * 16;
+  out->kp = out->k >= 1024 ? round_up(out->k, 128) : round_up(out->k, 64);
   return 0;
 }
 
@@ -56,8 +64,15 @@ Problem conv_problem(const ConvCall &c, int64_t co, const void *F, const void *I
                      bool implicit, const void *M, int out_float = 0, float scale = 1.0f) {
   Problem p;
   p.m = c.rows; p.n = co; p.k = c.k;
-  p.A = implicit ? I : M; p.a_sm = implicit ? c.k : c.ldm; p.a_sk = 1; p.a_unsigned = 1;
-  p.B = F; p.b_sk = 1; p.b_sn = c.k; p.b_unsigned = 0;
+  // written out: M holds the matrix and, behind its round_up(rows, 256) rows, the filters,
+  // both with pitch kp and zeros from k on
+  p.A = implicit ? I : M; p.a_sm = implicit ? c.k : c.kp; p.a_sk = 1; p.a_unsigned = 1;
+  p.B = implicit ? F : static_cast<const uint8_t *>(M) + round_up(c.rows, 256) * c.kp;
+  p.b_sk = 1; p.b_sn = implicit ? c.k : c.kp; p.b_unsigned = 0;
+  if (!implicit) {
+    p.k = c.kp;
+    p.rows_padded_to_256 = true;
+  }
   p.C = static_cast<int32_t *>(O); p.ldc = co;
   p.accumulate = mode == MIPGEMM_ACCUMULATE;
   p.out_float = out_float; p.scale = scale;
@@ -99,7 +114,7 @@ size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci
   if (conv_route(c, conv_problem(c, co, fake, fake, const_cast<void *>(fake), MIPGEMM_OVERWRITE,
                                  true, nullptr), &plan) != ROUTE_IM2COL)
     return 0;
-  return static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
+  return written_out_bytes(c, co);
 }
 
 const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
@@ -166,15 +181,25 @@ static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t w
   p.conv = &c.geom;
   if (route == ROUTE_TILES) return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
   if (route == ROUTE_ROWS) return static_cast<int>(mip::launch_conv_rows(p, s));
-  const size_t need = static_cast<size_t>(c.rows) * static_cast<size_t>(c.ldm);
+  const size_t need = written_out_bytes(c, co);
   if (!workspace) return -14;
   if (workspace_bytes < need) return -15;
-  hipError_t e = mip::launch_im2col(c.geom, c.rows, c.k, I, static_cast<uint8_t *>(workspace), c.ldm, s);
+  // the matrix and the filters, both with pitch kp and the k tail zeroed, so that the
+  // direct-to-LDS kernels can stream them whatever k and the alignment of F are
+  uint8_t *Mp = static_cast<uint8_t *>(workspace);
+  uint8_t *Fp = Mp + round_up(c.rows, 256) * c.kp;
+  hipError_t e = mip::launch_im2col(c.geom, c.rows, c.k, I, Mp, c.kp, s, c.kp);
   if (e != hipSuccess) return static_cast<int>(e);
-  // F is A (c_o x k, row-major), the matrix just written is B (k x n, column-major),
-  // O is C (column-major, ldc = c_o)
-  return mip::run_gemm(0, 1, out_float, scale, co, c.rows, c.k, F, c.k, MIPGEMM_ROW_MAJOR, workspace, c.ldm,
-             MIPGEMM_COL_MAJOR, O, co, MIPGEMM_COL_MAJOR, mode, nullptr, 0, stream);
+  p = conv_problem(c, co, F, I, O, mode, false, Mp, out_float, scale);
+  if (c.kp == c.k && reinterpret_cast<uintptr_t>(F) % 16 == 0) {
+    p.B = F;  // the filters can be streamed where they are
+    p.b_sn = c.k;
+    p.rows_padded_to_256 = false;
+  } else {
+    e = mip::launch_pack_b(c.k, co, reinterpret_cast<const uint8_t *>(F), c.k, true, Fp, c.kp, s, c.kp);
+    if (e != hipSuccess) return static_cast<int>(e);
+  }
+  return static_cast<int>(mip::launch_plan(p, mip::choose_plan(p), s));
 }
 
 int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,

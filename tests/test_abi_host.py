@@ -209,9 +209,9 @@ def test_conv_path_choice_and_workspace(M):
     assert name(2, 64, 48, 3, 64, 7, 7, 2, 3) == "implicit:rows"
     assert ws(2, 64, 48, 3, 64, 7, 7, 2, 3) == 0
     # 96 channels: not a multiple of 64, k too long for the row-segment kernel: the augmented
-    # matrix is written out, n rows of k bytes rounded up to 16
+    # matrix is written out, k padded to whole k blocks, and the filters re-pitched behind it
     assert name(2, 8, 8, 96, 16, 3, 3, 1, 1).startswith("im2col+")
-    assert ws(2, 8, 8, 96, 16, 3, 3, 1, 1) == 2 * 8 * 8 * 864
+    assert ws(2, 8, 8, 96, 16, 3, 3, 1, 1) == (256 + 256) * 896   # rows and filters in tiles of 256, k 864 -> 896
     assert name(0, 8, 8, 64, 16, 3, 3, 1, 1) == "none"
     assert name(2, 8, 8, 64, 16, 13, 3, 1, 1) == "invalid"
     assert ws(2, 8, 8, 64, 16, 13, 3, 1, 1) == 0

@@ -211,7 +211,7 @@ def test_conv_errors_and_empty(gpu):
 def _conv_errors_and_empty(gpu, shape):
     import torch
     need = gpu.mipgemm_conv_workspace_size(*shape)
-    assert need == 64 * 32                                   # 64 positions, 27 bytes rounded up to 32
+    assert need == (256 + 256) * 64                          # positions and filters in tiles of 256, k 27 -> 64
     dI = torch.zeros(8 * 8 * 3, dtype=torch.uint8, device="cuda")
     dF = torch.zeros(4 * 27, dtype=torch.uint8, device="cuda")
     dO = torch.full((64 * 4,), 9, dtype=torch.int32, device="cuda")
@@ -363,3 +363,26 @@ def test_convolution_replays_from_a_hip_graph(gpu, oracle, shape):
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(dO.cpu().numpy(), want), "replay %d" % replay
+
+
+# neither gathering kernel serves these (channels not a multiple of 64, k too long for the
+# row-segment kernel): the written-out route, whose matrix and filters are padded to whole
+# k blocks so that the direct-to-LDS kernels multiply them
+WRITTEN_OUT_SHAPES = [(2, 14, 14, 96, 40, 3, 3, 1, 1), (1, 10, 10, 160, 70, 3, 3, 2, 1),
+                      (2, 9, 9, 48, 33, 5, 5, 1, 2), (1, 30, 30, 96, 300, 3, 3, 1, 0)]
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", WRITTEN_OUT_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_on_the_written_out_route_by_default(gpu, oracle, shape, mode):
+    print("conv written out", shape, mode, flush=True)
+    name = gpu.mipgemm_conv_variant_name(*shape)
+    assert name.startswith("im2col+mfma_dma") or name.startswith("im2col+mfma_slab"), name
+    I, F = tensors(shape, 12)
+    ho = oracle.conv_out_extent(shape[1], shape[5], shape[7], shape[8])
+    wo = oracle.conv_out_extent(shape[2], shape[6], shape[7], shape[8])
+    rng = np.random.default_rng(13)
+    O0 = rng.integers(-1000, 1000, size=(shape[0], ho, wo, shape[4]), dtype=np.int32)
+    want = oracle.conv_direct(I, F, shape[7], shape[8], O=O0.copy() if mode else None, mode=mode)
+    got = run_conv(gpu, shape, I, F, O0, mode)
+    assert np.array_equal(got, want)
