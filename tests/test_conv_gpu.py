@@ -386,3 +386,33 @@ def test_conv_on_the_written_out_route_by_default(gpu, oracle, shape, mode):
     want = oracle.conv_direct(I, F, shape[7], shape[8], O=O0.copy() if mode else None, mode=mode)
     got = run_conv(gpu, shape, I, F, O0, mode)
     assert np.array_equal(got, want)
+
+
+def test_seeded_sweep_of_random_convolutions(gpu, oracle):
+    """60 random geometries (1-48 channels, filters up to 7 x 7, strides 1-3, paddings 0-4, up to
+    139 filters, both modes), each on the route the library picks and on the row-segment kernel
+    where that can serve."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 60:
+        ci = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 24, 32, 48]))
+        hf, wf = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        s, p = int(rng.integers(1, 4)), int(rng.integers(0, 5))
+        hi, wi = int(rng.integers(1, 40)), int(rng.integers(1, 300))
+        if hi + 2 * p < hf or wi + 2 * p < wf:
+            continue
+        b, co = int(rng.integers(1, 4)), int(rng.integers(1, 140))
+        shape = (b, hi, wi, ci, co, hf, wf, s, p)
+        mode = int(rng.integers(0, 2))
+        I = rng.integers(0, 256, size=(b, hi, wi, ci), dtype=np.uint8)
+        F = rng.integers(-128, 128, size=(co, hf, wf, ci), dtype=np.int8)
+        ho, wo = (hi + 2 * p - hf) // s + 1, (wi + 2 * p - wf) // s + 1
+        O0 = rng.integers(-1000, 1000, size=(b, ho, wo, co), dtype=np.int32)
+        want = oracle.conv_direct(I, F, s, p, O=O0.copy() if mode else None, mode=mode)
+        for route in (None, "rows"):
+            with Env(MIPGEMM_CONV=route):
+                name = gpu.mipgemm_conv_variant_name(*shape)
+            print("conv sweep", shape, mode, route, name, flush=True)
+            got = run_conv(gpu, shape, I, F, O0, mode, MIPGEMM_CONV=route)
+            assert np.array_equal(got, want), (shape, mode, route, name)
+        done += 1

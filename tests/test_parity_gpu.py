@@ -655,3 +655,35 @@ def test_packed_route_forced_on_small_and_skinny_shapes(gpu, oracle, spec):
     assert np.array_equal(dC.cpu().numpy(), want)
     assert (ws[need:].cpu().numpy() == 0x5A).all()
     assert not (ws[:need].cpu().numpy() == 0x5A).all()           # the packed operands were written
+
+
+def test_seeded_sweep_of_the_packed_route(gpu, oracle):
+    """40 random small problems (any order, padded leading dimensions, either operand unsigned,
+    both modes) forced through the packed route."""
+    import torch
+    rng = np.random.default_rng(2025)
+    os.environ["MIPGEMM_PACK"] = "always"
+    try:
+        for it in range(40):
+            m, n, k = int(rng.integers(1, 700)), int(rng.integers(1, 700)), int(rng.integers(1, 1500))
+            oa, ob, oc = (int(x) for x in rng.integers(0, 2, size=3))
+            au = bool(rng.integers(0, 2))
+            bu = (not au) and bool(rng.integers(0, 2))
+            pad, mode = int(rng.choice([0, 1, 3, 16, 17])), int(rng.integers(0, 2))
+            case = W.Case("packsweep_%d" % it, 8, it, m, n, k, a_unsigned=au, b_unsigned=bu, orderA=oa,
+                          orderB=ob, orderC=oc, pad=pad, mode=mode, c_dist=("uniform", -1000, 1000),
+                          seed=64)
+            print("packed sweep", (m, n, k, oa, ob, oc, pad, au, bu, mode), flush=True)
+            ops = W.materialize(case)
+            want = oracle_result(oracle, case, ops)
+            need = _packed_bytes(m, n, k)
+            ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+            dC = torch.from_numpy(ops.C).cuda()
+            getattr(gpu, "mipgemm_" + case.entry)(
+                m, n, k, torch.from_numpy(ops.A.view(np.uint8)).cuda(), case.lda, oa,
+                torch.from_numpy(ops.B.view(np.uint8)).cuda(), case.ldb, ob, dC, case.ldc, oc, mode,
+                workspace=ws, workspace_bytes=need)
+            torch.cuda.synchronize()
+            assert np.array_equal(dC.cpu().numpy(), want), (m, n, k, oa, ob, oc, pad, au, bu, mode)
+    finally:
+        del os.environ["MIPGEMM_PACK"]
