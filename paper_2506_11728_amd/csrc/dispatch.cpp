@@ -154,8 +154,25 @@ Plan choose_plan(const Problem &p) {
     // The same kernel serves short k, where the tiled kernels cannot split k
     // and 64-column tiles leave most compute units idle.
     const bool slab_ok = p.m <= 64 && slab_eligible(p, 1);
-    if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192) plan = {KIND_SLAB, SHAPE_64, 1};
-    else if (slab_ok && p.k < 1024 && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
+    // Slabs of 32 columns re-read A half as often and need half the workgroups; they win
+    // (warm and cold) wherever they fill the compute units' rounds as evenly as slabs of 16 do:
+    // n = 8192 (256 slabs of 32: one round) and 16384, not 11008 (344: two rounds, the second
+    // a third full) nor 4096 (128: half a round).  Measured, us warm/cold, m = 1, k = 4096:
+    // n = 16384 15.7/19.7 -> 12.5/18.0; m = 16: 18.5/21.9 -> 14.7/19.6.
+    auto round_fill = [&](int64_t slabs) {
+      return (double)slabs / (double)((slabs + kComputeUnits - 1) / kComputeUnits * kComputeUnits);
+    };
+    const bool wide_slabs = slab_eligible(p, 2) && round_fill(p.n / 32) >= round_fill(p.n / 16) - 0.02;
+    // "short k": the slab kernel still wins where the tiles, too few to fill the chip, would
+    // have to split k (a zero-fill launch plus atomics): up to k = 4096 at m <= 16, 2048 at 32,
+    // 1024 at 64; with a row-major B (16-byte pieces of every line per slab) only up to 2048,
+    // cold it loses beyond ((1, 4096, 3072): 11.6 against 8.5 us).  Measured, us warm/cold:
+    // (1, 1024, 2048) 4.9/5.6 -> 3.6/4.5, (16, 2048, 2048) 5.3/6.1 -> 4.5/5.5,
+    // (64, 4096, 1024) 6.3/7.2 -> 5.1/5.7.
+    const bool short_k = p.k * (p.m > 16 ? p.m : 16) <= 65536 && (p.b_sk == 1 || p.k <= 2048);
+    if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192)
+      plan = {KIND_SLAB, SHAPE_64, wide_slabs ? 2 : 1};
+    else if (slab_ok && short_k && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
