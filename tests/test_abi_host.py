@@ -120,12 +120,12 @@ def test_variant_choice(M):
     assert name(4352, 4352, 4096, 4096, 0, 4352, 0, 4352, 0) == "mfma_dma128"        # 289 tiles of 256 x 256: a second round for 33
     assert name(4608, 4608, 4096, 4096, 0, 4608, 0, 4608, 0) == "mfma_dma256_k128"
     # unaligned operands cannot use the direct-to-LDS kernels
-    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128"
+    assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128x64"
     # a ragged row edge can, but not with the deep-k kernel; an unsigned operand can
     assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256"
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256_k128"
     # a row-major B with n not a multiple of 16 cannot
-    assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile128"
+    assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile128x64"
     # short in one dimension: a tile that is short there too
     assert name(16, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma64"
     assert name(64, 100352, 576, 576, 0, 100352, 0, 100352, 0) == "mfma_dma64x256"
@@ -143,7 +143,7 @@ def test_variant_choice(M):
     # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
     assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma64x128"
     # k not a multiple of 64 does not
-    assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128"
+    assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128x64"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"
     assert name(0, 4, 4, 4, 0, 4, 0, 4, 0) == "none"
     assert name(4, 4, 4, 1, 0, 4, 0, 4, 0) == "invalid"
