@@ -182,7 +182,9 @@ Plan choose_plan(const Problem &p) {
     // bounds it, and the narrower tile keeps more of them in flight per compute unit;
     // measured on 12 unaligned shapes from 1001 x 4099 x 513 to 4097 x 4099 x 2049: 9-25 % over
     // 128 x 128 on every one)
-    else plan = {KIND_STAGED, sh == SHAPE_256 || sh == SHAPE_128 ? SHAPE_128X64 : sh, 1};
+    // The wide side goes across the operand that is dearer to fetch again, a column-major A:
+    // 8191 x 8193 x 8195 with such an A 4570 us on 128 x 64 tiles, 2570 on 64 x 128.
+    else plan = {KIND_STAGED, sh == SHAPE_256 || sh == SHAPE_128 ? (p.a_sk == 1 ? SHAPE_128X64 : SHAPE_64X128) : sh, 1};
   }
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
     plan.splits = p.out_float ? 1 : forced_splits();  // float sums are not combined out of order
