@@ -172,7 +172,12 @@ Plan choose_plan(const Problem &p) {
     const bool short_k = p.k * (p.m > 16 ? p.m : 16) <= 65536 && (p.b_sk == 1 || p.k <= 2048);
     if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192)
       plan = {KIND_SLAB, SHAPE_64, wide_slabs ? 2 : 1};
-    else if (slab_ok && short_k && tile_count(p, SHAPE_64) < kComputeUnits / 2 && p.n / 16 >= 64)
+    // (Float output cannot split k at all, sums of floats not being combined out of order:
+    // there the slab kernel takes every such problem, whatever k.  Measured, us warm/cold:
+    // (16, 2048, 8192) 17.8/29.2 -> 9.7/11.2, with a row-major B 17.7/35.3 -> 10.5/26.6;
+    // (1, 4096, 4096) row-major B 10.5/18.5 -> 7.2/14.5.)
+    else if (slab_ok && (short_k || p.out_float) && tile_count(p, SHAPE_64) < kComputeUnits / 2 &&
+             p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
