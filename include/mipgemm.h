@@ -325,8 +325,10 @@ const char *mipgemm_strerror(int code);
 /*
  * Name of the kernel variant the dispatcher picks for these sizes, orders,
  * leading dimensions and pointer alignments (all pointers taken as 16-byte
- * aligned when `aligned16` is non-zero), for a call without workspace.  Host-only, launches nothing; meant
- * for tests, benchmarks and profiles.  Returns a static string.
+ * aligned when `aligned16` is non-zero), for an overwriting call without workspace
+ * (an accumulating call into an int32 C may take tiles with split k where this
+ * names the skinny-m kernel).  Host-only, launches nothing; meant for tests,
+ * benchmarks and profiles.  Returns a static string.
  */
 const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k,
                                  int64_t lda, int orderA,

@@ -153,7 +153,14 @@ Plan choose_plan(const Problem &p) {
     // which the tiled kernels, with their 64-byte pieces and split k, do better.)
     // The same kernel serves short k, where the tiled kernels cannot split k
     // and 64-column tiles leave most compute units idle.
-    const bool slab_ok = p.m <= 64 && slab_eligible(p, 1);
+    // (Adding into an int32 C that already holds values needs no zero-fill launch: with a k
+    // long enough to split, the tiles then win or tie.  Measured, us warm/cold, slab against
+    // tiles: (16, 4096, 4096) 6.4/9.5 against 4.7/7.0, (1, 1024, 2048) 3.7/4.7 against
+    // 3.3/4.0, (64, 4096, 1024) 5.4/6.5 against 4.5/5.2, (16, 16384, 4096) 16.1/21.9 against
+    // 15.0/18.2, (1, 11008, 4096) 10.4/12.5 against 10.5/12.2.  At k = 1024 only from 16
+    // rows on: (1, 4096, 1024) 2.9/3.5 against 3.4/4.1, (16, 8192, 1024) 4.2/5.7 against 3.9/4.7.)
+    const bool adds_in_place = p.accumulate && !p.out_float && p.k >= (p.m >= 16 ? 1024 : 2048);
+    const bool slab_ok = p.m <= 64 && !adds_in_place && slab_eligible(p, 1);
     // Slabs of 32 columns re-read A half as often and need half the workgroups; they win
     // (warm and cold) wherever they fill the compute units' rounds as evenly as slabs of 16 do:
     // n = 8192 (256 slabs of 32: one round) and 16384, not 11008 (344: two rounds, the second
