@@ -217,7 +217,9 @@ Plan choose_plan(const Problem &p) {
       // and one workgroup too many would cost a second round)
       const bool small_tile = plan.shape == SHAPE_64;
       const int64_t target = short_side <= 16 && small_tile ? 2 * kComputeUnits : kComputeUnits;
-      if (tiles < target / 2 && !p.out_float) {
+      // (an accumulating call needs no zero-fill launch and gains from two ranges already
+      // at half a round of tiles: (128, 4096, 4096) 11.2 -> 8.8 us, overwriting 11.0 either way)
+      if ((p.accumulate ? tiles <= target / 2 : tiles < target / 2) && !p.out_float) {
         const int64_t want = short_side <= 16 && small_tile ? (target + tiles - 1) / tiles : target / tiles;
         // the register-staged kernel has a shallow pipeline with little to amortise:
         // ranges of two k blocks already pay, and it tolerates twice the atomics
@@ -227,6 +229,10 @@ Plan choose_plan(const Problem &p) {
         const int64_t atomics_ok = (short_side <= 16 ? 64 : (short_side <= 64 ? 8 : 4)) * (staged ? 2 : 1);
         int64_t sp = want < most ? want : most;
         if (sp > atomics_ok) sp = atomics_ok;
+        // the zero-fill launch of an overwriting call costs more than the ranges of a short k
+        // save: (512, 512, 1024) 5.1 us whole, 6.4 us in two ranges (accumulating 5.0 and 4.5);
+        // (512, 512, 2048) 6.7 and 7.3, (256, 256, 2048) 6.5 and 6.0, (512, 512, 4096) 10.6 and 8.7
+        if (!p.accumulate && short_side > 64 && p.k < (tiles <= 32 ? 2048 : 3072)) sp = 1;
         plan.splits = (int)sp;
       }
     }

@@ -77,18 +77,25 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
     int32_t *crow = C + row * ldc + 4 * (lane >> 5);
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
+      // an accumulating call has the old words of all four pieces of the block in flight
+      // before the first store (a load behind every store would wait for it in turn)
+      v4i old[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+      bool whole[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int col = j * 32 + 8 * q;  // plus 4 * (lane / 32), already in crow
+        whole[q] = FULL || col + 4 * (lane >> 5) + 3 < cols;
+        if (accumulate && whole[q]) old[q] = reinterpret_cast<const c_quad *>(crow + col)->v;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = j * 32 + 8 * q;
         v4i val = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                    acc[i][j][4 * q + 3]};
-        if (FULL || col + 4 * (lane >> 5) + 3 < cols) {
-          c_quad *dst = reinterpret_cast<c_quad *>(crow + col);
-          v4i old = {0, 0, 0, 0};
-          if (accumulate) old = dst->v;
+        if (whole[q]) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[e], accumulate);
-          dst->v = val;
+          for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[q][e], accumulate);
+          reinterpret_cast<c_quad *>(crow + col)->v = val;
         } else {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -114,34 +121,53 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
 constexpr int STORE_PATCH_WORDS = 32 * 36;
 constexpr int STORE_PATCH_BYTES = STORE_PATCH_WORDS * 4;
 
+// An accumulating call reads the old words of C one 32 x 32 block ahead of the block
+// it is writing, so that their latency hides behind the turn through LDS and the
+// stores of the block before (loaded only when needed, a store per load in turn, the
+// 2048^3 case took 25.1 us against 15.5 us for an overwriting call).
 template <int FM, int FN>
 __device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], int32_t *C,
                                                      int64_t ldc, bool accumulate, int lane,
                                                      int32_t *patch, const Finish fin) {
+  // the piece of a 32 x 32 block this lane handles in pass t: 4 words of row t * 8 + lane / 8
+  const int r0 = lane >> 3, c0 = (lane & 7) * 4;
+  auto piece = [&](int block, int t) {
+    const int i = block / FN, j = block % FN;
+    return reinterpret_cast<v4i_dword_aligned *>(C + (int64_t)(i * 32 + t * 8 + r0) * ldc + j * 32 + c0);
+  };
+  v4i old[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+  if (accumulate) {
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+    for (int t = 0; t < 4; ++t) old[t] = __builtin_nontemporal_load(piece(0, t));
+  }
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
+  for (int block = 0; block < FM * FN; ++block) {
+    const int i = block / FN, j = block % FN;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        v4i val = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                   acc[i][j][4 * q + 3]};
-        *reinterpret_cast<v4i *>(patch + (lane & 31) * 36 + 8 * q + 4 * (lane >> 5)) = val;
-      }
-      // same wave wrote and reads: LDS operations of a wave complete in order
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int r = t * 8 + (lane >> 3), c = (lane & 7) * 4;
-        v4i val = *reinterpret_cast<const v4i *>(patch + r * 36 + c);
-        v4i_dword_aligned *dst =
-            reinterpret_cast<v4i_dword_aligned *>(C + (int64_t)(i * 32 + r) * ldc + j * 32 + c);
-        v4i old = {0, 0, 0, 0};
-        if (accumulate) old = __builtin_nontemporal_load(dst);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[e], accumulate);
-        __builtin_nontemporal_store(val, dst);
-      }
+    for (int q = 0; q < 4; ++q) {
+      v4i val = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                 acc[i][j][4 * q + 3]};
+      *reinterpret_cast<v4i *>(patch + (lane & 31) * 36 + 8 * q + 4 * (lane >> 5)) = val;
     }
+    // same wave wrote and reads: LDS operations of a wave complete in order
+    v4i val[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      val[t] = *reinterpret_cast<const v4i *>(patch + (t * 8 + r0) * 36 + c0);
+    v4i next[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    if (accumulate && block + 1 < FM * FN) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) next[t] = __builtin_nontemporal_load(piece(block + 1, t));
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) val[t][e] = fin(val[t][e], old[t][e], accumulate);
+      __builtin_nontemporal_store(val[t], piece(block, t));
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) old[t] = next[t];
+  }
 }
 
 // Split-k write-back: every workgroup adds its partial sums into C with integer
