@@ -68,8 +68,21 @@ struct __attribute__((packed, aligned(1))) unaligned_word { uint32_t w; };
 __device__ __forceinline__ void store_rows_via_lds(const v16i (&acc)[1][2], int32_t *C, int ldc,
                                                    int rows, bool accumulate, int lane,
                                                    int32_t *patch, const Finish fin) {
+  // the piece of block j this lane handles in pass t: 4 words of row t * 8 + lane / 8
+  // (a 32 x 64 patch of O spans fewer than 2^31 words: a uniform base and a 32-bit offset)
+  const int r0 = lane >> 3, c0 = (lane & 7) * 4;
+  auto piece = [&](int j, int t) {
+    return reinterpret_cast<v4i_dword_aligned *>(C + (uint32_t)((t * 8 + r0) * ldc + j * 32 + c0));
+  };
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
+    // an accumulating call has the old words of the block in flight before its first store
+    v4i old[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      old[t] = v4i{0, 0, 0, 0};
+      if (accumulate && t * 8 + r0 < rows) old[t] = __builtin_nontemporal_load(piece(j, t));
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       v4i val = {acc[0][j][4 * q], acc[0][j][4 * q + 1], acc[0][j][4 * q + 2], acc[0][j][4 * q + 3]};
@@ -78,16 +91,11 @@ __device__ __forceinline__ void store_rows_via_lds(const v16i (&acc)[1][2], int3
     // same wave wrote and reads: LDS operations of a wave complete in order
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const int r = t * 8 + (lane >> 3), c = (lane & 7) * 4;
-      v4i val = *reinterpret_cast<const v4i *>(patch + r * 36 + c);
-      if (r < rows) {
-        // (a 32 x 64 patch of O spans fewer than 2^31 words: a uniform base and a 32-bit offset)
-        v4i_dword_aligned *dst = reinterpret_cast<v4i_dword_aligned *>(C + (uint32_t)(r * ldc + j * 32 + c));
-        v4i old = {0, 0, 0, 0};
-        if (accumulate) old = __builtin_nontemporal_load(dst);
+      v4i val = *reinterpret_cast<const v4i *>(patch + (t * 8 + r0) * 36 + c0);
+      if (t * 8 + r0 < rows) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[e], accumulate);
-        __builtin_nontemporal_store(val, dst);
+        for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[t][e], accumulate);
+        __builtin_nontemporal_store(val, piece(j, t));
       }
     }
   }
