@@ -233,14 +233,17 @@ __global__ __launch_bounds__(NTHREADS) void slab_kernel(SlabParams P) {
 #pragma unroll
     for (int w = 1; w < 4; ++w) s += red[((w * MT + mt) * NT + nt) * 64 + lane];
     int32_t *c = P.C + n0 + 16 * nt + (lane & 15);
+    // (an accumulating call reads its four old words before the first store, not one behind each)
+    int old[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int row = 16 * mt + 4 * (lane >> 4) + v;
-      if (row < P.m) {
-        int32_t *dst = c + row * P.ldc;
-        const int old = P.accumulate ? *dst : 0;
-        *dst = fin(s[v], old, P.accumulate != 0);
-      }
+      if (P.accumulate && row < P.m) old[v] = c[row * P.ldc];
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = 16 * mt + 4 * (lane >> 4) + v;
+      if (row < P.m) c[row * P.ldc] = fin(s[v], old[v], P.accumulate != 0);
     }
   }
 }
