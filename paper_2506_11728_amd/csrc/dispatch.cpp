@@ -158,8 +158,10 @@ Plan choose_plan(const Problem &p) {
     // tiles: (16, 4096, 4096) 6.4/9.5 against 4.7/7.0, (1, 1024, 2048) 3.7/4.7 against
     // 3.3/4.0, (64, 4096, 1024) 5.4/6.5 against 4.5/5.2, (16, 16384, 4096) 16.1/21.9 against
     // 15.0/18.2, (1, 11008, 4096) 10.4/12.5 against 10.5/12.2.  At k = 1024 only from 16
-    // rows on: (1, 4096, 1024) 2.9/3.5 against 3.4/4.1, (16, 8192, 1024) 4.2/5.7 against 3.9/4.7.)
-    const bool adds_in_place = p.accumulate && !p.out_float && p.k >= (p.m >= 16 ? 1024 : 2048);
+    // rows on: (1, 4096, 1024) 2.9/3.5 against 3.4/4.1, (16, 8192, 1024) 4.2/5.7 against 3.9/4.7;
+    // with fewer rows from k = 1536: (8, 4096, 1536) 4.0/5.1 against 3.5/4.3,
+    // (4, 16384, 1536) 6.2/8.4 against 4.6/8.2.)
+    const bool adds_in_place = p.accumulate && !p.out_float && p.k >= (p.m >= 16 ? 1024 : 1536);
     const bool slab_ok = p.m <= 64 && !adds_in_place && slab_eligible(p, 1);
     // Slabs of 32 columns re-read A half as often and need half the workgroups; they win
     // (warm and cold) wherever they fill the compute units' rounds as evenly as slabs of 16 do:
