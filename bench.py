@@ -37,7 +37,12 @@ def parse_args():
     ap.add_argument("--case", type=str, default=None, help="name of a workload case to run instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--cpu-sample-rows", type=int, default=8192,
+                    help="rows of C the oracle computes (and the GPU result is compared on); "
+                         "all 8192 take about 22 s on 16 host threads")
+    ap.add_argument("--timeline", type=int, default=0,
+                    help="time that many launches one by one, from a cold start, print them as one "
+                         "JSON line and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy and exit (scales the HBM byte counters)")
     ap.add_argument("--no-ceiling", action="store_true",
@@ -341,11 +346,8 @@ def run_conv_table(M):
             ldm = (k + 15) // 16 * 16
             dM = torch.zeros(n * ldm, dtype=torch.uint8, device="cuda")      # a ready-made matrix
             args = (b, hi, hi, ci, co, hf, hf, stride, pad)
-            os.environ["MIPGEMM_CONV"] = "im2col"
-            try:
+            with M.tuning(MIPGEMM_CONV="im2col"):
                 need = M.mipgemm_conv_workspace_size(*args)                # of the written-out route
-            finally:
-                del os.environ["MIPGEMM_CONV"]
             dW = torch.zeros(need, dtype=torch.uint8, device="cuda")
 
             def gemm_only():
@@ -356,11 +358,8 @@ def run_conv_table(M):
                 M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=dW, workspace_bytes=need)
 
             t_gemm = replay_us(gemm_only)
-            os.environ["MIPGEMM_CONV"] = "im2col"
-            try:
+            with M.tuning(MIPGEMM_CONV="im2col"):
                 t_explicit = replay_us(conv)
-            finally:
-                del os.environ["MIPGEMM_CONV"]
             t_implicit = replay_us(conv)
             moved = image.size + filt.size + 4 * n * co
             print("| %d | %dx%dx%d | %d of %dx%d | (%d, %d, %d) | %.1f | %.1f | %.1f | %s | %.0f |" % (
@@ -591,6 +590,22 @@ def run_conv_layer(M, args):
     }))
 
 
+def run_timeline(step, stream, case, launches):
+    """Every launch between its own pair of events, starting from a device that has done
+    nothing yet: how long the device takes to reach its working clocks."""
+    import torch
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+    torch.cuda.synchronize()
+    events[0].record(stream)
+    for i in range(launches):
+        step()
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    us = [events[i].elapsed_time(events[i + 1]) * 1e3 for i in range(launches)]
+    print(json.dumps({"workload": case.name, "launches": launches,
+                      "us_per_launch": [round(x, 1) for x in us]}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -631,6 +646,24 @@ def main():
         fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
            dC, case.ldc, case.orderC, case.mode, stream=stream)
 
+    if args.timeline:
+        run_timeline(step, stream, case, args.timeline)
+        return
+
+    ceiling = None
+    if not args.no_ceiling:
+        # What the matrix instruction itself sustains on this device with its operands in
+        # registers, and the shader clock it ran at: the chip is power-limited and the rate
+        # depends on the operand bits.  Run before the timed region: the probes (about 0.1 s
+        # of matrix work) also bring the device out of its idle clocks, which the first tens
+        # of milliseconds of any load otherwise run at (profiles/launch_timeline_*.txt).
+        ceiling = {"unit": "TOPS"}
+        for key, pattern in (("near_zero_operands", 0), ("random_operands_rotated_by_valu", 1),
+                             ("random_operands_two_sets", 2), ("random_operands_six_sets", 3)):
+            tops_p, mhz_p = M.mipgemm_mfma_ceiling_clocked(pattern, 20000)
+            ceiling[key] = tops_p
+            ceiling[key + "_shader_mhz"] = mhz_p
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -645,9 +678,9 @@ def main():
     kernel_ms = ev0.elapsed_time(ev1) / args.steps     # one kernel launch per step
     ms_per_step = wall * 1e3 / args.steps
 
-    variant = M.mipgemm_variant_name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
-                                     case.orderB, case.ldc, case.orderC, case.a_unsigned,
-                                     case.b_unsigned, True)
+    variant = M.mipgemm_variant_name_for_mode(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
+                                              case.orderB, case.ldc, case.orderC, case.a_unsigned,
+                                              case.b_unsigned, True, case.mode)
     tops = case.ops / (ms_per_step * 1e-3) / 1e12
     kernel_tops = case.ops / (kernel_ms * 1e-3) / 1e12
     kernel_gbs = case.algorithmic_bytes / (kernel_ms * 1e-3) / 1e9
@@ -663,6 +696,22 @@ def main():
     roofline["kernel_ms"] = kernel_ms
     roofline["traffic"] = recorded_traffic(variant, case)
     roofline["algorithmic_bytes"] = case.algorithmic_bytes
+    if variant == "mfma_dma256_k128" and case.entry == "s8s8s32":
+        # the shader clock during the main loops of the same kernel, right after the timed steps
+        tiles = -(-case.m // 256) * -(-case.n // 256)
+        clocks = torch.zeros(2 * (-(-tiles // 8) * 8), dtype=torch.int64, device="cuda")
+        for _ in range(3):
+            M.mipgemm_s8s8s32_clocked(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb,
+                                      case.orderB, dC, case.ldc, case.orderC, case.mode, clocks,
+                                      clocks.numel() * 8, stream=stream)
+        torch.cuda.synchronize()
+        c = clocks.cpu().numpy().reshape(-1, 2).sum(axis=0)
+        roofline["shader_mhz"] = float(c[0]) / float(c[1]) * 100.0 if c[1] else None
+        # matrix instructions issue back to back at 32 clocks each: the share of the main
+        # loops' clocks that the matrix pipe was busy
+        # (per wave and tile k / 32 steps of 16 instructions of 32 clocks; three launches)
+        roofline["mfma_busy_frac_of_main_loop"] = (
+            3.0 * tiles * case.k * 16 / float(c[0]) if c[0] else None)
 
     out = {
         "metric": "int8 GEMM TOPS (int32 acc) at m=n=k=8192; % of MI355X int8 MFMA peak",
@@ -676,14 +725,10 @@ def main():
         "roofline": roofline,
     }
 
-    if not args.no_ceiling:
-        # what the matrix instruction itself sustains on this device, operands in registers:
-        # the chip is power-limited and the rate depends on the operand bits
-        zero = M.mipgemm_mfma_ceiling(0, 20000)
-        rand = M.mipgemm_mfma_ceiling(1, 20000)
-        out["mfma_only_ceiling"] = {
-            "unit": "TOPS", "near_zero_operands": zero, "random_operands": rand,
-            "kernel_frac_of_random_ceiling": kernel_tops / rand}
+    if ceiling is not None:
+        best_random = max(ceiling["random_operands_two_sets"], ceiling["random_operands_six_sets"])
+        ceiling["kernel_frac_of_random_ceiling"] = kernel_tops / best_random
+        out["mfma_only_ceiling"] = ceiling
 
     check_rows = None
     if not args.no_cpu_baseline:

@@ -35,8 +35,25 @@
  * Execution.  Each call validates its arguments on the host, enqueues its
  * kernels on `stream` and returns without waiting.  Only kernels are enqueued
  * (no memory-set or copy operations), so a call may be recorded into a HIP
- * graph by stream capture and replayed.  The library holds no
- * mutable global state: calls from several threads are safe.
+ * graph by stream capture and replayed.  Calls from several threads are safe:
+ * the only state the library keeps is a table of kernels that have been granted
+ * a large dynamic LDS size (guarded), the device's compute-unit count (read once)
+ * and the tuning values below.
+ *
+ * Tuning values.  Four process-wide overrides exist for tests, tuning runs and
+ * profiles; unset, the dispatcher decides.  They are taken from the environment
+ * variables of the same names ONCE, at the first call into the library, and can
+ * afterwards only be changed with mipgemm_set_tuning():
+ *     MIPGEMM_VARIANT  kernel variant for the GEMM calls: "simple" (one thread per
+ *                      element of C: a cross-check, hundreds of times slower),
+ *                      "dma256k128", "slab16", "slab32", "tile<shape>" or
+ *                      "dma<shape>" with <shape> one of 256, 128, 64, 64x256,
+ *                      256x64, 64x128, 128x64; a variant that cannot serve a
+ *                      problem falls back (the names of mipgemm_variant_name say
+ *                      what ran)
+ *     MIPGEMM_SPLITK   number of k ranges of the tile kernels
+ *     MIPGEMM_PACK     "always" / "never": the packed route whenever / never
+ *     MIPGEMM_CONV     "im2col" / "rows": the convolution route
  *
  * Return value.  0 on success.  A negative value -i means that the i-th
  * argument (counted from 1 in the order of the prototype) is invalid: a
@@ -262,6 +279,15 @@ size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci
                                    int64_t stride, int64_t pad);
 
 /*
+ * The same for a call whose F or I is NOT 16-byte aligned: the tile kernels cannot
+ * gather from such tensors, so layers that need no workspace above may need one
+ * here (a call without it fails with -14 or -15 and touches nothing).
+ */
+size_t mipgemm_conv_workspace_size_unaligned(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                             int64_t co, int64_t hf, int64_t wf,
+                                             int64_t stride, int64_t pad);
+
+/*
  * The augmented matrix alone (IM2COL of Section 7.2): M has one row per output
  * position n = (g, oy, ox) and k = h_f w_f c_i bytes per row, rows `ldm` bytes apart
  * (ldm >= k); bytes of a row beyond k are not written.  As the B operand of a
@@ -337,6 +363,26 @@ const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k,
                                  int a_unsigned, int b_unsigned, int aligned16);
 
 /*
+ * The same with the call's mode (MIPGEMM_OVERWRITE or MIPGEMM_ACCUMULATE) taken into
+ * account: mode is argument 13 here.
+ */
+const char *mipgemm_variant_name_for_mode(int64_t m, int64_t n, int64_t k,
+                                          int64_t lda, int orderA,
+                                          int64_t ldb, int orderB,
+                                          int64_t ldc, int orderC,
+                                          int a_unsigned, int b_unsigned, int aligned16,
+                                          int mode);
+
+/*
+ * Sets one tuning value (see "Tuning values" above) for the whole process: `name`
+ * is the variable's name, `value` its text as in the environment, NULL or "" to
+ * clear it.  Returns 0, or -1 for an unknown name or a value that does not parse
+ * (nothing changes then).  Calls already running keep the values they started with;
+ * meant for tests and tuning scripts, not for steering concurrent production calls.
+ */
+int mipgemm_set_tuning(const char *name, const char *value);
+
+/*
  * The same for a call that is given a workspace of sufficient size: "packed+"
  * and the kernel that multiplies the packed operands when the packed route is
  * taken, else what mipgemm_variant_name returns.
@@ -360,8 +406,41 @@ const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k,
  * entry points this call allocates a few bytes of device memory, waits for its
  * kernel to finish and frees them again.  Returns 0, the negative number of an
  * invalid argument (1 pattern, 2 iterations, 4 tops), or a positive hipError_t.
+ * (The rate of pattern 1 includes register moves between the matrix
+ * instructions; mipgemm_mfma_ceiling_clocked has patterns without them.)
  */
 int mipgemm_mfma_ceiling(int pattern, int iterations, void *stream, double *tops);
+
+/*
+ * The same with more operand patterns and the shader clock the device ran at while
+ * the loop was executing (each workgroup reads the shader clock counter and the
+ * constant 100 MHz counter before and after its loop; `shader_mhz`, a HOST
+ * pointer, may be NULL).  pattern 0 and 1 as above; in pattern 1 the operands are
+ * rotated in registers between iterations, which puts 128 register moves between
+ * the 32 matrix instructions of an iteration.  pattern 2: random bytes in two fixed
+ * operand sets used in turn; pattern 3: random bytes in six fixed operand sets used
+ * in turn; in both the loop holds nothing but matrix instructions.
+ */
+int mipgemm_mfma_ceiling_clocked(int pattern, int iterations, void *stream,
+                                 double *tops, double *shader_mhz);
+
+/*
+ * For benchmarks: mipgemm_s8s8s32 on the kernel for large aligned problems (256 x
+ * 256 tiles, 128-deep k blocks), with every workgroup adding the shader clocks and
+ * the 10 ns ticks of its main loop to clocks[2 w] and clocks[2 w + 1] (w = the
+ * workgroup's number; `clocks` is DEVICE memory that the caller has zeroed, two
+ * 64-bit counters per tile of C with the tile count rounded up to a multiple of 8,
+ * `clocks_bytes` its size).  Sum of clocks / sum of ticks * 100 = shader MHz.
+ * Arguments 1..13 as in mipgemm_s8s8s32, then stream=14 clocks=15 clocks_bytes=16.
+ * Returns -1 when the problem is not one that kernel takes (m, n multiples of 256,
+ * k a multiple of 128, 16-byte aligned operands).
+ */
+int mipgemm_s8s8s32_clocked(int64_t m, int64_t n, int64_t k,
+                            const int8_t *A, int64_t lda, int orderA,
+                            const int8_t *B, int64_t ldb, int orderB,
+                            int32_t *C, int64_t ldc, int orderC,
+                            int mode, void *stream,
+                            unsigned long long *clocks, size_t clocks_bytes);
 
 #ifdef __cplusplus
 }

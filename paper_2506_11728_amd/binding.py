@@ -47,7 +47,10 @@ def exported_symbols():
             "mipgemm_mfma_ceiling", "mipgemm_conv_s8u8s32", "mipgemm_conv_workspace_size",
             "mipgemm_conv_variant_name", "mipgemm_im2col_u8", "mipgemm_conv_s8u8f32",
             "mipgemm_pack_b", "mipgemm_s8s8s32_batched", "mipgemm_u8s8s32_batched",
-            "mipgemm_s8u8s32_batched", "mipgemm_variant_name_with_workspace"]
+            "mipgemm_s8u8s32_batched", "mipgemm_variant_name_with_workspace",
+            "mipgemm_variant_name_for_mode", "mipgemm_set_tuning",
+            "mipgemm_conv_workspace_size_unaligned", "mipgemm_mfma_ceiling_clocked",
+            "mipgemm_s8s8s32_clocked"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -88,6 +91,13 @@ def load_library() -> ctypes.CDLL:
                                                              ctypes.c_size_t, vp, ctypes.c_float]
             lib.mipgemm_conv_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
+            lib.mipgemm_conv_workspace_size_unaligned.restype = ctypes.c_size_t
+            lib.mipgemm_conv_workspace_size_unaligned.argtypes = [i64] * 9
+            lib.mipgemm_variant_name_for_mode.restype = ctypes.c_char_p
+            lib.mipgemm_variant_name_for_mode.argtypes = (
+                [ctypes.c_int64] * 3 + [ctypes.c_int64, ctypes.c_int] * 3 + [ctypes.c_int] * 4)
+            lib.mipgemm_set_tuning.restype = ctypes.c_int
+            lib.mipgemm_set_tuning.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
             lib.mipgemm_conv_variant_name.restype = ctypes.c_char_p
             lib.mipgemm_conv_variant_name.argtypes = [i64] * 9
             for fn in (lib.mipgemm_s8s8s32_batched, lib.mipgemm_u8s8s32_batched,
@@ -102,6 +112,12 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_mfma_ceiling.restype = ctypes.c_int
             lib.mipgemm_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                                  ctypes.POINTER(ctypes.c_double)]
+            lib.mipgemm_mfma_ceiling_clocked.restype = ctypes.c_int
+            lib.mipgemm_mfma_ceiling_clocked.argtypes = [
+                ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
+                ctypes.POINTER(ctypes.c_double)]
+            lib.mipgemm_s8s8s32_clocked.restype = ctypes.c_int
+            lib.mipgemm_s8s8s32_clocked.argtypes = _GEMM_ARGTYPES[:13] + [vp, vp, ctypes.c_size_t]
             _lib = lib
     return _lib
 
@@ -201,6 +217,11 @@ def mipgemm_conv_workspace_size(b, hi, wi, ci, co, hf, wf, stride, pad) -> int:
     return int(load_library().mipgemm_conv_workspace_size(b, hi, wi, ci, co, hf, wf, stride, pad))
 
 
+def mipgemm_conv_workspace_size_unaligned(b, hi, wi, ci, co, hf, wf, stride, pad) -> int:
+    return int(load_library().mipgemm_conv_workspace_size_unaligned(b, hi, wi, ci, co, hf, wf,
+                                                                    stride, pad))
+
+
 def mipgemm_conv_variant_name(b, hi, wi, ci, co, hf, wf, stride, pad) -> str:
     return load_library().mipgemm_conv_variant_name(b, hi, wi, ci, co, hf, wf, stride,
                                                     pad).decode()
@@ -276,6 +297,41 @@ def mipgemm_variant_name(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
         int(a_unsigned), int(b_unsigned), int(aligned16)).decode()
 
 
+def mipgemm_variant_name_for_mode(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+                                  a_unsigned=False, b_unsigned=False, aligned16=True,
+                                  mode=OVERWRITE) -> str:
+    return load_library().mipgemm_variant_name_for_mode(
+        m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
+        int(a_unsigned), int(b_unsigned), int(aligned16), int(mode)).decode()
+
+
+def mipgemm_set_tuning(name: str, value) -> None:
+    """Sets one of the dispatcher's tuning values (MIPGEMM_VARIANT, MIPGEMM_SPLITK, MIPGEMM_PACK,
+    MIPGEMM_CONV) for the whole process; None or "" clears it."""
+    rc = load_library().mipgemm_set_tuning(name.encode(), None if value is None else str(value).encode())
+    if rc != 0:
+        raise ValueError("mipgemm_set_tuning(%r, %r) rejected" % (name, value))
+
+
+class tuning:
+    """Context manager: the given tuning values inside, cleared again afterwards.
+
+    tuning(MIPGEMM_VARIANT="dma64", MIPGEMM_SPLITK=4); None leaves a value cleared."""
+
+    def __init__(self, **values):
+        self.values = values
+
+    def __enter__(self):
+        for k, v in self.values.items():
+            mipgemm_set_tuning(k, v)
+        return self
+
+    def __exit__(self, *exc):
+        for k in self.values:
+            mipgemm_set_tuning(k, None)
+        return False
+
+
 def mipgemm_variant_name_with_workspace(m, n, k, lda, orderA, ldb, orderB, ldc, orderC,
                                         a_unsigned=False, b_unsigned=False, aligned16=True) -> str:
     return load_library().mipgemm_variant_name_with_workspace(
@@ -290,3 +346,24 @@ def mipgemm_mfma_ceiling(pattern: int, iterations: int = 20000, stream=None) -> 
     if rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc) if rc > 0 else "invalid argument %d" % -rc)
     return out.value
+
+
+def mipgemm_mfma_ceiling_clocked(pattern: int, iterations: int = 20000, stream=None):
+    """(TOPS, shader MHz) of the register-resident int8 MFMA loop; patterns 0..3 as in the header."""
+    tops, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = load_library().mipgemm_mfma_ceiling_clocked(pattern, iterations, _stream(stream),
+                                                     ctypes.byref(tops), ctypes.byref(mhz))
+    if rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc) if rc > 0 else "invalid argument %d" % -rc)
+    return tops.value, mhz.value
+
+
+def mipgemm_s8s8s32_clocked(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                            clocks, clocks_bytes, stream=None, check=True):
+    """mipgemm_s8s8s32 on the large-problem kernel with per-workgroup clock counters (benchmarks)."""
+    rc = load_library().mipgemm_s8s8s32_clocked(
+        m, n, k, _ptr(A), lda, orderA, _ptr(B), ldb, orderB, _ptr(C), ldc, orderC, mode,
+        _stream(stream), _ptr(clocks), clocks_bytes)
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc

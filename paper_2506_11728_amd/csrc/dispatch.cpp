@@ -1,8 +1,11 @@
 // Which kernel serves which problem: eligibility, tile shape, k ranges.  Host only.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "mip_internal.h"
+#include "tuning.h"
 
 namespace mip {
 
@@ -56,15 +59,15 @@ const char *plan_name(const Plan &plan) {
   }
 }
 
-// MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
+// The tuning value MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
 // "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
 // 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
 // eligible for; others fall back to the staged kernel of the same shape.
 // MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
 static bool forced_plan(const Problem &p, Plan *plan) {
-  const char *e = std::getenv("MIPGEMM_VARIANT");
-  if (!e || !*e) return false;
+  const char *e = tuning().variant;
+  if (!*e) return false;
   if (!std::strcmp(e, "simple")) { *plan = {KIND_SIMPLE, SHAPE_64, 1}; return true; }
   if (!std::strcmp(e, "dma256k128")) {
     if (!dma_k128_eligible(p)) return false;
@@ -89,11 +92,42 @@ static bool forced_plan(const Problem &p, Plan *plan) {
   return false;
 }
 
-static int forced_splits() {
-  const char *e = std::getenv("MIPGEMM_SPLITK");
-  if (!e || !*e) return 0;
-  int v = std::atoi(e);
-  return v > 0 ? v : 0;
+static int forced_splits() { return tuning().splitk; }
+
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
+  if (bytes <= 64 * 1024) return hipSuccess;
+  struct Granted { const void *kernel; int device; size_t bytes; };
+  static std::mutex lock;
+  static std::vector<Granted> granted;  // a few dozen kernels at most
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> guard(lock);
+  for (Granted &g : granted)
+    if (g.kernel == kernel && g.device == device) {
+      if (g.bytes >= bytes) return hipSuccess;
+      e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+      if (e == hipSuccess) g.bytes = bytes;
+      return e;
+    }
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) granted.push_back({kernel, device, bytes});
+  return e;
+}
+
+// Compute units of the current device, asked once; 256 (an MI355X) where no device answers,
+// as on a build host that only names kernels.
+int64_t compute_units() {
+  static std::once_flag once;
+  static int64_t count = 256;
+  std::call_once(once, [] {
+    int device = 0, n = 0;
+    if (hipGetDevice(&device) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && n > 0)
+      count = n;
+    (void)hipGetLastError();  // a missing device must not surface in a later call
+  });
+  return count;
 }
 
 // over all problems of a batch: what the chip sees is their sum
@@ -103,7 +137,7 @@ static int64_t tile_count(const Problem &p, Shape s) {
 }
 
 Plan choose_plan(const Problem &p) {
-  constexpr int64_t kComputeUnits = 256;
+  const int64_t kComputeUnits = compute_units();
   if (p.m == 0 || p.n == 0) return {KIND_NONE, SHAPE_64, 1};
   if (p.k == 0) return {p.accumulate ? KIND_NONE : KIND_FILL, SHAPE_64, 1};
   Plan plan;

@@ -13,7 +13,12 @@ namespace mip {
 // automatic wait-count insertion, which would drain every outstanding load
 // before any LDS read, stays out of the pipeline; the kernel places its own
 // s_waitcnt vmcnt before the barrier that publishes a stage.  M0 carries the
-// LDS base and needs one wait state before the load reads it.
+// LDS base and needs one wait state before the load reads it.  M0 is reserved
+// in this compiler: the register allocator never holds a value in it, and naming
+// it on the clobber list only draws a "reserved register" warning.  The compiler
+// sets M0 itself, right before use, for dynamically indexed register arrays and
+// message sends; the kernels that call this keep every register array fully
+// unrolled and send no messages, so nothing of the compiler's lives in M0 here.
 __device__ __forceinline__ void dma16(uint32_t voff, const uint8_t *sbase, uint32_t lds_addr) {
   asm volatile(
       "s_mov_b32 m0, %2\n\t"
@@ -21,7 +26,7 @@ __device__ __forceinline__ void dma16(uint32_t voff, const uint8_t *sbase, uint3
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(voff), "s"(sbase), "s"(lds_addr)
-      :);  // M0 is reserved: the compiler keeps nothing live in it across statements
+      :);
 }
 
 // The same with a full 64-bit address per lane (lanes may point anywhere).

@@ -378,9 +378,8 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   } else {
     P.conv = ConvGeom{};
   }
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  {
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);

@@ -32,6 +32,30 @@ struct Finish {
 };
 typedef v4i v4i_dword_aligned __attribute__((aligned(4)));  // four int32 of C: only dword alignment is known
 
+// The same with the case fixed at compile time: MODE bit 0 = accumulate (the old word is
+// needed), bit 1 = float output.  The write-back loops are instantiated once per MODE and
+// entered through a wave-uniform switch: a loop that has to allow for the old words of C
+// carries waits on the memory counter between its stores, and that counter counts stores as
+// well, so an overwriting call written that way keeps only a handful of stores in flight per
+// wave (measured on 256 x 256 tiles: 10 us to issue a tile's 64 stores per lane, the same
+// whether one compute unit stores or all of them).  The overwriting instances have no loads
+// and therefore no such waits.
+template <int MODE>
+struct FinishAs {
+  float scale;
+  static constexpr bool ACCUMULATE = (MODE & 1) != 0;
+  static constexpr bool TO_FLOAT = (MODE & 2) != 0;
+  __device__ __forceinline__ int operator()(int acc, int old) const {
+    if (!TO_FLOAT) return ACCUMULATE ? (int)((uint32_t)acc + (uint32_t)old) : acc;
+    const float s = (float)acc;
+    const float r = ACCUMULATE ? __fmaf_rn(s, scale, __int_as_float(old)) : __fmul_rn(s, scale);
+    return __float_as_int(r);
+  }
+};
+__device__ __forceinline__ int finish_mode(const Finish &fin, bool accumulate) {
+  return (accumulate ? 1 : 0) | (fin.to_float ? 2 : 0);
+}
+
 // Unsigned-operand correction (exact modulo 2^32).  sumB[j]: this lane's partial
 // sum over k of column (32*j + l%32) of the staged B; sumA[i]: same for row
 // (32*i + l%32) of A; lanes l and l^32 hold the two k halves.
@@ -66,10 +90,11 @@ __device__ __forceinline__ void unsigned_correction(v16i (&acc)[FM][FN], const i
 
 // C points at the first element of the wave's sub-tile; rows / cols are how
 // many of its 32*FM x 32*FN elements lie inside the matrix.
-template <int FM, int FN, bool FULL>
-__device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t *C, int64_t ldc,
-                                             int64_t rows, int64_t cols, bool accumulate,
-                                             int lane, const Finish fin) {
+template <int FM, int FN, bool FULL, int MODE>
+__device__ __forceinline__ void store_blocks_as(const v16i (&acc)[FM][FN], int32_t *C, int64_t ldc,
+                                                int64_t rows, int64_t cols, int lane,
+                                                const FinishAs<MODE> fin) {
+  constexpr bool ACCUMULATE = FinishAs<MODE>::ACCUMULATE;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     const int row = i * 32 + (lane & 31);
@@ -85,7 +110,7 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
       for (int q = 0; q < 4; ++q) {
         const int col = j * 32 + 8 * q;  // plus 4 * (lane / 32), already in crow
         whole[q] = FULL || col + 4 * (lane >> 5) + 3 < cols;
-        if (accumulate && whole[q]) old[q] = reinterpret_cast<const c_quad *>(crow + col)->v;
+        if (ACCUMULATE && whole[q]) old[q] = reinterpret_cast<const c_quad *>(crow + col)->v;
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -94,17 +119,29 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
                    acc[i][j][4 * q + 3]};
         if (whole[q]) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[q][e], accumulate);
+          for (int e = 0; e < 4; ++e) val[e] = fin(val[e], old[q][e]);
           reinterpret_cast<c_quad *>(crow + col)->v = val;
         } else {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             if (col + 4 * (lane >> 5) + e < cols)
-              crow[col + e] = fin(val[e], accumulate ? crow[col + e] : 0, accumulate);
+              crow[col + e] = fin(val[e], ACCUMULATE ? crow[col + e] : 0);
           }
         }
       }
     }
+  }
+}
+
+template <int FM, int FN, bool FULL>
+__device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t *C, int64_t ldc,
+                                             int64_t rows, int64_t cols, bool accumulate,
+                                             int lane, const Finish fin) {
+  switch (finish_mode(fin, accumulate)) {  // wave-uniform
+    case 0: store_blocks_as<FM, FN, FULL, 0>(acc, C, ldc, rows, cols, lane, FinishAs<0>{fin.scale}); break;
+    case 1: store_blocks_as<FM, FN, FULL, 1>(acc, C, ldc, rows, cols, lane, FinishAs<1>{fin.scale}); break;
+    case 2: store_blocks_as<FM, FN, FULL, 2>(acc, C, ldc, rows, cols, lane, FinishAs<2>{fin.scale}); break;
+    default: store_blocks_as<FM, FN, FULL, 3>(acc, C, ldc, rows, cols, lane, FinishAs<3>{fin.scale}); break;
   }
 }
 
@@ -121,27 +158,33 @@ __device__ __forceinline__ void store_blocks(const v16i (&acc)[FM][FN], int32_t 
 constexpr int STORE_PATCH_WORDS = 32 * 36;
 constexpr int STORE_PATCH_BYTES = STORE_PATCH_WORDS * 4;
 
-// An accumulating call reads the old words of C one 32 x 32 block ahead of the block
-// it is writing, so that their latency hides behind the turn through LDS and the
-// stores of the block before (loaded only when needed, a store per load in turn, the
-// 2048^3 case took 25.1 us against 15.5 us for an overwriting call).
-template <int FM, int FN>
-__device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], int32_t *C,
-                                                     int64_t ldc, bool accumulate, int lane,
-                                                     int32_t *patch, const Finish fin) {
+// An accumulating call reads the old words of C up to three 32 x 32 blocks ahead of the block
+// it is writing, so that their latency hides behind the turns through LDS and the stores of
+// the blocks before (loaded only when needed, a store per load in turn, the 2048^3 case took
+// 25.1 us against 15.5 us for an overwriting call; one block ahead 18.7 us).
+template <int FM, int FN, int MODE>
+__device__ __forceinline__ void store_blocks_via_lds_as(const v16i (&acc)[FM][FN], int32_t *C,
+                                                        int64_t ldc, int lane, int32_t *patch,
+                                                        const FinishAs<MODE> fin) {
+  constexpr bool ACCUMULATE = FinishAs<MODE>::ACCUMULATE;
+  constexpr int NB = FM * FN;
+  constexpr int AHEAD = ACCUMULATE ? (NB < 3 ? NB : 3) : 1;  // blocks of old words in registers
   // the piece of a 32 x 32 block this lane handles in pass t: 4 words of row t * 8 + lane / 8
   const int r0 = lane >> 3, c0 = (lane & 7) * 4;
   auto piece = [&](int block, int t) {
     const int i = block / FN, j = block % FN;
     return reinterpret_cast<v4i_dword_aligned *>(C + (int64_t)(i * 32 + t * 8 + r0) * ldc + j * 32 + c0);
   };
-  v4i old[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
-  if (accumulate) {
+  v4i old[AHEAD][4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) old[t] = __builtin_nontemporal_load(piece(0, t));
-  }
+  for (int b = 0; b < AHEAD; ++b)
 #pragma unroll
-  for (int block = 0; block < FM * FN; ++block) {
+    for (int t = 0; t < 4; ++t) {
+      old[b][t] = v4i{0, 0, 0, 0};
+      if (ACCUMULATE) old[b][t] = __builtin_nontemporal_load(piece(b, t));
+    }
+#pragma unroll
+  for (int block = 0; block < NB; ++block) {
     const int i = block / FN, j = block % FN;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -154,19 +197,28 @@ __device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], 
 #pragma unroll
     for (int t = 0; t < 4; ++t)
       val[t] = *reinterpret_cast<const v4i *>(patch + (t * 8 + r0) * 36 + c0);
-    v4i next[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
-    if (accumulate && block + 1 < FM * FN) {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) next[t] = __builtin_nontemporal_load(piece(block + 1, t));
-    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) val[t][e] = fin(val[t][e], old[t][e], accumulate);
+      for (int e = 0; e < 4; ++e) val[t][e] = fin(val[t][e], old[block % AHEAD][t][e]);
       __builtin_nontemporal_store(val[t], piece(block, t));
     }
+    if (ACCUMULATE && block + AHEAD < NB) {  // the slot just used takes the block AHEAD further on
 #pragma unroll
-    for (int t = 0; t < 4; ++t) old[t] = next[t];
+      for (int t = 0; t < 4; ++t) old[block % AHEAD][t] = __builtin_nontemporal_load(piece(block + AHEAD, t));
+    }
+  }
+}
+
+template <int FM, int FN>
+__device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], int32_t *C,
+                                                     int64_t ldc, bool accumulate, int lane,
+                                                     int32_t *patch, const Finish fin) {
+  switch (finish_mode(fin, accumulate)) {  // wave-uniform
+    case 0: store_blocks_via_lds_as<FM, FN, 0>(acc, C, ldc, lane, patch, FinishAs<0>{fin.scale}); break;
+    case 1: store_blocks_via_lds_as<FM, FN, 1>(acc, C, ldc, lane, patch, FinishAs<1>{fin.scale}); break;
+    case 2: store_blocks_via_lds_as<FM, FN, 2>(acc, C, ldc, lane, patch, FinishAs<2>{fin.scale}); break;
+    default: store_blocks_via_lds_as<FM, FN, 3>(acc, C, ldc, lane, patch, FinishAs<3>{fin.scale}); break;
   }
 }
 

@@ -315,22 +315,32 @@ __global__ __launch_bounds__(NTHREADS_ROWS) void conv_rows_kernel(RowsParams P) 
   // The two kinds of waves run loops of their own, with the same number of barriers (whole
   // waves take either branch, and a barrier counts waves wherever they wait): so each loop
   // is scheduled, and its memory waits are placed, for what that kind of wave does.
+  // The barrier is issued as the bare instruction with explicit fences, not as __syncthreads():
+  // the two loops sit in branches that whole waves take differently, which a convergent
+  // workgroup barrier of the language does not allow for.  Both kinds of wave execute exactly
+  // 1 + trips barriers, trips = the number of tiles t = blockIdx.x, blockIdx.x + step, ... below
+  // ntiles, the same expression in both loops.
+  auto role_barrier = []() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
   const int ntiles = (int)P.tiles, step = (int)gridDim.x;
   if (wave >= 4) {
     stage_tile(tile_at(blockIdx.x), smem);  // the host launches no more workgroups than tiles
-    __syncthreads();
+    role_barrier();
     int cur = 0;
     for (int t = blockIdx.x; t < ntiles; t += step) {
       if (ntiles - t > step) stage_tile(tile_at(t + step), smem + (cur ^ 1) * P.stage_bytes);
-      __syncthreads();  // the next stage is filled, this one is free
+      role_barrier();  // the next stage is filled, this one is free
       cur ^= 1;
     }
   } else {
-    __syncthreads();
+    role_barrier();
     int cur = 0;
     for (int t = blockIdx.x; t < ntiles; t += step) {
       compute_tile(tile_at(t), smem + cur * P.stage_bytes);
-      __syncthreads();
+      role_barrier();
       cur ^= 1;
     }
   }

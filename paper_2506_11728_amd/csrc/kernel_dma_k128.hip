@@ -27,17 +27,30 @@ struct DmaParams {
   int accumulate;         // C += instead of C =
   int out_float;          // dequantised output: float(sum) * scale
   float scale;
+  // not null: workgroup w adds the shader clocks and the 10 ns ticks it ran for to
+  // clocks[2 w], clocks[2 w + 1] (benchmarks: the clock the device sustained)
+  unsigned long long *clocks;
 };
 
 // ---------------------------------------------------------------------------
-// 256 x 256 tile, k blocks of 128 in two LDS stages: half as many barriers per unit
+// 256 x 256 tile, k blocks of 128, two LDS stages for A and three for B: half as many barriers per unit
 // of work as the 64-deep kernel, and every row of a k-contiguous operand is fetched as one full
 // 128-byte line.  A block is four sub-blocks of 32; the barrier that publishes
 // block t+1 sits before the last sub-block of block t, whose fragments are
 // already in registers, so the refill of the stage just read starts there.
 // ---------------------------------------------------------------------------
 constexpr int KD2 = 128;
-constexpr int STAGE2_BYTES = (DM + DN) * KD2;          // 64 KiB
+constexpr int A_STAGE_BYTES = DM * KD2;                // 32 KiB
+constexpr int B_STAGE_BYTES = DN * KD2;                // 32 KiB
+constexpr int A_STAGES = 2;
+// The B blocks have a third stage (160 KB of LDS in all): the loads of B for block t+2 go out
+// a whole block earlier than a second stage would allow, and the barrier of step t lets them
+// fly on.  What must have landed at a barrier was then issued at least one block of matrix
+// instructions before it (with two stages each, the B half had three quarters of a block
+// less, too little for a miss in L2).
+constexpr int B_STAGES = 3;
+constexpr int B_BASE = A_STAGES * A_STAGE_BYTES;
+constexpr int LDS2_BYTES = B_BASE + B_STAGES * B_STAGE_BYTES;  // 160 KiB
 constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
@@ -54,6 +67,11 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   int tm, tn;
   if (!tile_of_workgroup(P.tiles_m, P.tiles_n, &tm, &tn)) return;
   const int64_t m0 = (int64_t)tm * DM, n0 = (int64_t)tn * DN;
+  unsigned long long clock0 = 0, tick0 = 0;
+  if (P.clocks) {
+    clock0 = __builtin_readcyclecounter();
+    tick0 = wall_clock64();
+  }
 
   uint32_t offA[LOADS2], offB[LOADS2];
 #pragma unroll
@@ -72,15 +90,10 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   const int64_t stepB = B_KC ? KD2 : KD2 * P.ldb;
 
   const uint32_t lds0 = lds_address(smem) + wave * 1024;
-  // direct load q of a block: 0..7 A, 8..15 B
-  auto issue_one = [&](int stage, int q) {
-    const uint32_t sa = lds0 + stage * STAGE2_BYTES;
-    if (q < LOADS2) dma16(offA[q], gA, sa + q * 4096);
-    else dma16(offB[q - LOADS2], gB, sa + DM * KD2 + (q - LOADS2) * 4096);
-  };
-  auto advance = [&]() {
-    gA += stepA;
-    gB += stepB;
+  // direct load q (0..7) of the next A block / the next B block into the given stage
+  auto issue_a = [&](int stage, int q) { dma16(offA[q], gA, lds0 + stage * A_STAGE_BYTES + q * 4096); };
+  auto issue_b = [&](int stage, int q) {
+    dma16(offB[q], gB, lds0 + B_BASE + stage * B_STAGE_BYTES + q * 4096);
   };
 
   v16i acc[4][4];
@@ -114,23 +127,30 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
           sumA[i] = __builtin_amdgcn_sdot4(a[i][r], 0x01010101, sumA[i], false);
     }
   };
-  auto read_frag = [&](int stage, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
-    const uint8_t *sa = smem + stage * STAGE2_BYTES;
-    if (f < 4) a[f] = SA::fragment(sa, wm * 128 + f * 32, ks, lane);
-    else b[f - 4] = SB::fragment(sa + DM * KD2, wn * 128 + (f - 4) * 32, ks, lane);
+  // fragment f (0..3 of A, 4..7 of B) of sub-block ks of the block in stages (sa, sb)
+  auto read_frag = [&](int sa, int sb, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
+    if (f < 4) a[f] = SA::fragment(smem + sa * A_STAGE_BYTES, wm * 128 + f * 32, ks, lane);
+    else b[f - 4] = SB::fragment(smem + B_BASE + sb * B_STAGE_BYTES, wn * 128 + (f - 4) * 32, ks, lane);
   };
 
   const int nkt = P.nkt;  // k / 128
-  // prologue: block 0 whole, published; then the first half of block 1
+  // prologue: block 0 whole, published; then A and B of block 1 (B of block 2 follows in step 0)
 #pragma unroll
-  for (int q = 0; q < 2 * LOADS2; ++q) issue_one(0, q);
-  advance();
+  for (int q = 0; q < LOADS2; ++q) issue_a(0, q);
+#pragma unroll
+  for (int q = 0; q < LOADS2; ++q) issue_b(0, q);
+  gA += stepA;
+  gB += stepB;
   publish_barrier<0>();
 #pragma unroll
-  for (int f = 0; f < 8; ++f) read_frag(0, 0, f, fa[0], fb[0]);
+  for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f, fa[0], fb[0]);
   if (nkt > 1) {
 #pragma unroll
-    for (int q = 0; q < LOADS2; ++q) issue_one(1, q);
+    for (int q = 0; q < LOADS2; ++q) issue_a(1, q);
+#pragma unroll
+    for (int q = 0; q < LOADS2; ++q) issue_b(1, q);
+    gA += stepA;
+    gB += stepB;
   }
 
   // 16 MFMAs of one sub-block, with up to 8 fragment reads and 8 direct loads between them
@@ -147,20 +167,31 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   };
   auto nothing = [](int) {};
 
-  // NEXT: block t+1 exists.  NEXT2: block t+2 exists.
+  // Step t multiplies block t (A in stage t % 2, B in stage t % 3 = bcur).  On entry A and B
+  // of block t+1 are on their way.  NEXT: block t+1 exists.  NEXT2: block t+2 exists.
+  int bcur = 0;
   auto step = [&](int t, auto next_tag, auto next2_tag) {
     constexpr bool NEXT = decltype(next_tag)::value;
     constexpr bool NEXT2 = decltype(next2_tag)::value;
     const int cur = t & 1, oth = cur ^ 1;
-    // sub-block 0; fetch sub-block 1; second half of block t+1 (first half went out in step t-1)
-    phase(0, [&](int f) { read_frag(cur, 1, f, fa[1], fb[1]); },
-          [&](int q) { if (NEXT) issue_one(oth, LOADS2 + q); });
-    if (NEXT) advance();
-    phase(1, [&](int f) { read_frag(cur, 2, f, fa[0], fb[0]); }, nothing);
-    phase(0, [&](int f) { read_frag(cur, 3, f, fa[1], fb[1]); }, nothing);
-    if (NEXT) publish_barrier<0>();  // block t+1 visible; stage `cur` may be refilled
-    phase(1, [&](int f) { if (NEXT) read_frag(oth, 0, f, fa[0], fb[0]); },
-          [&](int q) { if (NEXT2) issue_one(cur, q); });
+    const int bnext = bcur == B_STAGES - 1 ? 0 : bcur + 1;
+    const int bfill = bnext == B_STAGES - 1 ? 0 : bnext + 1;  // held block t-1: free since the last barrier
+    // sub-block 0; fetch sub-block 1; B of block t+2
+    phase(0, [&](int f) { read_frag(cur, bcur, 1, f, fa[1], fb[1]); },
+          [&](int q) { if (NEXT2) issue_b(bfill, q); });
+    if (NEXT2) gB += stepB;
+    phase(1, [&](int f) { read_frag(cur, bcur, 2, f, fa[0], fb[0]); }, nothing);
+    phase(0, [&](int f) { read_frag(cur, bcur, 3, f, fa[1], fb[1]); }, nothing);
+    // block t+1 visible (only the B loads of block t+2 may still fly); the A stage of block t
+    // may be refilled
+    if (NEXT) {
+      if (NEXT2) publish_barrier<LOADS2>();
+      else publish_barrier<0>();
+    }
+    phase(1, [&](int f) { if (NEXT) read_frag(oth, bnext, 0, f, fa[0], fb[0]); },
+          [&](int q) { if (NEXT2) issue_a(cur, q); });
+    if (NEXT2) gA += stepA;
+    bcur = bnext;
   };
   using std::integral_constant;
   using T = integral_constant<bool, true>;
@@ -170,6 +201,10 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   if (t + 1 < nkt) { step(t, T{}, F{}); ++t; }
   step(t, F{}, F{});
 
+  if (P.clocks && tid == 0) {  // the main loop alone: what the matrix pipe saw
+    P.clocks[2 * blockIdx.x] += __builtin_readcyclecounter() - clock0;
+    P.clocks[2 * blockIdx.x + 1] += wall_clock64() - tick0;
+  }
   // the last step has no barrier of its own: wait until no wave reads the stages any more
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
@@ -198,8 +233,9 @@ bool dma_k128_eligible(const Problem &p) {
   return true;
 }
 
-hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks) {
   DmaParams P;
+  P.clocks = clocks;
   P.A = static_cast<const uint8_t *>(p.A);
   P.B = static_cast<const uint8_t *>(p.B);
   P.C = p.C;
@@ -216,7 +252,7 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
   P.scale = p.scale;
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
-  const size_t lds = (size_t)2 * STAGE2_BYTES;
+  const size_t lds = (size_t)LDS2_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
   void (*kern)(DmaParams) = nullptr;
@@ -231,8 +267,7 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s) {
   else if (b_kc) MIP_PICK(false, true);
   else MIP_PICK(false, false);
 #undef MIP_PICK
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);
   return hipGetLastError();

@@ -292,9 +292,8 @@ hipError_t launch_slab(const Problem &p, int nt, hipStream_t s) {
   if (nt == 1) kern = mt == 1 ? pick<1, 1>(b_kc, uns) : (mt == 2 ? pick<2, 1>(b_kc, uns) : pick<4, 1>(b_kc, uns));
   else kern = mt == 1 ? pick<1, 2>(b_kc, uns) : (mt == 2 ? pick<2, 2>(b_kc, uns) : pick<4, 2>(b_kc, uns));
   const size_t lds = (size_t)4 * (DB * nt + DA * mt) * 1024;
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  {
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
   }
   dim3 grid((unsigned)(((P.tiles + 7) / 8) * 8));

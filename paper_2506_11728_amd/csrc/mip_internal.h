@@ -69,6 +69,12 @@ struct Plan {
 };
 
 Plan choose_plan(const Problem &p);
+int64_t compute_units();  // of the current device, asked once (256 where no device answers)
+
+// A kernel that takes more than 64 KB of dynamic LDS has to be told so once per device
+// (hipFuncAttributeMaxDynamicSharedMemorySize); remembered, so that only the first launch of a
+// kernel with a given size pays for the call.
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
 const char *plan_name(const Plan &plan);  // static string
 
 hipError_t launch_fill_zero(const Problem &p, hipStream_t s);
@@ -76,7 +82,9 @@ hipError_t launch_simple(const Problem &p, hipStream_t s);
 hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t s);
 
 bool dma_k128_eligible(const Problem &p);
-hipError_t launch_dma_k128(const Problem &p, hipStream_t s);
+// clocks: null, or room for two counters per workgroup (one per 256 x 256 tile, rounded up to a
+// multiple of 8) that the kernel adds its shader clocks and 10 ns ticks to
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks = nullptr);
 
 bool slab_eligible(const Problem &p, int nt);  // nt: slab width in blocks of 16 columns, 1 or 2
 hipError_t launch_slab(const Problem &p, int nt, hipStream_t s);

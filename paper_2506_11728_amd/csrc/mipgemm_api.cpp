@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "api_internal.h"
+#include "tuning.h"
 
 namespace mip {
 
@@ -83,15 +84,13 @@ static bool packing_size_ok(int64_t m, int64_t n, int64_t k) {
   // but 64 x 1000 x 1000 8.8-7.8 -> 10, 1000^2 x 100 7.8-6.6 -> 8.3, 16 x 11009 x 4099 38-28 -> 45-31
   return m >= 96 && n >= 96 && k >= 192 && (double)m * (double)n * (double)k >= 4194304.0;  // 2^22
 }
-// MIPGEMM_PACK pins the decision for tests and tuning: "always" packs whatever the
+// The tuning value MIPGEMM_PACK pins the decision for tests and tuning: "always" packs whatever the
 // direct-to-LDS kernels cannot stream, however small; "never" leaves everything in place.
 static bool packing_pays(const Problem &p, const mip::Plan &plan) {
   if (plan.kind != mip::KIND_STAGED && plan.kind != mip::KIND_SIMPLE) return false;
   if (p.batch != 1 || p.conv || p.m < 1 || p.n < 1 || p.k < 1 || !packable(p.m, p.n, p.k)) return false;
-  if (const char *e = std::getenv("MIPGEMM_PACK")) {
-    if (!std::strcmp(e, "always")) return true;
-    if (!std::strcmp(e, "never")) return false;
-  }
+  if (tuning().pack > 0) return true;
+  if (tuning().pack < 0) return false;
   return packing_size_ok(p.m, p.n, p.k);
 }
 
@@ -161,6 +160,21 @@ int mipgemm_s8s8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t ld
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
   return mip::run_gemm(0, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
+}
+
+int mipgemm_s8s8s32_clocked(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda,
+                            int orderA, const int8_t *B, int64_t ldb, int orderB, int32_t *C,
+                            int64_t ldc, int orderC, int mode, void *stream,
+                            unsigned long long *clocks, size_t clocks_bytes) {
+  Problem p;
+  int rc = validate_and_normalise(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                                  nullptr, 0, &p);
+  if (rc != 0) return rc;
+  if (!clocks) return -15;
+  if (p.m == 0 || p.n == 0 || p.k == 0 || !mip::dma_k128_eligible(p)) return -1;
+  const size_t tiles = static_cast<size_t>(((p.m + 255) / 256) * ((p.n + 255) / 256));
+  if (clocks_bytes < (tiles + 7) / 8 * 8 * 2 * sizeof(unsigned long long)) return -16;
+  return static_cast<int>(mip::launch_dma_k128(p, static_cast<hipStream_t>(stream), clocks));
 }
 
 int mipgemm_u8s8s32(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda, int orderA,
@@ -304,17 +318,24 @@ const char *mipgemm_strerror(int code) {
   return "unknown mipgemm error code";
 }
 
-const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, int orderA,
-                                 int64_t ldb, int orderB, int64_t ldc, int orderC, int a_unsigned,
-                                 int b_unsigned, int aligned16) {
+const char *mipgemm_variant_name_for_mode(int64_t m, int64_t n, int64_t k, int64_t lda, int orderA,
+                                          int64_t ldb, int orderB, int64_t ldc, int orderC,
+                                          int a_unsigned, int b_unsigned, int aligned16, int mode) {
   Problem p;
   // stand-in addresses that only carry the alignment
   const void *fake = reinterpret_cast<const void *>(aligned16 ? uintptr_t(4096) : uintptr_t(4097));
   int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, fake, lda, orderA, fake, ldb,
                                   orderB, reinterpret_cast<int32_t *>(uintptr_t(4096)), ldc,
-                                  orderC, MIPGEMM_OVERWRITE, nullptr, 0, &p);
+                                  orderC, mode, nullptr, 0, &p);
   if (rc != 0) return "invalid";
   return mip::plan_name(mip::choose_plan(p));
+}
+
+const char *mipgemm_variant_name(int64_t m, int64_t n, int64_t k, int64_t lda, int orderA,
+                                 int64_t ldb, int orderB, int64_t ldc, int orderC, int a_unsigned,
+                                 int b_unsigned, int aligned16) {
+  return mipgemm_variant_name_for_mode(m, n, k, lda, orderA, ldb, orderB, ldc, orderC, a_unsigned,
+                                       b_unsigned, aligned16, MIPGEMM_OVERWRITE);
 }
 
 const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k, int64_t lda,

@@ -4,6 +4,7 @@
 #include <cstring>
 
 #include "api_internal.h"
+#include "tuning.h"
 
 using mip::Problem;
 using mip::order_ok;
@@ -87,14 +88,14 @@ enum Route {
   ROUTE_IM2COL   // the augmented matrix is written to the workspace, then a plain GEMM
 };
 
-// MIPGEMM_CONV pins a route for tests and tuning: "im2col" the written-out one, "rows" the
+// The tuning value MIPGEMM_CONV pins a route for tests and tuning: "im2col" the written-out one, "rows" the
 // row-segment kernel where it can serve.
 Route conv_route(const ConvCall &c, Problem p, mip::Plan *plan) {
-  const char *e = std::getenv("MIPGEMM_CONV");
-  if (e && !std::strcmp(e, "im2col")) return ROUTE_IM2COL;
+  const int pinned = mip::tuning().conv;
+  if (pinned == 1) return ROUTE_IM2COL;
   if (p.m == 0 || p.n == 0) return ROUTE_IM2COL;
   p.conv = &c.geom;
-  if (e && !std::strcmp(e, "rows") && mip::conv_rows_eligible(p)) return ROUTE_ROWS;
+  if (pinned == 2 && mip::conv_rows_eligible(p)) return ROUTE_ROWS;
   *plan = mip::choose_plan(p);
   if (plan->kind == mip::KIND_DMA) return ROUTE_TILES;
   // The row-segment kernel stages the image once per block of 64 filters: with many filters
@@ -109,17 +110,29 @@ Route conv_route(const ConvCall &c, Problem p, mip::Plan *plan) {
 
 extern "C" {
 
-size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
-                                   int64_t hf, int64_t wf, int64_t stride, int64_t pad) {
+static size_t conv_workspace_for(const void *fake, int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                 int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad) {
   ConvCall c;
   if (conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c) != 0) return 0;
   if (c.rows == 0 || co == 0) return 0;
-  const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
   mip::Plan plan;
   if (conv_route(c, conv_problem(c, co, fake, fake, const_cast<void *>(fake), MIPGEMM_OVERWRITE,
                                  true, nullptr), &plan) != ROUTE_IM2COL)
     return 0;
   return written_out_bytes(c, co);
+}
+
+size_t mipgemm_conv_workspace_size(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
+                                   int64_t hf, int64_t wf, int64_t stride, int64_t pad) {
+  return conv_workspace_for(reinterpret_cast<const void *>(uintptr_t(4096)), b, hi, wi, ci, co, hf,
+                            wf, stride, pad);
+}
+
+size_t mipgemm_conv_workspace_size_unaligned(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                             int64_t co, int64_t hf, int64_t wf, int64_t stride,
+                                             int64_t pad) {
+  return conv_workspace_for(reinterpret_cast<const void *>(uintptr_t(4097)), b, hi, wi, ci, co, hf,
+                            wf, stride, pad);
 }
 
 const char *mipgemm_conv_variant_name(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,

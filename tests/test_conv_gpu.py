@@ -21,20 +21,17 @@ def gpu():
 
 
 class Env:
+    """Tuning values of the library (kernel variant, k ranges, convolution route) for the calls inside."""
+
     def __init__(self, **kv):
-        self.want = kv
+        import paper_2506_11728_amd as M
+        self.ctx = M.tuning(**kv)
 
     def __enter__(self):
-        self.old = {k: os.environ.pop(k, None) for k in self.want}
-        for k, v in self.want.items():
-            if v is not None:
-                os.environ[k] = str(v)
+        self.ctx.__enter__()
 
     def __exit__(self, *a):
-        for k, v in self.old.items():
-            os.environ.pop(k, None)
-            if v is not None:
-                os.environ[k] = v
+        self.ctx.__exit__(*a)
 
 
 def tensors(shape, seed):

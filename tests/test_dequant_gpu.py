@@ -67,16 +67,9 @@ def test_dequant_against_oracle(gpu, oracle, case, scale, variant):
     dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
     dC = torch.from_numpy(C0.copy()).cuda()
     fn = getattr(gpu, "mipgemm_" + case.entry.replace("s32", "f32"))
-    old = os.environ.pop("MIPGEMM_VARIANT", None)
-    if variant != "auto":
-        os.environ["MIPGEMM_VARIANT"] = variant
-    try:
+    with gpu.tuning(MIPGEMM_VARIANT=None if variant == "auto" else variant):
         fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
            dC, case.ldc, case.orderC, case.mode, scale=scale)
-    finally:
-        os.environ.pop("MIPGEMM_VARIANT", None)
-        if old is not None:
-            os.environ["MIPGEMM_VARIANT"] = old
     torch.cuda.synchronize()
     raw = dC.cpu().numpy()
     assert np.array_equal(raw[pad_mask], C0[pad_mask])               # padding untouched

@@ -31,20 +31,15 @@ class VariantEnv:
     """Pins the kernel variant (and optionally the split-k factor) for the calls inside."""
 
     def __init__(self, variant, splits=None):
-        self.want = {"MIPGEMM_VARIANT": None if variant == "auto" else variant,
-                     "MIPGEMM_SPLITK": None if splits is None else str(splits)}
+        import paper_2506_11728_amd as M
+        self.ctx = M.tuning(MIPGEMM_VARIANT=None if variant == "auto" else variant,
+                            MIPGEMM_SPLITK=splits)
 
     def __enter__(self):
-        self.old = {k: os.environ.pop(k, None) for k in self.want}
-        for k, v in self.want.items():
-            if v is not None:
-                os.environ[k] = v
+        self.ctx.__enter__()
 
     def __exit__(self, *a):
-        for k, v in self.old.items():
-            os.environ.pop(k, None)
-            if v is not None:
-                os.environ[k] = v
+        self.ctx.__exit__(*a)
 
 
 def gpu_gemm(M, case, A, B, C, variant="auto", splits=None):
@@ -129,28 +124,31 @@ def test_conv_cases_through_swapped_u8s8(gpu, oracle, case):
 
 
 # ---------------------------------------------------------------------------
-# the headline size: sampled rows through the oracle, closed form, Freivalds
+# the headline size: every element against the oracle, closed form, Freivalds
 # ---------------------------------------------------------------------------
 
-def test_headline_8192_sampled_rows_and_freivalds(gpu, oracle):
+def test_headline_8192_every_element_and_freivalds(gpu, oracle):
+    """m = n = k = 8192, as dispatched (the kernel the benchmark times): all 2^26 elements of C
+    against the oracle's (about 25 s of host time), then three exact integer identities."""
     case = W.headline_case()
+    name = gpu.mipgemm_variant_name_for_mode(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
+                                             case.orderB, case.ldc, case.orderC, False, False, True,
+                                             case.mode)
+    assert name == "mfma_dma256_k128"
     ops = W.materialize(case)
-    got = gpu_gemm(gpu, case, ops.A, ops.B, ops.C).reshape(case.m, case.ldc)
+    got = gpu_gemm(gpu, case, ops.A, ops.B, ops.C)
+    print("headline: oracle on all %d rows" % case.m, flush=True)
+    want = oracle_result(oracle, case, ops)
+    assert np.array_equal(got, want)
+    got = got.reshape(case.m, case.ldc)
     rng = np.random.default_rng(99)
-    rows = np.unique(np.concatenate([rng.integers(0, case.m, size=48),
-                                     [0, 1, 31, 32, 127, 128, 255, 256, 4095, 4096, 8190, 8191]]))
-    # the oracle computes the sampled rows one block at a time: A restricted to those rows
-    A_rows = np.ascontiguousarray(ops.A.reshape(case.m, case.lda)[rows]).reshape(-1)
-    C_rows = np.zeros(rows.size * case.n, dtype=np.int32)
-    oracle.gemm_s8s8s32(rows.size, case.n, case.k, A_rows, case.lda, W.ROW_MAJOR,
-                        ops.B, case.ldb, W.ROW_MAJOR, C_rows, case.n, W.ROW_MAJOR, W.OVERWRITE)
-    assert np.array_equal(got[rows], C_rows.reshape(rows.size, case.n))
-    # every element, through an exact integer identity: C x == A (B x)
+    # and through an exact integer identity that involves neither the oracle nor the GPU path: C x == A (B x)
     for _ in range(3):
         x = rng.integers(-2, 2, size=case.n, endpoint=True).astype(np.int64)
         lhs = got.astype(np.int64) @ x
         rhs = ops.A2d.astype(np.int64) @ (ops.B2d.astype(np.int64) @ x)
         assert np.array_equal(lhs, rhs)
+    _expected.pop(case.name, None)   # 256 MB: not kept for the rest of the session
 
 
 def test_headline_8192_extreme_values(gpu):
@@ -289,6 +287,41 @@ def test_mfma_ceiling_probe(gpu):
     assert 500 < rand <= zero * 1.05 and zero < 5600      # TOPS, below the datasheet peak + margin
     with pytest.raises(gpu.MipGemmError):
         gpu.mipgemm_mfma_ceiling(2, 2000)
+    # the clocked form: more patterns, and a shader clock between idle and the maximum
+    for pattern in range(4):
+        tops, mhz = gpu.mipgemm_mfma_ceiling_clocked(pattern, 3000)
+        assert 500 < tops < 5600 and 300 < mhz < 2600, (pattern, tops, mhz)
+        # the rate follows from the clock: 4 SIMDs x 2048 operations per clock and compute unit
+        assert tops <= 256 * 4 * 2048 * mhz * 1e6 / 1e12 * 1.03
+    with pytest.raises(gpu.MipGemmError):
+        gpu.mipgemm_mfma_ceiling_clocked(4, 2000)
+
+
+def test_clocked_entry_point_matches_the_plain_one(gpu, oracle):
+    """mipgemm_s8s8s32_clocked: same bits as the oracle, counters filled for every tile."""
+    import torch
+    case = W.Case("clocked_512x768x1024", 8, 0, 512, 768, 1024, seed=31)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+    clocks = torch.zeros(2 * 8, dtype=torch.int64, device="cuda")     # 6 tiles, rounded up to 8
+    gpu.mipgemm_s8s8s32_clocked(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb,
+                                case.orderB, dC, case.ldc, case.orderC, case.mode, clocks, 16 * 8)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+    c = clocks.cpu().numpy().reshape(8, 2)
+    assert (c[:6] > 0).all() and (c[6:] == 0).all()
+    mhz = c[:6, 0].sum() / c[:6, 1].sum() * 100.0
+    assert 300 < mhz < 2600
+    # too little room for the counters, a shape the kernel does not take: nothing is launched
+    assert gpu.mipgemm_s8s8s32_clocked(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb,
+                                       case.orderB, dC, case.ldc, case.orderC, case.mode, clocks, 15 * 8,
+                                       check=False) == -16
+    assert gpu.mipgemm_s8s8s32_clocked(100, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb,
+                                       case.orderB, dC, case.ldc, case.orderC, case.mode, clocks, 16 * 8,
+                                       check=False) == -1
 
 
 def _deep_k_cases():
@@ -644,15 +677,11 @@ def test_packed_route_forced_on_small_and_skinny_shapes(gpu, oracle, spec):
     dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
     dC = torch.from_numpy(ops.C).cuda()
     ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda")
-    with VariantEnv("auto"):
-        os.environ["MIPGEMM_PACK"] = "always"
-        try:
-            assert gpu.mipgemm_variant_name_with_workspace(m, n, k, case.lda, oa, case.ldb, ob, case.ldc,
-                                                           oc, au, bu, True).startswith("packed")
-            getattr(gpu, "mipgemm_" + case.entry)(m, n, k, dA, case.lda, oa, dB, case.ldb, ob, dC,
-                                                  case.ldc, oc, mode, workspace=ws, workspace_bytes=need)
-        finally:
-            del os.environ["MIPGEMM_PACK"]
+    with VariantEnv("auto"), gpu.tuning(MIPGEMM_PACK="always"):
+        assert gpu.mipgemm_variant_name_with_workspace(m, n, k, case.lda, oa, case.ldb, ob, case.ldc,
+                                                       oc, au, bu, True).startswith("packed")
+        getattr(gpu, "mipgemm_" + case.entry)(m, n, k, dA, case.lda, oa, dB, case.ldb, ob, dC,
+                                              case.ldc, oc, mode, workspace=ws, workspace_bytes=need)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), want)
     assert (ws[need:].cpu().numpy() == 0x5A).all()
@@ -664,8 +693,7 @@ def test_seeded_sweep_of_the_packed_route(gpu, oracle):
     both modes) forced through the packed route."""
     import torch
     rng = np.random.default_rng(2025)
-    os.environ["MIPGEMM_PACK"] = "always"
-    try:
+    with gpu.tuning(MIPGEMM_PACK="always"):
         for it in range(40):
             m, n, k = int(rng.integers(1, 700)), int(rng.integers(1, 700)), int(rng.integers(1, 1500))
             oa, ob, oc = (int(x) for x in rng.integers(0, 2, size=3))
@@ -687,5 +715,3 @@ def test_seeded_sweep_of_the_packed_route(gpu, oracle):
                 workspace=ws, workspace_bytes=need)
             torch.cuda.synchronize()
             assert np.array_equal(dC.cpu().numpy(), want), (m, n, k, oa, ob, oc, pad, au, bu, mode)
-    finally:
-        del os.environ["MIPGEMM_PACK"]
