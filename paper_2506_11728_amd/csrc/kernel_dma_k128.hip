@@ -30,6 +30,10 @@ struct DmaParams {
   // not null: workgroup w adds the shader clocks and the 10 ns ticks it ran for to
   // clocks[2 w], clocks[2 w + 1] (benchmarks: the clock the device sustained)
   unsigned long long *clocks;
+  // Workgroups of the first round (the first first_round workgroup numbers: one per compute
+  // unit) start late by their row in the XCD's patch of tiles times stagger_ticks (10 ns
+  // each); 0 = all at once.
+  int first_round, stagger_ticks;
 };
 
 // ---------------------------------------------------------------------------
@@ -52,6 +56,7 @@ constexpr int B_STAGES = 3;
 constexpr int B_BASE = A_STAGES * A_STAGE_BYTES;
 constexpr int LDS2_BYTES = B_BASE + B_STAGES * B_STAGE_BYTES;  // 160 KiB
 constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
+constexpr int STAGGER_TICKS = 100;                     // 1 us between the rows of an XCD's patch
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
 template <bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
@@ -67,6 +72,17 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   int tm, tn;
   if (!tile_of_workgroup(P.tiles_m, P.tiles_n, &tm, &tn)) return;
   const int64_t m0 = (int64_t)tm * DM, n0 = (int64_t)tn * DN;
+  // With several rounds of tiles all compute units would reach their write-backs at the
+  // same moments, round after round, and the 32 of one XCD share one path to memory: a tile's
+  // stores take about 7 us then, against 3.5 us when only four compute units of an XCD store
+  // at a time.  The eight tile rows of an XCD's patch therefore start 1 us apart and stay
+  // apart in every later round (the workgroups of one row share their A panel and keep
+  // step; a B panel's users drift by a few k blocks, which the L2 still covers).
+  if (P.stagger_ticks > 0 && (int)blockIdx.x < P.first_round) {
+    const unsigned long long until =
+        wall_clock64() + (unsigned long long)((blockIdx.x / 8) % 8) * P.stagger_ticks;
+    while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
+  }
   unsigned long long clock0 = 0, tick0 = 0;
   if (P.clocks) {
     clock0 = __builtin_readcyclecounter();
@@ -252,6 +268,10 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
   P.scale = p.scale;
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
+  // (measured at 8192^3, four rounds: 326 -> 310 us on constant operands, 452 -> 444 us on
+  // random ones; the 7 us of late start are not earned back by a single round)
+  P.first_round = (int)compute_units();
+  P.stagger_ticks = ntiles >= 2 * P.first_round ? STAGGER_TICKS : 0;
   const size_t lds = (size_t)LDS2_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
