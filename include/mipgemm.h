@@ -88,6 +88,11 @@ extern "C" {
 /* largest m, n, k or leading dimension accepted */
 #define MIPGEMM_MAX_DIM 2147483647LL
 
+/* size of the static device buffer behind mipgemm_s8s8s32_noalloc, and the code that
+ * call returns for a problem that would need more */
+#define MIPGEMM_STATIC_SCRATCH_BYTES (64u << 20)
+#define MIPGEMM_ERR_STATIC_SCRATCH (-100)
+
 /*
  * Signed x signed: the paper's MIP GEMM proper (Section 5; every instruction it
  * surveys for this role, sdot / vmadot / the AMX tile product, takes two signed
@@ -102,6 +107,34 @@ int mipgemm_s8s8s32(int64_t m, int64_t n, int64_t k,
                     int mode,
                     void *workspace, size_t workspace_bytes,
                     void *stream);
+
+/*
+ * mipgemm_s8s8s32 for callers that can neither allocate device memory nor bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments without the workspace pair (stream is argument
+ * 14), same results, same errors.  Where mipgemm_s8s8s32 would pack its operands
+ * into the caller's workspace, this call packs them into a static device buffer
+ * of MIPGEMM_STATIC_SCRATCH_BYTES (64 MiB) that every GPU the library runs on
+ * holds from the first such call until the process ends; the call allocates and
+ * frees nothing.  A problem whose packed operands need more, i.e.
+ * mipgemm_workspace_size-style (round_up(m, 256) + round_up(n, 256)) * kp bytes
+ * above that limit, is rejected with MIPGEMM_ERR_STATIC_SCRATCH: nothing is
+ * enqueued and nothing is touched (operands that are 16-byte aligned with k a
+ * multiple of 64 are streamed as they are stored, need no buffer and have no such
+ * limit).  All calls on one GPU share the one buffer: calls that overlap in time
+ * on the same GPU (two streams, two threads) race on it and must be serialised by
+ * the caller.  The buffer keeps the last call's contents; every byte a call reads
+ * back it has written first, so nothing needs clearing.
+ */
+int mipgemm_s8s8s32_noalloc(int64_t m, int64_t n, int64_t k,
+                            const int8_t *A, int64_t lda, int orderA,
+                            const int8_t *B, int64_t ldb, int orderB,
+                            int32_t *C, int64_t ldc, int orderC,
+                            int mode,
+                            void *stream);
+
+/* MIPGEMM_STATIC_SCRATCH_BYTES as the loaded library was built with. */
+size_t mipgemm_static_scratch_bytes(void);
 
 /*
  * Unsigned A (for example activations quantized to 0..255) times signed B

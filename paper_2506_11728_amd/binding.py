@@ -50,7 +50,7 @@ def exported_symbols():
             "mipgemm_s8u8s32_batched", "mipgemm_variant_name_with_workspace",
             "mipgemm_variant_name_for_mode", "mipgemm_set_tuning",
             "mipgemm_conv_workspace_size_unaligned", "mipgemm_mfma_ceiling_clocked",
-            "mipgemm_s8s8s32_clocked"]
+            "mipgemm_s8s8s32_clocked", "mipgemm_s8s8s32_noalloc", "mipgemm_static_scratch_bytes"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -118,6 +118,10 @@ def load_library() -> ctypes.CDLL:
                 ctypes.POINTER(ctypes.c_double)]
             lib.mipgemm_s8s8s32_clocked.restype = ctypes.c_int
             lib.mipgemm_s8s8s32_clocked.argtypes = _GEMM_ARGTYPES[:13] + [vp, vp, ctypes.c_size_t]
+            lib.mipgemm_s8s8s32_noalloc.restype = ctypes.c_int
+            lib.mipgemm_s8s8s32_noalloc.argtypes = _GEMM_ARGTYPES[:13] + [vp]
+            lib.mipgemm_static_scratch_bytes.restype = ctypes.c_size_t
+            lib.mipgemm_static_scratch_bytes.argtypes = []
             _lib = lib
     return _lib
 
@@ -367,3 +371,21 @@ def mipgemm_s8s8s32_clocked(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, ord
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc
+
+
+ERR_STATIC_SCRATCH = -100
+
+
+def mipgemm_s8s8s32_noalloc(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                            stream=None, check=True):
+    """mipgemm_s8s8s32 with the packed route's buffers in the library's static device array."""
+    rc = load_library().mipgemm_s8s8s32_noalloc(
+        m, n, k, _ptr(A), lda, orderA, _ptr(B), ldb, orderB, _ptr(C), ldc, orderC, mode,
+        _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_static_scratch_bytes() -> int:
+    return int(load_library().mipgemm_static_scratch_bytes())

@@ -20,6 +20,10 @@ int validate_and_normalise(int a_unsigned, int b_unsigned, int64_t m, int64_t n,
                            int orderB, void *C, int64_t ldc, int orderC, int mode,
                            void *workspace, size_t workspace_bytes, Problem *out);
 
+// Bytes of workspace with which this call would take the packed route (operands that the
+// direct-to-LDS kernels cannot stream, and a product large enough for packing to pay), else 0.
+size_t packed_route_bytes(const Problem &p);
+
 // Enqueues the kernels of a plan.
 hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s);
 

@@ -94,6 +94,10 @@ static bool packing_pays(const Problem &p, const mip::Plan &plan) {
   return packing_size_ok(p.m, p.n, p.k);
 }
 
+size_t packed_route_bytes(const Problem &p) {
+  return packing_pays(p, choose_plan(p)) ? packed_bytes(p.m, p.n, p.k) : 0;
+}
+
 int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
         int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb, int orderB,
         void *C, int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
@@ -314,6 +318,8 @@ const char *mipgemm_strerror(int code) {
       "invalid argument 17 (scale is not finite)", "invalid argument 18", "invalid argument 19",
       "invalid argument 20"};
   if (code <= 0 && code >= -20) return args[-code];
+  if (code == MIPGEMM_ERR_STATIC_SCRATCH)
+    return "the problem needs more scratch memory than the library's static buffer holds";
   if (code > 0) return hipGetErrorString(static_cast<hipError_t>(code));
   return "unknown mipgemm error code";
 }
