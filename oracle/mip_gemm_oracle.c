@@ -45,8 +45,13 @@
  * hand-worked example stored under tests/golden/.  The dequantised variant at
  * the end of the file is pinned by the same hand-worked example with exact
  * scales, by scale = 1 against the integer function, by closed forms and by
- * linearity in the scale.
+ * linearity in the scale.  The requantised variant is pinned by hand-worked
+ * values (scale 1/8 of the same example, a row of exact ties and saturating
+ * values, and a sum above 2^24 whose float32 image decides the tie), by scale = 1
+ * on small sums against the integer function, by the fp64 dequantised function
+ * away from ties, and by the same three IEEE operations done by numpy.
  */
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -151,6 +156,61 @@ int oracle_mip_gemm_dequant(int a_unsigned, int b_unsigned,
             if (mode == ORACLE_ACCUMULATE)
                 r += (double)C0[at(i, j, ldc, orderC)];
             out[(size_t)i * (size_t)n + (size_t)j] = r;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Requantised result, int8: the integer product brought back to 8 bits for the
+ * next quantized layer.  The paper's scheme (Section 7.3) represents a real
+ * matrix X by X^q with X ~ s_X X^q (symmetric, scale only); the product
+ * C^r = s_A s_B C^q expressed in the output's own scale s_C is therefore
+ *
+ *     Q(i,j) = clip( rint( scale * S(i,j) ), -128, 127 ),   scale = s_A s_B / s_C
+ *
+ * The paper does not spell this step out.  Readings taken (both the oracle and
+ * the GPU take the rounding decision in the same precision, float32, which is
+ * the precision the GPU entry point computes in):
+ *   - S is the int32 sum defined at the top of this file (wraparound reading);
+ *   - S is converted to float32 (round to nearest, ties to even), multiplied by
+ *     `scale` in one float32 multiplication, and rounded to an integer with
+ *     ties to even (rintf in the default rounding mode);
+ *   - the result saturates to the full int8 range [-128, 127];
+ *   - there is no accumulate form (a quantized output has no running sum);
+ *   - `scale` must be finite.
+ * Q is m x n int8 with leading dimension ldq in order orderQ; bytes outside the
+ * m x n matrix are never written.
+ */
+int oracle_mip_gemm_requant(int a_unsigned, int b_unsigned,
+                            int64_t m, int64_t n, int64_t k,
+                            const void *A, int64_t lda, int orderA,
+                            const void *B, int64_t ldb, int orderB,
+                            float scale,
+                            int8_t *Q, int64_t ldq, int orderQ)
+{
+    if (m < 0 || n < 0 || k < 0) return -1;
+    if (orderA != ORACLE_ROW_MAJOR && orderA != ORACLE_COL_MAJOR) return -1;
+    if (orderB != ORACLE_ROW_MAJOR && orderB != ORACLE_COL_MAJOR) return -1;
+    if (orderQ != ORACLE_ROW_MAJOR && orderQ != ORACLE_COL_MAJOR) return -1;
+    if (lda < (orderA == ORACLE_ROW_MAJOR ? k : m)) return -1;
+    if (ldb < (orderB == ORACLE_ROW_MAJOR ? n : k)) return -1;
+    if (ldq < (orderQ == ORACLE_ROW_MAJOR ? n : m)) return -1;
+    if (!(scale == scale) || scale - scale != 0.0f) return -1;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t j = 0; j < n; ++j) {
+            uint32_t s = 0u;
+            for (int64_t p = 0; p < k; ++p)
+                s += widen(A, at(i, p, lda, orderA), a_unsigned)
+                   * widen(B, at(p, j, ldb, orderB), b_unsigned);
+            volatile float f = (float)(int32_t)s;   /* one rounding: int32 -> float32 */
+            volatile float r = f * scale;           /* one rounding: float32 product   */
+            float q = rintf(r);                     /* to an integer, ties to even     */
+            if (q > 127.0f) q = 127.0f;
+            if (q < -128.0f) q = -128.0f;
+            Q[at(i, j, ldq, orderQ)] = (int8_t)q;
         }
     }
     return 0;

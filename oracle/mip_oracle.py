@@ -37,7 +37,7 @@ def build(force: bool = False) -> str:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-             "-Wall", "-Wextra", "-o", tmp, _SRC, _SRC_CONV])
+             "-Wall", "-Wextra", "-o", tmp, _SRC, _SRC_CONV, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -55,6 +55,9 @@ def _load():
             lib.oracle_mip_gemm_dequant.restype = ci
             lib.oracle_mip_gemm_dequant.argtypes = [ci, ci, i64, i64, i64, vp, i64, ci, vp, i64, ci,
                                                     ctypes.c_float, vp, i64, ci, ci, vp]
+            lib.oracle_mip_gemm_requant.restype = ci
+            lib.oracle_mip_gemm_requant.argtypes = [ci, ci, i64, i64, i64, vp, i64, ci, vp, i64, ci,
+                                                    ctypes.c_float, vp, i64, ci]
             lib.oracle_num_threads.restype = ci
             lib.oracle_conv_out_extent.restype = i64
             lib.oracle_conv_out_extent.argtypes = [i64, i64, i64, i64]
@@ -150,6 +153,30 @@ def gemm_dequant(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return out
+
+
+def gemm_requant(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB, scale,
+                 Q, ldq, orderQ):
+    """Q (m x n, int8) = clip(rint(scale * (A * B))), in place on the flat int8 buffer ``Q``
+    (the quantization scheme of the paper's Section 7.3 applied to the output; the rounding
+    decision is taken in float32).  ``scale`` is rounded to float32 first."""
+    A = np.asarray(A)
+    B = np.asarray(B)
+    want_a = np.uint8 if a_unsigned else np.int8
+    want_b = np.uint8 if b_unsigned else np.int8
+    if A.dtype != want_a or B.dtype != want_b or Q.dtype != np.int8:
+        raise TypeError("operand dtypes do not match the entry point")
+    if not Q.flags.writeable or Q.ndim != 1 or not Q.flags.c_contiguous:
+        raise ValueError("Q must be a flat, contiguous, writeable buffer")
+    if A.size < _min_len(m, k, lda, orderA) or B.size < _min_len(k, n, ldb, orderB) \
+            or Q.size < _min_len(m, n, ldq, orderQ):
+        raise ValueError("buffer shorter than the matrix it is said to hold")
+    rc = _load().oracle_mip_gemm_requant(
+        int(bool(a_unsigned)), int(bool(b_unsigned)), m, n, k, A.ctypes.data, lda, orderA,
+        B.ctypes.data, ldb, orderB, float(np.float32(scale)), Q.ctypes.data, ldq, orderQ)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return Q
 
 
 # ---------------------------------------------------------------------------

@@ -516,3 +516,92 @@ def test_dequant_closed_forms_and_wraparound(oracle):
     k = 131072
     got = run_dequant(oracle, np.full((1, k), -128, np.int8), np.full((k, 1), -128, np.int8), 1.0)
     assert got[0, 0] == -2.0 ** 31
+
+
+# ---------------------------------------------------------------------------
+# requantised variant (paper Section 7.3 applied to the output: Q = clip(rint(scale * C^q)))
+# ---------------------------------------------------------------------------
+
+def run_requant(oracle, A2d, B2d, scale, oa=R, ob=R, oq=R, pad=0):
+    m, k = A2d.shape
+    n = B2d.shape[1]
+    lda = (k if oa == R else m) + pad
+    ldb = (n if ob == R else k) + pad
+    ldq = (n if oq == R else m) + pad
+    A = W.embed(A2d, oa, lda, A2d.dtype.type(W.SENTINEL_BYTE))
+    B = W.embed(B2d, ob, ldb, B2d.dtype.type(W.SENTINEL_BYTE))
+    Q = W.embed(np.full((m, n), 0x33, dtype=np.int8), oq, ldq, np.int8(W.SENTINEL_BYTE))
+    oracle.gemm_requant(A2d.dtype == np.uint8, B2d.dtype == np.uint8, m, n, k, A, lda, oa, B, ldb, ob,
+                        scale, Q, ldq, oq)
+    mask = W.padding_mask(m, n, oq, ldq)
+    assert (Q[mask] == np.int8(W.SENTINEL_BYTE)).all()          # padding untouched
+    return W.extract(Q, m, n, oq, ldq)
+
+
+def test_requant_hand_worked_values(oracle):
+    """A dropped rounding, rounding half away from zero, a clip to +-127, or a decision taken in
+    double instead of float32 each fail one of these."""
+    g = _read_matrices(os.path.join(GOLDEN, "hand_worked_2x3x4.txt"))
+    q = _read_matrices(os.path.join(GOLDEN, "hand_worked_requant.txt"))
+    A, B = g["A"].astype(np.int8), g["B"].astype(np.int8)
+    assert np.array_equal(run_requant(oracle, A, B, 2.0 ** -3), q["Q_EIGHTH"])
+    assert np.array_equal(run_requant(oracle, A, B, 2.0 ** -5), q["Q_32ND"])
+    # ties and saturation: the column sums are what the file says they are (checked here in
+    # Python integers), and the oracle turns them into the hand-worked bytes
+    ones, TB = np.ones((1, 3), dtype=np.int8), q["TIES_B"].astype(np.int8)
+    assert [sum(int(TB[p, j]) for p in range(3)) for j in range(11)] == [int(x) for x in q["TIES_S"][0]]
+    assert np.array_equal(run_requant(oracle, ones, TB, 0.5), q["TIES_Q"])
+    # a sum above 2^24: its float32 image decides
+    a = np.full((1, 1025), -128, dtype=np.int8)
+    a[0, -1] = 1
+    assert 1024 * 16384 + 1 == int(q["F32_S"][0, 0])
+    assert run_requant(oracle, a, a.T.copy(), 2.0 ** -25)[0, 0] == q["F32_Q_SCALE_2POWMINUS25"][0, 0]
+    assert run_requant(oracle, a, a.T.copy(), 3 * 2.0 ** -25)[0, 0] == q["F32_Q_SCALE_3x2POWMINUS25"][0, 0]
+
+
+@pytest.mark.parametrize("types", ["s8s8", "u8s8", "s8u8"])
+def test_requant_against_the_integer_and_the_fp64_functions(oracle, types):
+    rng = np.random.default_rng(37)
+    m, n, k = 19, 23, 96
+    ta = np.uint8 if types == "u8s8" else np.int8
+    tb = np.uint8 if types == "s8u8" else np.int8
+    A, B = rand(rng, (m, k), ta), rand(rng, (k, n), tb)
+    S, _, _ = run(oracle, A, B)                                  # integer oracle, pinned above
+    # scale 1 on sums that fit: the sum itself; beyond, the nearer end of the range
+    assert np.array_equal(run_requant(oracle, A, B, 1.0), np.clip(S, -128, 127))
+    for scale in (2.0 ** -9, 1.0 / 3000, 7.3e-4, -2.0 ** -10, -1.9e-3):
+        s32 = np.float32(scale)
+        got = run_requant(oracle, A, B, scale, oa=CM, ob=CM, oq=CM, pad=3)
+        # the same three IEEE float32 operations done by numpy on the integer oracle's sums
+        want = np.clip(np.rint(S.astype(np.float32) * s32), -128, 127).astype(np.int8)
+        assert np.array_equal(got, want)
+        # and the fp64 dequantised oracle, wherever its value is not within 1e-4 of a tie
+        D = run_dequant(oracle, A, B, scale)
+        safe = np.abs(np.abs(D - np.floor(D)) - 0.5) > 1e-4
+        assert safe.mean() > 0.99
+        assert np.array_equal(got[safe], np.clip(np.rint(D), -128, 127).astype(np.int8)[safe])
+        # odd symmetry of round-half-even, away from the asymmetric ends of the range
+        neg = run_requant(oracle, A, B, -scale, oa=CM, ob=CM, oq=CM, pad=3)
+        inner = (got > -128) & (got < 127) & (neg > -128) & (neg < 127)
+        assert np.array_equal(neg[inner], -got[inner])
+
+
+def test_requant_layouts_closed_forms_and_bad_scale(oracle):
+    rng = np.random.default_rng(41)
+    A, B = rand(rng, (5, 40), np.int8), rand(rng, (40, 7), np.uint8)
+    ref = run_requant(oracle, A, B, 1e-3)
+    for oa in (R, CM):
+        for ob in (R, CM):
+            for oq in (R, CM):
+                assert np.array_equal(run_requant(oracle, A, B, 1e-3, oa, ob, oq, pad=17), ref)
+    # all(-128) x all(-128), k = 8: S = 131072; times 2^-11 = 64; times 2^-10 = 128 -> 127
+    A8, B8 = np.full((2, 8), -128, np.int8), np.full((8, 3), -128, np.int8)
+    assert (run_requant(oracle, A8, B8, 2.0 ** -11) == 64).all()
+    assert (run_requant(oracle, A8, B8, 2.0 ** -10) == 127).all()
+    assert (run_requant(oracle, A8, B8, -2.0 ** -10) == -128).all()
+    assert (run_requant(oracle, A8, B8, 0.0) == 0).all()
+    # an empty sum is 0; empty matrices touch nothing
+    assert (run_requant(oracle, np.zeros((2, 0), np.int8), np.zeros((0, 3), np.int8), 5.0) == 0).all()
+    for bad in (float("nan"), float("inf")):
+        with pytest.raises(ValueError):
+            run_requant(oracle, A8, B8, bad)
