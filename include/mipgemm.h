@@ -249,6 +249,47 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k,
                     void *stream, float scale);
 
 /*
+ * Requantised output: the integer product brought back to 8 bits for the next
+ * quantized layer.  The paper's scheme (Section 7.3) represents a real matrix X by
+ * X^q with X ~ s_X X^q and gets C^r = s_A s_B C^q; in the output's own scale s_C
+ * that is
+ *     C(i,j) = clip( rint( float(S(i,j)) * scale ), -128, 127 ),  scale = s_A s_B / s_C
+ * with S the int32 sum of the s32 entry points, float() and the product rounded to
+ * nearest even in float32, rint rounding to the nearest integer with ties to even,
+ * and saturation to the full int8 range (the paper does not spell this step out:
+ * these are the readings taken).  C is int8 (ldc counts bytes; no alignment
+ * needed), which makes the write a quarter of the int32 one: on shapes whose time
+ * is the write of C (convolutions at large batch, short k) that is most of it.
+ * Arguments and numbering as for the f32 entry points (`scale` = 17, finite);
+ * `mode` must be MIPGEMM_OVERWRITE (a quantized output has no running sum: -13).
+ * A problem with few tiles splits k only with workspace for slots of partial sums,
+ * as the f32 entry points do (mipgemm_workspace_size_f32 bytes).
+ */
+int mipgemm_s8s8s8(int64_t m, int64_t n, int64_t k,
+                   const int8_t *A, int64_t lda, int orderA,
+                   const int8_t *B, int64_t ldb, int orderB,
+                   int8_t *C, int64_t ldc, int orderC,
+                   int mode,
+                   void *workspace, size_t workspace_bytes,
+                   void *stream, float scale);
+
+int mipgemm_u8s8s8(int64_t m, int64_t n, int64_t k,
+                   const uint8_t *A, int64_t lda, int orderA,
+                   const int8_t *B, int64_t ldb, int orderB,
+                   int8_t *C, int64_t ldc, int orderC,
+                   int mode,
+                   void *workspace, size_t workspace_bytes,
+                   void *stream, float scale);
+
+int mipgemm_s8u8s8(int64_t m, int64_t n, int64_t k,
+                   const int8_t *A, int64_t lda, int orderA,
+                   const uint8_t *B, int64_t ldb, int orderB,
+                   int8_t *C, int64_t ldc, int orderC,
+                   int mode,
+                   void *workspace, size_t workspace_bytes,
+                   void *stream, float scale);
+
+/*
  * Convolution by lowering (paper Section 7.2: O = CONV(F, I); the input tensor is
  * turned into an augmented matrix by IM2COL and the convolution into a GEMM of
  * dimensions (m, n, k) = (c_o, b h_o w_o, c_i h_f w_f); the paper counts the
@@ -372,6 +413,23 @@ int mipgemm_pack_b(int64_t k, int64_t n,
  */
 size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k,
                               int orderA, int orderB, int orderC);
+
+/*
+ * The same for the f32 entry points.  Besides the packed operands, a float-output
+ * call can use room for slots of partial sums: a problem with too few tiles of C
+ * to occupy the device splits k over several workgroups per tile, and since float
+ * sums must not be combined in arbitrary order, the workgroups of a tile meet in
+ * such slots with their int32 partial sums (splits x tile size x 4 bytes per tile;
+ * the last to arrive adds them up, still in integers, and converts once: same
+ * result as an unsplit call).  Without the room such a call keeps all of k in one
+ * workgroup per tile and runs up to twice as long on long-k, few-tile shapes.
+ * (The per-tile counters of that scheme live in a 4 MiB static device array of
+ * the library, handed out in rotation, so that concurrent calls use different
+ * ones; the int32 entry points add their k ranges into C with atomics and need
+ * no slots.)
+ */
+size_t mipgemm_workspace_size_f32(int64_t m, int64_t n, int64_t k,
+                                  int orderA, int orderB, int orderC);
 
 /*
  * Static, human-readable text for a return value of the functions above.  For a

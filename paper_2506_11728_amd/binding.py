@@ -50,7 +50,8 @@ def exported_symbols():
             "mipgemm_s8u8s32_batched", "mipgemm_variant_name_with_workspace",
             "mipgemm_variant_name_for_mode", "mipgemm_set_tuning",
             "mipgemm_conv_workspace_size_unaligned", "mipgemm_mfma_ceiling_clocked",
-            "mipgemm_s8s8s32_clocked", "mipgemm_s8s8s32_noalloc", "mipgemm_static_scratch_bytes"]
+            "mipgemm_s8s8s32_clocked", "mipgemm_s8s8s32_noalloc", "mipgemm_static_scratch_bytes",
+            "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -70,12 +71,15 @@ def load_library() -> ctypes.CDLL:
                 fn = getattr(lib, name)
                 fn.restype = ctypes.c_int
                 fn.argtypes = _GEMM_ARGTYPES
-            for name in ("mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32"):
+            for name in ("mipgemm_s8s8f32", "mipgemm_u8s8f32", "mipgemm_s8u8f32",
+                         "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8"):
                 fn = getattr(lib, name)
                 fn.restype = ctypes.c_int
                 fn.argtypes = _GEMM_ARGTYPES + [ctypes.c_float]
             lib.mipgemm_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_workspace_size.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+            lib.mipgemm_workspace_size_f32.restype = ctypes.c_size_t
+            lib.mipgemm_workspace_size_f32.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
             lib.mipgemm_strerror.restype = ctypes.c_char_p
             lib.mipgemm_strerror.argtypes = [ctypes.c_int]
             for fn in (lib.mipgemm_variant_name, lib.mipgemm_variant_name_with_workspace):
@@ -195,6 +199,27 @@ def mipgemm_s8u8f32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mod
                  mode, workspace, workspace_bytes, stream, check, scale)
 
 
+def mipgemm_s8s8s8(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                   workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """C (int8) = clip(rint(scale * (A * B))): the integer GEMM with the requantising scale fused in."""
+    return _call("mipgemm_s8s8s8", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
+
+
+def mipgemm_u8s8s8(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                   workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """Same with an unsigned A."""
+    return _call("mipgemm_u8s8s8", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
+
+
+def mipgemm_s8u8s8(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                   workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """Same with an unsigned B."""
+    return _call("mipgemm_s8u8s8", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check, scale)
+
+
 def mipgemm_conv_s8u8s32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode,
                          workspace=None, workspace_bytes=0, stream=None, check=True):
     """O = [O +] CONV(F, I) by lowering to the integer GEMM (see include/mipgemm.h)."""
@@ -288,6 +313,10 @@ def mipgemm_pack_b(k, n, B, ldb, orderB, P, ldp, stream=None, check=True):
 
 def mipgemm_workspace_size(m, n, k, orderA, orderB, orderC) -> int:
     return int(load_library().mipgemm_workspace_size(m, n, k, orderA, orderB, orderC))
+
+
+def mipgemm_workspace_size_f32(m, n, k, orderA, orderB, orderC) -> int:
+    return int(load_library().mipgemm_workspace_size_f32(m, n, k, orderA, orderB, orderC))
 
 
 def mipgemm_strerror(code: int) -> str:

@@ -136,10 +136,19 @@ static int64_t tile_count(const Problem &p, Shape s) {
          (p.batch > 1 ? p.batch : 1);
 }
 
+size_t splitk_slot_bytes(const Problem &p, const Plan &plan) {
+  if (plan.kind != KIND_DMA || plan.splits < 2 || !p.out_float) return 0;  // (int32 outputs add into C)
+  const int64_t bm = kShapeRows[plan.shape], bn = kShapeCols[plan.shape];
+  const int64_t tiles = ((p.m + bm - 1) / bm) * ((p.n + bn - 1) / bn) * (p.batch > 1 ? p.batch : 1);
+  const double bytes = (double)tiles * (double)plan.splits * (double)(bm * bn * 4);
+  return bytes < 1.0e15 ? (size_t)bytes : 0;
+}
+
 Plan choose_plan(const Problem &p) {
   const int64_t kComputeUnits = compute_units();
   if (p.m == 0 || p.n == 0) return {KIND_NONE, SHAPE_64, 1};
-  if (p.k == 0) return {p.accumulate ? KIND_NONE : KIND_FILL, SHAPE_64, 1};
+  // (the zero fill writes words; an int8 output of an empty sum goes through the simple kernel)
+  if (p.k == 0) return {p.accumulate ? KIND_NONE : (p.out_float == 2 ? KIND_SIMPLE : KIND_FILL), SHAPE_64, 1};
   Plan plan;
   if (!forced_plan(p, &plan)) {
     // The largest tile that still gives most compute units a workgroup; a
@@ -219,7 +228,10 @@ Plan choose_plan(const Problem &p) {
     // there the slab kernel takes every such problem, whatever k.  Measured, us warm/cold:
     // (16, 2048, 8192) 17.8/29.2 -> 9.7/11.2, with a row-major B 17.7/35.3 -> 10.5/26.6;
     // (1, 4096, 4096) row-major B 10.5/18.5 -> 7.2/14.5.)
-    else if (slab_ok && (short_k || p.out_float) && tile_count(p, SHAPE_64) < kComputeUnits / 2 &&
+    // (With a workspace a float output splits k through slots of partial sums, and then the
+    // tiles win here as they do for an int32 output: (64, 4096, 4096) 15.7 -> 9.4 us,
+    // (16, 4096, 4096) 10.8 -> 9.2 us.)
+    else if (slab_ok && (short_k || (p.out_float && !p.ws)) && tile_count(p, SHAPE_64) < kComputeUnits / 2 &&
              p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
@@ -235,7 +247,10 @@ Plan choose_plan(const Problem &p) {
     else plan = {KIND_STAGED, sh == SHAPE_256 || sh == SHAPE_128 ? (p.a_sk == 1 ? SHAPE_128X64 : SHAPE_64X128) : sh, 1};
   }
   if (plan.kind == KIND_STAGED || plan.kind == KIND_DMA) {
-    plan.splits = p.out_float ? 1 : forced_splits();  // float sums are not combined out of order
+    // float sums are not combined out of order: a float output splits k only through slots of
+    // integer partial sums, which need room in a workspace
+    const bool may_split = !p.out_float || (p.ws != nullptr && plan.kind == KIND_DMA);
+    plan.splits = may_split ? forced_splits() : 1;
     if (plan.splits == 0) {
       // Too few tiles to fill the chip: cut k into ranges of at least 512 (128 for the
       // register-staged kernel) until
@@ -255,7 +270,8 @@ Plan choose_plan(const Problem &p) {
       const int64_t target = short_side <= 16 && small_tile ? 2 * kComputeUnits : kComputeUnits;
       // (an accumulating call needs no zero-fill launch and gains from two ranges already
       // at half a round of tiles: (128, 4096, 4096) 11.2 -> 8.8 us, overwriting 11.0 either way)
-      if ((p.accumulate ? tiles <= target / 2 : tiles < target / 2) && !p.out_float) {
+      // (a float output through slots needs no zeroed C either: it splits as an accumulating call does)
+      if (((p.accumulate || p.out_float) ? tiles <= target / 2 : tiles < target / 2) && may_split) {
         const int64_t want = short_side <= 16 && small_tile ? (target + tiles - 1) / tiles : target / tiles;
         // the register-staged kernel has a shallow pipeline with little to amortise:
         // ranges of two k blocks already pay, and it tolerates twice the atomics
@@ -268,7 +284,7 @@ Plan choose_plan(const Problem &p) {
         // the zero-fill launch of an overwriting call costs more than the ranges of a short k
         // save: (512, 512, 1024) 5.1 us whole, 6.4 us in two ranges (accumulating 5.0 and 4.5);
         // (512, 512, 2048) 6.7 and 7.3, (256, 256, 2048) 6.5 and 6.0, (512, 512, 4096) 10.6 and 8.7
-        if (!p.accumulate && short_side > 64 && p.k < (tiles <= 32 ? 2048 : 3072)) sp = 1;
+        if (!p.accumulate && !p.out_float && short_side > 64 && p.k < (tiles <= 32 ? 2048 : 3072)) sp = 1;
         plan.splits = (int)sp;
       }
     }

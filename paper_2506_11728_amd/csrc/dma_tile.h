@@ -39,7 +39,12 @@ struct DmaTileParams {
   int kt_per_split;       // k blocks per workgroup (blockIdx.y picks the range)
   int accumulate;         // C += instead of C =
   int atomic;             // several workgroups add into the same tile (split k)
-  int out_float;          // dequantised output: float(sum) * scale
+  // split k through partial-sum slots instead (see combine_k_ranges): `splits` slots per tile
+  // in `slots`, one zeroed counter per tile in `tickets`; null = not used
+  int32_t *slots;
+  unsigned *tickets;
+  int splits;
+  int out_float;          // 1 dequantised output: float(sum) * scale; 2 requantised int8 output
   float scale;
   ConvGeom conv;          // CONV kernels only
   int64_t a_sb, b_sb, c_sb;  // byte / element offsets of problem z of a batch (blockIdx.z)
@@ -283,8 +288,21 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   // ---- write-back: unsigned-operand correction, then C = / += / atomic += ----
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // stages are dead from here on
   unsigned_correction<FM, FN>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
+  if (P.slots) {  // only the workgroup that draws the tile's last ticket writes C
+    const int64_t tile = ((int64_t)blockIdx.z * P.tiles_m + tm) * P.tiles_n + tn;
+    if (!combine_k_ranges<FM, FN>(acc, P.slots + tile * P.splits * (int64_t)(BM * BN), blockIdx.y,
+                                  P.splits, P.tickets + tile, wave, lane, tid,
+                                  reinterpret_cast<int *>(smem)))
+      return;
+    __syncthreads();  // the word of LDS the ticket went through is patch memory below
+  }
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < P.m && nw < P.n) {
+    if (P.out_float == 2) {  // int8 output: C is a matrix of bytes
+      store_blocks_q8<FM, FN>(acc, reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw, P.ldc, P.m - mw,
+                              P.n - nw, lane, P.scale);
+      return;
+    }
     int32_t *C = P.C + mw * P.ldc + nw;
     const bool full = m0 + BM <= P.m && n0 + BN <= P.n;
     const Finish fin = {P.scale, P.out_float};
@@ -344,8 +362,27 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   P.accumulate = p.accumulate;
   P.out_float = p.out_float;
   P.scale = p.scale;
-  if (p.out_float) splits = 1;  // float sums must not be combined in arbitrary order
-  P.atomic = splits > 1;
+  const int64_t all_tiles = (int64_t)P.tiles_m * P.tiles_n * (p.batch > 1 ? p.batch : 1);
+  P.slots = nullptr;
+  P.tickets = nullptr;
+  P.splits = splits;
+  // A float output cannot add its k ranges into C (float sums must not be combined in
+  // arbitrary order): given room for one slot of integer partial sums per k range and tile,
+  // the ranges meet there, and the workgroup that comes last converts the complete sum.
+  // (An int32 output keeps the atomics: measured on twelve shapes, slots win where C is
+  // large, 2048^3 in two ranges 22 against 40 us, but there no split wins at all, 15 us;
+  // where splitting pays C is small and the atomics are cheaper, (16, 4096, 4096) in four
+  // ranges 8.3 against 9.1 us, (512, 512, 4096) 10.5 against 17 us.)
+  if (splits > 1 && p.out_float && p.ws &&
+      p.ws_bytes / ((size_t)BM * BN * 4) / (size_t)splits >= (size_t)all_tiles) {
+    unsigned *tickets = nullptr;
+    if (splitk_tickets(all_tiles, &tickets) == hipSuccess) {
+      P.slots = static_cast<int32_t *>(p.ws);
+      P.tickets = tickets;
+    }
+  }
+  if (p.out_float && !P.slots) splits = 1;  // float sums must not be combined in arbitrary order
+  P.atomic = splits > 1 && !P.slots;
   if (P.atomic && !p.accumulate) {
     hipError_t e = launch_fill_zero(p, s);  // partial sums are added into C: start from zero
     if (e != hipSuccess) return e;
@@ -354,10 +391,14 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   P.b_sb = p.b_sb;
   P.c_sb = p.c_sb;
   const int ntiles = P.tiles_m * P.tiles_n;
-  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits, (unsigned)p.batch);
+  if (splits == 1) {  // (a float output that found no room for slots)
+    P.kt_per_split = P.nkt;
+    P.splits = 1;
+  }
   // a workgroup with fewer k blocks than stages never touches the later stages: leave them
   // out, so that more workgroups of a short-k problem fit a compute unit (the write-back
   // patches, one per wave, must still fit)
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits, (unsigned)p.batch);
   const int stages = P.kt_per_split < DMA_STAGES ? P.kt_per_split : DMA_STAGES;
   size_t lds = (size_t)stages * (BM + BN) * BK;
   if (lds < 4 * (size_t)STORE_PATCH_BYTES) lds = 4 * (size_t)STORE_PATCH_BYTES;

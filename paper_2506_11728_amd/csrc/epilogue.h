@@ -22,7 +22,7 @@ struct __attribute__((packed, aligned(4))) c_quad { v4i v; };
 // stores below move bit patterns.
 struct Finish {
   float scale;
-  int to_float;
+  int to_float;  // 0 int32, 1 float; 2 = requantised int8 output, which has write-back loops of its own
   __device__ __forceinline__ int operator()(int acc, int old, bool accumulate) const {
     if (!to_float) return accumulate ? (int)((uint32_t)acc + (uint32_t)old) : acc;
     const float s = (float)acc;
@@ -254,6 +254,129 @@ __device__ __forceinline__ void add_blocks_atomic(const v16i (&acc)[FM][FN], int
       }
     }
   }
+}
+
+// Requantised output (paper Section 7.3, X ~ s_X X^q, applied to the product: the int32 sum
+// brought into the int8 scale of the next layer): Q = clip(rint(scale * S), -128, 127), the
+// sum converted to float (nearest even), one float multiplication, rounding to the nearest
+// integer with ties to even, saturation.  C is a matrix of BYTES here (ldc counts bytes).
+__device__ __forceinline__ int requantise(int sum, float scale) {
+  float r = __builtin_rintf(__fmul_rn((float)sum, scale));
+  r = fminf(fmaxf(r, -128.0f), 127.0f);
+  return (int)r & 0xff;
+}
+
+struct __attribute__((packed, aligned(1))) q8_run { v4i v; };  // 16 output bytes at any address
+
+// The blocks sit transposed in the registers (lane = row of C, four consecutive registers =
+// four consecutive columns): four sums make one packed word, and a lane and its partner 32
+// lanes on, which hold alternate words of the same row, swap two words each so that every
+// lane ends up with 16 consecutive bytes of its row.  One 16-byte store per lane and block;
+// at a ragged edge the bytes go out one by one.
+template <int FM, int FN>
+__device__ __forceinline__ void store_blocks_q8(const v16i (&acc)[FM][FN], int8_t *C, int64_t ldc,
+                                                int64_t rows, int64_t cols, int lane, float scale) {
+  const int h = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = i * 32 + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      int word[4];  // word q: columns 8 q + 4 h .. + 3 of the block
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        word[q] = requantise(acc[i][j][4 * q], scale) | requantise(acc[i][j][4 * q + 1], scale) << 8 |
+                  requantise(acc[i][j][4 * q + 2], scale) << 16 |
+                  requantise(acc[i][j][4 * q + 3], scale) << 24;
+      // the lower half of the wave keeps columns 0..15 (its words 0, 1 and the partner's),
+      // the upper half columns 16..31
+      const int got0 = __shfl_xor(h ? word[0] : word[2], 32);
+      const int got1 = __shfl_xor(h ? word[1] : word[3], 32);
+      const v4i run = h ? v4i{got0, word[2], got1, word[3]} : v4i{word[0], got0, word[1], got1};
+      const int col = j * 32 + 16 * h;
+      if (row >= rows || col >= cols) continue;
+      int8_t *dst = C + row * ldc + col;
+      if (col + 16 <= cols) {
+        reinterpret_cast<q8_run *>(dst)->v = run;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (col + e < cols) dst[e] = (int8_t)(run[e >> 2] >> (8 * (e & 3)));
+      }
+    }
+  }
+}
+
+// Split k without atomics and without a zeroed C: every workgroup of a tile writes its partial
+// sums into its own slot of a caller-supplied buffer (register order: one coalesced 16-byte
+// store per lane), then takes a ticket; the workgroup that draws the last ticket adds the
+// other slots to its own registers and goes on to the ordinary write-back, so that any mode
+// and a float output work as in an unsplit call (the sum is complete, in integers, before
+// anything is converted).  Nobody waits for anybody.  `slots` points at the tile's `splits`
+// slots of 4 * FM * FN * 1024 words; `ticket` at the tile's counter, which is zero on entry
+// and zero again when the last workgroup leaves.  Returns true in the workgroup that holds
+// the complete sums.  Integer addition is associative: the result is the same bits whichever
+// workgroup comes last.
+//
+// Visibility between workgroups, which may run on different XCDs with L2 caches of their
+// own: every slot access carries the device-scope bit (sc1: the store is written through to
+// the level all XCDs share, the load is served from there), a workgroup draws its ticket, a
+// device-scope atomic, only after its stores have been acknowledged (vmcnt 0), and the last
+// workgroup issues its loads only after its ticket has come back.  Device-wide fences, which
+// write back and invalidate a whole L2, are not needed and were measured to cost about
+// 0.1 us per workgroup serialised per XCD (2048^3 in 2 x 2048 workgroups: 350 us).
+__device__ __forceinline__ void store16_device_scope(v4i *p, v4i v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ v4i load16_device_scope(const v4i *p) {
+  v4i v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+  return v;  // in flight: the caller waits with loads_landed before touching it
+}
+// "the loads issued above have landed": ties the registers to the wait, so that nothing that
+// uses them is scheduled before it
+__device__ __forceinline__ void loads_landed(v4i &a, v4i &b, v4i &c, v4i &d) {
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
+}
+
+template <int FM, int FN>
+__device__ __forceinline__ bool combine_k_ranges(v16i (&acc)[FM][FN], int32_t *slots, int range,
+                                                 int splits, unsigned *ticket, int wave, int lane,
+                                                 int tid, int *lds_word) {
+  constexpr int WAVE_WORDS = FM * FN * 1024;
+  constexpr int SLOT_WORDS = 4 * WAVE_WORDS;
+  v4i *mine = reinterpret_cast<v4i *>(slots + (int64_t)range * SLOT_WORDS + wave * WAVE_WORDS) + lane;
+#pragma unroll
+  for (int b = 0; b < FM * FN; ++b)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      store16_device_scope(mine + (b * 4 + q) * 64,
+                           v4i{acc[b / FN][b % FN][4 * q], acc[b / FN][b % FN][4 * q + 1],
+                               acc[b / FN][b % FN][4 * q + 2], acc[b / FN][b % FN][4 * q + 3]});
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the slot has arrived where every XCD reads it
+  __syncthreads();
+  if (tid == 0) *lds_word = atomicAdd(ticket, 1u) == (unsigned)(splits - 1) ? 1 : 0;
+  __syncthreads();
+  if (!*lds_word) return false;
+  for (int r = 0; r < splits; ++r) {
+    if (r == range) continue;
+    const v4i *other =
+        reinterpret_cast<const v4i *>(slots + (int64_t)r * SLOT_WORDS + wave * WAVE_WORDS) + lane;
+#pragma unroll
+    for (int b = 0; b < FM * FN; ++b) {
+      v4i v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = load16_device_scope(other + (b * 4 + q) * 64);
+      loads_landed(v[0], v[1], v[2], v[3]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          acc[b / FN][b % FN][4 * q + e] = (int)((uint32_t)acc[b / FN][b % FN][4 * q + e] + (uint32_t)v[q][e]);
+    }
+  }
+  if (tid == 0) atomicExch(ticket, 0u);  // every range has drawn: the counter is free again
+  return true;
 }
 
 }  // namespace mip

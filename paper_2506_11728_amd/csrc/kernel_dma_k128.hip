@@ -25,7 +25,7 @@ struct DmaParams {
   int tiles_m, tiles_n;
   int nkt;                // k / 128
   int accumulate;         // C += instead of C =
-  int out_float;          // dequantised output: float(sum) * scale
+  int out_float;          // 1 dequantised output: float(sum) * scale; 2 requantised int8 output
   float scale;
   // not null: workgroup w adds the shader clocks and the 10 ns ticks it ran for to
   // clocks[2 w], clocks[2 w + 1] (benchmarks: the clock the device sustained)
@@ -225,6 +225,12 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
   const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;  // the wave's 128 x 128 patch
+  if (P.out_float == 2) {  // int8 output: C is a matrix of bytes
+    if (mw < P.m && nw < P.n)
+      store_blocks_q8<4, 4>(acc, reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw, P.ldc, P.m - mw,
+                            P.n - nw, lane, P.scale);
+    return;
+  }
   if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
     store_blocks_via_lds<4, 4>(acc, P.C + mw * P.ldc + nw, P.ldc, P.accumulate != 0, lane,
                                reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES),

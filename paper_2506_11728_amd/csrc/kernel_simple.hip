@@ -29,6 +29,12 @@ __global__ __launch_bounds__(256) void simple_kernel(Problem p) {
     if (!p.b_unsigned) bv = (uint32_t)(int32_t)(int8_t)bv;
     acc += av * bv;
   }
+  if (p.out_float == 2) {  // requantised int8 output: clip(rint(float(sum) * scale))
+    float r = __builtin_rintf(__fmul_rn((float)(int32_t)acc, p.scale));
+    r = fminf(fmaxf(r, -128.0f), 127.0f);
+    reinterpret_cast<int8_t *>(p.C)[z * p.c_sb + i * p.ldc + j] = (int8_t)(int)r;
+    return;
+  }
   uint32_t *c = reinterpret_cast<uint32_t *>(p.C) + z * p.c_sb + i * p.ldc + j;
   if (!p.out_float) {
     *c = p.accumulate ? *c + acc : acc;
@@ -65,7 +71,8 @@ hipError_t launch_simple(const Problem &p, hipStream_t s) {
     Problem q = p;
     q.m = p.m - i0 < slab ? p.m - i0 : slab;
     q.A = static_cast<const uint8_t *>(p.A) + i0 * p.a_sm;
-    q.C = p.C + i0 * p.ldc;
+    q.C = p.out_float == 2 ? reinterpret_cast<int32_t *>(reinterpret_cast<int8_t *>(p.C) + i0 * p.ldc)
+                           : p.C + i0 * p.ldc;
     dim3 grid = grid_for(q.m, q.n, q.batch);
     hipLaunchKernelGGL(simple_kernel, grid, dim3(256), 0, s, q);
     hipError_t e = hipGetLastError();

@@ -260,6 +260,7 @@ void (*pick(bool b_kc, int uns))(SlabParams) {
 
 bool slab_eligible(const Problem &p, int nt) {
   if (p.conv || p.batch != 1 || p.m < 1 || p.m > 64 || p.a_sk != 1) return false;
+  if (p.out_float == 2) return false;  // (no int8 write-back here)
   if (nt != 1 && nt != 2) return false;
   if (p.n % (16 * nt) || p.k % 64 || p.k < 64) return false;
   if (p.b_sk != 1 && p.b_sn != 1) return false;

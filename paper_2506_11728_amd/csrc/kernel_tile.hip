@@ -167,6 +167,11 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   unsigned_correction<FM, FN>(acc, sumA, sumB, flipA != 0, flipB != 0, lane);
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < p.m && nw < p.n) {
+    if (p.out_float == 2) {  // int8 output: C is a matrix of bytes
+      store_blocks_q8<FM, FN>(acc, reinterpret_cast<int8_t *>(p.C) + mw * p.ldc + nw, p.ldc, p.m - mw,
+                              p.n - nw, lane, p.scale);
+      return;
+    }
     int32_t *C = p.C + mw * p.ldc + nw;
     const Finish fin = {p.scale, p.out_float};
     if (tp.atomic) {

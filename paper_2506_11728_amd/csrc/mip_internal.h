@@ -31,7 +31,8 @@ struct Problem {
   int64_t ldc;
   int a_unsigned, b_unsigned;
   int accumulate;
-  // dequantised output (paper Section 7.3): C holds floats, float(sum) * scale
+  // 1: dequantised output (paper Section 7.3): C holds floats, float(sum) * scale
+  // 2: requantised output: C holds int8 (ldc counts bytes), clip(rint(float(sum) * scale))
   int out_float;
   float scale;
   // batch > 1: that many independent problems of the same shape; problem z reads A + z*a_sb,
@@ -42,6 +43,10 @@ struct Problem {
   // A and B are the library's own packed buffers: k-contiguous, and readable (with whatever
   // contents) up to the next multiple of 256 rows, so that whole tiles may be fetched
   bool rows_padded_to_256 = false;
+  // device memory the kernels may use for the duration of the call (what is left of the
+  // caller's workspace): slots of partial sums for split k (16-byte aligned)
+  void *ws = nullptr;
+  size_t ws_bytes = 0;
   // not null: A is never materialised, the kernel gathers it from the image tensor
   // (only the direct-to-LDS tile kernels can; a_sm is then the nominal row length k)
   const ConvGeom *conv = nullptr;
@@ -123,6 +128,14 @@ hipError_t launch_conv_rows(const Problem &p, hipStream_t s);
 hipError_t launch_pack_pair(int64_t k, int64_t kfill, int64_t m, const uint8_t *A, int64_t lda,
                             bool a_kc, uint8_t *Ap, int64_t n, const uint8_t *B, int64_t ldb,
                             bool b_kc, uint8_t *Bp, int64_t ldp, hipStream_t s);
+
+// `count` zeroed 32-bit counters in device memory that no other call in flight uses: the
+// tickets of split k through partial-sum slots.  The kernels leave them zeroed.
+hipError_t splitk_tickets(int64_t count, unsigned **out);
+
+// Bytes of partial-sum slots the plan's split k wants (0: no split, or a kernel that adds
+// into C with atomics whatever it is given).
+size_t splitk_slot_bytes(const Problem &p, const Plan &plan);
 
 bool dma_eligible(const Problem &p, Shape shape);
 hipError_t launch_dma(const Problem &p, Shape shape, int splits, hipStream_t s);

@@ -117,6 +117,16 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
   if (p.batch == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
+  // what the kernels may use of the workspace: all of it, or what the packed operands leave
+  uint8_t *ws = static_cast<uint8_t *>(workspace);
+  size_t ws_bytes = workspace ? workspace_bytes : 0;
+  if (reinterpret_cast<uintptr_t>(ws) % 16 != 0 && ws_bytes > 0) {  // slots are read 16 bytes at a time
+    const size_t skip = 16 - reinterpret_cast<uintptr_t>(ws) % 16;
+    ws = skip < ws_bytes ? ws + skip : nullptr;
+    ws_bytes = skip < ws_bytes ? ws_bytes - skip : 0;
+  }
+  p.ws = ws_bytes ? ws : nullptr;
+  p.ws_bytes = ws_bytes;
   mip::Plan plan = mip::choose_plan(p);
   if (packing_pays(p, plan) && workspace && workspace_bytes >= packed_bytes(p.m, p.n, p.k)) {
     // Pack A and Pack B (paper Section 4.1) into aligned, k-contiguous buffers with the k
@@ -133,6 +143,11 @@ int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t
     p.B = Bp; p.b_sn = kp; p.b_sk = 1;
     p.k = kp;
     p.rows_padded_to_256 = true;
+    // the packed operands keep the front of the workspace
+    const size_t used = (packed_bytes(p.m, p.n, kp) + 255) / 256 * 256;
+    p.ws = workspace_bytes > used ? static_cast<uint8_t *>(workspace) + used : nullptr;
+    p.ws_bytes = workspace_bytes > used ? workspace_bytes - used : 0;
+    if (p.ws && reinterpret_cast<uintptr_t>(p.ws) % 16 != 0) { p.ws = nullptr; p.ws_bytes = 0; }
     plan = mip::choose_plan(p);
   }
   return static_cast<int>(launch_plan(p, plan, s));
@@ -290,18 +305,85 @@ int mipgemm_s8u8f32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t ld
                  workspace_bytes, stream, scale);
 }
 
-size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k, int orderA, int orderB, int orderC) {
+static size_t recommended_workspace(int64_t m, int64_t n, int64_t k, int orderA, int orderB,
+                                    int orderC, int out_float) {
   // Operands that are 16-byte aligned with k a multiple of 64 go straight from their own
   // storage through LDS into the matrix cores; the others are packed first when that pays.
+  // Either way, a problem with too few tiles for the chip splits k, and the ranges meet in
+  // slots of partial sums when there is room for them.
   if (m < 0 || n < 0 || k < 0 || m > MIPGEMM_MAX_DIM || n > MIPGEMM_MAX_DIM || k > MIPGEMM_MAX_DIM)
     return 0;
   if (!mip::order_ok(orderA) || !mip::order_ok(orderB) || !mip::order_ok(orderC)) return 0;
-  if (!mip::packing_size_ok(m, n, k)) return 0;
+  if (m == 0 || n == 0 || k == 0) return 0;
   // the tightest leading dimensions of these orders, on 16-byte aligned pointers
-  const bool a_ok = (orderA == MIPGEMM_ROW_MAJOR ? k : m) % 16 == 0;
-  const bool b_ok = (orderB == MIPGEMM_ROW_MAJOR ? n : k) % 16 == 0;
-  if (a_ok && b_ok && k % 64 == 0) return 0;
-  return mip::packed_bytes(m, n, k);
+  Problem p;
+  const void *fake = reinterpret_cast<const void *>(uintptr_t(4096));
+  if (validate_and_normalise(0, 0, m, n, k, fake, orderA == MIPGEMM_ROW_MAJOR ? k : m, orderA, fake,
+                             orderB == MIPGEMM_ROW_MAJOR ? n : k, orderB,
+                             reinterpret_cast<int32_t *>(uintptr_t(4096)),
+                             orderC == MIPGEMM_ROW_MAJOR ? n : m, orderC, MIPGEMM_OVERWRITE, nullptr, 0,
+                             &p) != 0)
+    return 0;
+  p.ws = const_cast<void *>(fake);  // "there is a workspace": the plan may count on slots
+  p.ws_bytes = ~size_t(0) / 2;
+  p.out_float = out_float;
+  size_t total = 0;
+  mip::Plan plan = mip::choose_plan(p);
+  if (mip::packing_size_ok(p.m, p.n, p.k) && mip::packing_pays(p, plan)) {
+    total = (mip::packed_bytes(p.m, p.n, p.k) + 255) / 256 * 256;
+    const int64_t kp = mip::padded_k(p.k);
+    p.a_sm = p.b_sn = kp;
+    p.a_sk = p.b_sk = 1;
+    p.k = kp;
+    p.rows_padded_to_256 = true;
+    plan = mip::choose_plan(p);
+  }
+  return total + mip::splitk_slot_bytes(p, plan);
+}
+
+// Requantised int8 output (the paper's quantization scheme, Section 7.3, applied to the
+// product).  Same arguments and numbering as the f32 entry points; overwrite only.
+static int run_q8(int a_unsigned, int b_unsigned, int64_t m, int64_t n, int64_t k, const void *A,
+                  int64_t lda, int orderA, const void *B, int64_t ldb, int orderB, int8_t *C,
+                  int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
+                  void *stream, float scale) {
+  Problem p;
+  int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB, C,
+                                  ldc, orderC, mode, workspace, workspace_bytes, &p);
+  if (rc != 0) return rc;
+  if (mode != MIPGEMM_OVERWRITE) return -13;  // a quantized output has no running sum
+  if (!(scale == scale) || scale - scale != 0.0f) return -17;
+  return mip::run_gemm(a_unsigned, b_unsigned, 2, scale, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc,
+                       orderC, mode, workspace, workspace_bytes, stream);
+}
+
+int mipgemm_s8s8s8(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
+                   const int8_t *B, int64_t ldb, int orderB, int8_t *C, int64_t ldc, int orderC,
+                   int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_q8(0, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                workspace_bytes, stream, scale);
+}
+
+int mipgemm_u8s8s8(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda, int orderA,
+                   const int8_t *B, int64_t ldb, int orderB, int8_t *C, int64_t ldc, int orderC,
+                   int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_q8(1, 0, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                workspace_bytes, stream, scale);
+}
+
+int mipgemm_s8u8s8(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
+                   const uint8_t *B, int64_t ldb, int orderB, int8_t *C, int64_t ldc, int orderC,
+                   int mode, void *workspace, size_t workspace_bytes, void *stream, float scale) {
+  return run_q8(0, 1, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
+                workspace_bytes, stream, scale);
+}
+
+size_t mipgemm_workspace_size(int64_t m, int64_t n, int64_t k, int orderA, int orderB, int orderC) {
+  return recommended_workspace(m, n, k, orderA, orderB, orderC, 0);
+}
+
+size_t mipgemm_workspace_size_f32(int64_t m, int64_t n, int64_t k, int orderA, int orderB, int orderC) {
+  return recommended_workspace(m, n, k, orderA, orderB, orderC, 1);
 }
 
 const char *mipgemm_strerror(int code) {

@@ -119,3 +119,125 @@ def test_dequant_rejects_bad_scale_and_empty_k(gpu):
     want = C0.reshape(3, 4).copy()
     want[:, :3] = 0.0
     assert np.array_equal(dC.cpu().numpy().reshape(3, 4), want)
+
+
+# ---------------------------------------------------------------------------
+# float output with k split over several workgroups per tile: the ranges meet in slots of
+# int32 partial sums in the workspace, the last to arrive converts the complete sum
+# ---------------------------------------------------------------------------
+
+def _check_float(gpu, oracle, case, scale, variant, splits, with_workspace=True, replays=0):
+    import torch
+    ops = W.materialize(case)
+    rng = np.random.default_rng(case.index)
+    C0 = (rng.standard_normal(ops.C.size) * 50).astype(np.float32)
+    pad_mask = W.padding_mask(case.m, case.n, case.orderC, case.ldc)
+    want = oracle.gemm_dequant(case.a_unsigned, case.b_unsigned, case.m, case.n, case.k,
+                               ops.A, case.lda, case.orderA, ops.B, case.ldb, case.orderB,
+                               scale, C0, case.ldc, case.orderC, case.mode)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(C0.copy()).cuda()
+    need = max(gpu.mipgemm_workspace_size_f32(case.m, case.n, case.k, case.orderA, case.orderB,
+                                              case.orderC), 64 << 20) if with_workspace else 0
+    ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda") if need else None
+    fn = getattr(gpu, "mipgemm_" + case.entry.replace("s32", "f32"))
+
+    def call():
+        fn(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb, case.orderB,
+           dC, case.ldc, case.orderC, case.mode, scale=scale, workspace=ws, workspace_bytes=need)
+
+    def verify():
+        torch.cuda.synchronize()
+        raw = dC.cpu().numpy()
+        assert np.array_equal(raw[pad_mask], C0[pad_mask])
+        got = W.extract(raw, case.m, case.n, case.orderC, case.ldc).astype(np.float64)
+        c0 = W.extract(C0, case.m, case.n, case.orderC, case.ldc).astype(np.float64)
+        bound = 2.0 ** -23 * (np.abs(want) + (np.abs(c0) if case.mode == W.ACCUMULATE else 0.0))
+        assert (np.abs(got - want) <= bound).all()
+        if case.mode == W.OVERWRITE:       # bit for bit the two IEEE operations of an unsplit call
+            S = np.rint(want / float(np.float32(scale)))
+            assert np.array_equal(got.astype(np.float32), S.astype(np.float32) * np.float32(scale))
+        if ws is not None:
+            assert (ws[need:].cpu().numpy() == 0x5A).all()          # nothing behind the workspace
+
+    with gpu.tuning(MIPGEMM_VARIANT=None if variant == "auto" else variant, MIPGEMM_SPLITK=splits):
+        if replays == 0:
+            call()
+            verify()
+        else:
+            call()                                               # warm-up outside the capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            dC.copy_(torch.from_numpy(C0))
+            with torch.cuda.graph(graph):
+                call()
+            for _ in range(replays):                             # same counters every replay
+                dC.copy_(torch.from_numpy(C0))
+                torch.cuda.synchronize()
+                graph.replay()
+                verify()
+
+
+def _split_cases():
+    out = []
+    shapes = [(256, 256, 8192), (128, 1024, 4096), (64, 4096, 2048), (200, 136, 1024), (1, 4096, 1024),
+              (512, 512, 4096), (33, 2000, 1536)]
+    for idx, (m, n, k) in enumerate(shapes):
+        uns, mode = idx % 3, (idx // 2) % 2
+        oa, ob, oc = 0 if m % 16 else idx % 2, 0 if n % 16 else (idx // 2) % 2, (idx // 3) % 2
+        out.append(W.Case("deqsplit_%dx%dx%d_u%d_m%d_%d%d%d" % (m, n, k, uns, mode, oa, ob, oc), 8, 100 + idx,
+                          m, n, k, a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob,
+                          orderC=oc, pad=16 * (idx % 2), mode=mode,
+                          a_dist=("uniform", 0, 255) if uns == 1 else ("normal", 24.0),
+                          b_dist=("uniform", 0, 255) if uns == 2 else ("normal", 32.0),
+                          c_dist=("uniform", -1000, 1000), seed=17))
+    return out
+
+
+@pytest.mark.parametrize("variant,splits", [("dma64", 2), ("dma64", 5), ("dma64x128", 3), ("dma128x64", 4),
+                                            ("dma128", 2), ("dma64x256", 7), ("dma256x64", 3),
+                                            ("dma256", 2), ("dma64", 1000), ("auto", None)])
+@pytest.mark.parametrize("case", _split_cases(), ids=lambda c: c.name)
+def test_float_output_with_split_k_through_slots(gpu, oracle, case, variant, splits):
+    _check_float(gpu, oracle, case, 0.0123, variant, splits)
+
+
+def test_float_split_k_is_dispatched_with_a_workspace_and_not_without(gpu, oracle):
+    """A long-k, few-tile float problem: with room for slots the dispatcher splits k (the
+    workspace query says how much room), without it the call still gives the same result."""
+    case = W.Case("deqsplit_auto", 8, 120, 256, 256, 8192, seed=17)
+    assert gpu.mipgemm_workspace_size_f32(case.m, case.n, case.k, 0, 0, 0) > 0
+    assert gpu.mipgemm_workspace_size(case.m, case.n, case.k, 0, 0, 0) == 0    # int32: atomics into C
+    _check_float(gpu, oracle, case, 2.0 ** -9, "auto", None)
+    _check_float(gpu, oracle, case, 2.0 ** -9, "auto", None, with_workspace=False)
+    _check_float(gpu, oracle, case, 2.0 ** -9, "dma64", 4, with_workspace=False)  # no room: one range
+
+
+def test_float_split_k_replays_from_a_hip_graph(gpu, oracle):
+    case = W.Case("deqsplit_graph", 8, 121, 128, 1024, 4096, mode=W.ACCUMULATE, seed=17)
+    _check_float(gpu, oracle, case, 0.004, "dma64", 6, replays=4)
+
+
+def test_float_split_k_on_two_streams_at_once(gpu, oracle):
+    """Two calls in flight at the same time take different ticket counters."""
+    import torch
+    case = W.Case("deqsplit_streams", 8, 122, 256, 512, 4096, seed=17)
+    ops = W.materialize(case)
+    want = oracle.gemm_dequant(False, False, case.m, case.n, case.k, ops.A, case.lda, 0, ops.B, case.ldb, 0,
+                               0.01, None, case.ldc, 0, W.OVERWRITE)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    outs = [torch.zeros(case.m * case.n, dtype=torch.float32, device="cuda") for _ in range(2)]
+    wss = [torch.empty(64 << 20, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+    with gpu.tuning(MIPGEMM_VARIANT="dma64", MIPGEMM_SPLITK=4):
+        for rep in range(20):
+            for s, o, w in zip(streams, outs, wss):
+                gpu.mipgemm_s8s8f32(case.m, case.n, case.k, dA, case.lda, 0, dB, case.ldb, 0, o, case.ldc, 0,
+                                    W.OVERWRITE, scale=0.01, workspace=w, workspace_bytes=w.numel(), stream=s)
+    torch.cuda.synchronize()
+    S = np.rint(want / float(np.float32(0.01)))
+    for o in outs:
+        assert np.array_equal(o.cpu().numpy().reshape(case.m, case.n), S.astype(np.float32) * np.float32(0.01))
