@@ -299,8 +299,14 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < P.m && nw < P.n) {
     if (P.out_float == 2) {  // int8 output: C is a matrix of bytes
-      store_blocks_q8<FM, FN>(acc, reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw, P.ldc, P.m - mw,
-                              P.n - nw, lane, P.scale);
+      int8_t *Q = reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw;
+      if constexpr (FN >= 2) {
+        if (m0 + BM <= P.m && n0 + BN <= P.n) {
+          store_blocks_q8_via_lds<FM, FN>(acc, Q, P.ldc, lane, smem + wave * STORE_PATCH_BYTES, P.scale);
+          return;
+        }
+      }
+      store_blocks_q8<FM, FN>(acc, Q, P.ldc, P.m - mw, P.n - nw, lane, P.scale);
       return;
     }
     int32_t *C = P.C + mw * P.ldc + nw;

@@ -307,6 +307,45 @@ __device__ __forceinline__ void store_blocks_q8(const v16i (&acc)[FM][FN], int8_
   }
 }
 
+// The same for a sub-tile that lies wholly inside the matrix, turned through the wave's LDS
+// patch so that one store instruction writes whole rows of the sub-tile, 32 * FN bytes each
+// (FN = 4: eight full 128-byte lines per instruction, where the direct form above leaves 32
+// bytes in each of 32 lines).  `patch` is this wave's STORE_PATCH_BYTES of LDS; the caller
+// has made sure that no wave still reads operand stages from LDS.
+template <int FM, int FN>
+__device__ __forceinline__ void store_blocks_q8_via_lds(const v16i (&acc)[FM][FN], int8_t *C,
+                                                        int64_t ldc, int lane, uint8_t *patch,
+                                                        float scale) {
+  static_assert(FN >= 2 && FN <= 4, "rows of 64 to 128 bytes");
+  constexpr int PITCH = 32 * FN + 16;          // bytes; 32 rows fit the patch for FN <= 4
+  constexpr int LANES_PER_ROW = 2 * FN;        // 16 bytes each
+  constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
+  const int h = lane >> 5, r = lane & 31;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      int word[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        word[q] = requantise(acc[i][j][4 * q], scale) | requantise(acc[i][j][4 * q + 1], scale) << 8 |
+                  requantise(acc[i][j][4 * q + 2], scale) << 16 |
+                  requantise(acc[i][j][4 * q + 3], scale) << 24;
+      const int got0 = __shfl_xor(h ? word[0] : word[2], 32);
+      const int got1 = __shfl_xor(h ? word[1] : word[3], 32);
+      const v4i run = h ? v4i{got0, word[2], got1, word[3]} : v4i{word[0], got0, word[1], got1};
+      *reinterpret_cast<v4i *>(patch + r * PITCH + j * 32 + 16 * h) = run;
+    }
+    // same wave wrote and reads: LDS operations of a wave complete in order
+#pragma unroll
+    for (int t = 0; t < 32 / ROWS_PER_PASS; ++t) {
+      const int row = t * ROWS_PER_PASS + lane / LANES_PER_ROW, piece = lane % LANES_PER_ROW;
+      const v4i v = *reinterpret_cast<const v4i *>(patch + row * PITCH + piece * 16);
+      reinterpret_cast<q8_run *>(C + (int64_t)(i * 32 + row) * ldc + piece * 16)->v = v;
+    }
+  }
+}
+
 // Split k without atomics and without a zeroed C: every workgroup of a tile writes its partial
 // sums into its own slot of a caller-supplied buffer (register order: one coalesced 16-byte
 // store per lane), then takes a ticket; the workgroup that draws the last ticket adds the

@@ -226,9 +226,11 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
   const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;  // the wave's 128 x 128 patch
   if (P.out_float == 2) {  // int8 output: C is a matrix of bytes
-    if (mw < P.m && nw < P.n)
-      store_blocks_q8<4, 4>(acc, reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw, P.ldc, P.m - mw,
-                            P.n - nw, lane, P.scale);
+    int8_t *Q = reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw;
+    if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
+      store_blocks_q8_via_lds<4, 4>(acc, Q, P.ldc, lane, smem + wave * STORE_PATCH_BYTES, P.scale);
+    else if (mw < P.m && nw < P.n)
+      store_blocks_q8<4, 4>(acc, Q, P.ldc, P.m - mw, P.n - nw, lane, P.scale);
     return;
   }
   if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))

@@ -168,8 +168,15 @@ __global__ __launch_bounds__(NTHREADS) void tile_kernel(TileParams tp) {
   const int64_t mw = m0 + wm * (BM / 2), nw = n0 + wn * (BN / 2);  // the wave's sub-tile
   if (mw < p.m && nw < p.n) {
     if (p.out_float == 2) {  // int8 output: C is a matrix of bytes
-      store_blocks_q8<FM, FN>(acc, reinterpret_cast<int8_t *>(p.C) + mw * p.ldc + nw, p.ldc, p.m - mw,
-                              p.n - nw, lane, p.scale);
+      int8_t *Q = reinterpret_cast<int8_t *>(p.C) + mw * p.ldc + nw;
+      if constexpr (FN >= 2) {
+        if (!edge_tile) {
+          // the k loop ended on a workgroup barrier: no wave still reads the stages
+          store_blocks_q8_via_lds<FM, FN>(acc, Q, p.ldc, lane, smem + wave * STORE_PATCH_BYTES, p.scale);
+          return;
+        }
+      }
+      store_blocks_q8<FM, FN>(acc, Q, p.ldc, p.m - mw, p.n - nw, lane, p.scale);
       return;
     }
     int32_t *C = p.C + mw * p.ldc + nw;

@@ -68,8 +68,33 @@ def oracle_result(oracle, case, ops):
     return _expected[case.name]
 
 
+_ran = {}          # forced variant -> names of the kernels that served it, over the session
+
+
+def kernel_that_runs(M, case, variant):
+    """Name of the kernel the library takes for this case under this forced variant: a variant
+    that cannot serve a case falls back (a direct-to-LDS variant on unaligned operands to the
+    register-staged kernel of the same tile shape, the kernel for large problems and the
+    skinny-m kernel to whatever the dispatcher picks), and a test that believes it covers a
+    kernel has to know which one actually ran."""
+    with VariantEnv(variant):
+        name = M.mipgemm_variant_name_for_mode(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
+                                               case.orderB, case.ldc, case.orderC, case.a_unsigned,
+                                               case.b_unsigned, case.pad % 16 == 0, case.mode)
+    if variant == "simple":
+        assert name == "simple"
+    elif variant.startswith("tile"):
+        assert name == "mfma_" + variant
+    elif variant.startswith("dma") and variant != "dma256k128":
+        assert name in ("mfma_" + variant, "mfma_tile" + variant[3:])
+    _ran.setdefault(variant, set()).add(name)
+    return name
+
+
 def check_case(M, oracle, case, variant, splits=None):
-    print("case", case.name, "variant", variant, "splits", splits, flush=True)
+    if case.m and case.n and case.k:
+        print("case", case.name, "variant", variant, "splits", splits, "kernel",
+              kernel_that_runs(M, case, variant), flush=True)
     ops = W.materialize(case)
     want = oracle_result(oracle, case, ops)
     got = gpu_gemm(M, case, ops.A, ops.B, ops.C, variant, splits)
@@ -97,6 +122,19 @@ def test_small_cases_every_variant(gpu, oracle, case, variant):
 @pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
 def test_large_cases(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
+
+
+def test_every_forced_variant_ran_its_own_kernel_on_some_case():
+    """After the two sweeps above: each direct-to-LDS and each staged variant was served by the
+    kernel of its own name on at least one case (not only by its fall-back)."""
+    assert _ran, "runs after test_small_cases_every_variant and test_large_cases"
+    for variant in VARIANTS:
+        if variant == "auto":
+            continue
+        own = "simple" if variant == "simple" else "mfma_" + variant
+        assert own in _ran.get(variant, set()), (variant, _ran.get(variant))
+    assert "mfma_dma256_k128" in _ran.get("dma256k128", set())
+    assert "mfma_dma256_k128" in _ran.get("auto", set())      # the 4096^3 cases as dispatched
 
 
 SPLIT_CASES = [c for c in W.all_cases() if c.k >= 513 and _ops_count(c) <= 2.5e9]
