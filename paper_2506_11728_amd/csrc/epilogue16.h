@@ -1,0 +1,162 @@
+// Write-back of accumulator blocks produced by v_mfma_i32_16x16x64_i8 (the paper's C_r,
+// Section 4.1: kept in registers over loop L6, stored once after it).
+//
+// The kernel issues the instruction with the B fragment as first operand and the A fragment
+// as second, so each 16 x 16 block comes out transposed in the register file: lane l owns C
+// row (l % 16) of the block and its four registers are columns 4 * (l / 16) .. + 3, four
+// consecutive int32 of one row of C.  A wave's sub-tile is FM x FN such blocks.
+#pragma once
+#include "epilogue.h"
+
+namespace mip {
+
+// Unsigned-operand correction (exact modulo 2^32): what has to be added to every element of
+// block row i (row_corr[i], the same in all four registers) and to the four registers of
+// every block in block column j (col_corr[j]).  sumA[i]: this lane's partial sum over k of
+// row (16 i + l % 16) of the staged A, the four lane groups l / 16 holding four quarters of
+// every 64 k; sumB[j]: the same for column (16 j + l % 16) of B.  The write-back adds them on
+// the way to LDS, so that the accumulators are never all in ordinary registers at once.
+template <int FM, int FN>
+struct Correction16 {
+  int row_corr[FM];
+  v4i col_corr[FN];
+};
+
+template <int FM, int FN>
+__device__ __forceinline__ Correction16<FM, FN> unsigned_correction16(const int (&sumA)[FM],
+                                                                      const int (&sumB)[FN],
+                                                                      bool a_unsigned, bool b_unsigned,
+                                                                      int lane) {
+  Correction16<FM, FN> c;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    c.col_corr[j] = v4i{0, 0, 0, 0};
+    if (a_unsigned) {  // sum_p (a - 128) b + 128 sum_p b: needs B's column sums
+      int total = sumB[j] + __shfl_xor(sumB[j], 16);
+      total += __shfl_xor(total, 32);  // every lane: column l % 16 of block column j
+#pragma unroll
+      for (int v = 0; v < 4; ++v) c.col_corr[j][v] = 128 * __shfl(total, 4 * (lane >> 4) + v);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    c.row_corr[i] = 0;
+    if (b_unsigned) {  // needs A's row sums, which end up in the lanes that own the row
+      int total = sumA[i] + __shfl_xor(sumA[i], 16);
+      total += __shfl_xor(total, 32);
+      c.row_corr[i] = 128 * total;
+    }
+  }
+  return c;
+}
+
+// The wave's patch of LDS for the write-back: 16 rows of 16 * FN words, rows 4 words further
+// apart than their length so that the sixteen lanes of one access never share a bank.
+template <int FN>
+struct Patch16 {
+  static constexpr int PITCH = 16 * FN + 4;  // words
+  static constexpr int WORDS = 16 * PITCH;
+  static constexpr int BYTES = 4 * WORDS;
+};
+
+struct __attribute__((packed, aligned(1))) q8_word { int w; };  // four output bytes at any address
+
+// Write-back of a wave's sub-tile, sixteen rows at a time turned through the wave's LDS patch
+// so that a store instruction covers whole rows of the sub-tile (FN = 8: two rows of 512
+// bytes, four full 128-byte lines each; straight from the registers it would leave 64 bytes in
+// each of 16 lines).  The stores are non-temporal: C is written once and never read by this
+// kernel, and letting it allocate in L2 evicts the operand panels other workgroups stream.
+// MODE bit 0: accumulate (the old word is read), bit 1: float output (the dequantised
+// product of paper Section 7.3), 4: requantised int8 output, C a matrix of bytes and ldc
+// counted in bytes.  FULL: the sub-tile lies wholly inside the matrix; otherwise rows and
+// cols say how much of it does, and stores at the edge go out element by element.
+// C points at the first element of the sub-tile; `patch` is the wave's Patch16<FN>::WORDS of
+// LDS, which no wave still reads as operand stages.
+template <int FM, int FN, int MODE, bool FULL, bool CORRECT>
+__device__ __forceinline__ void store_blocks16_as(const v4i (&acc)[FM][FN], void *Cv, int64_t ldc,
+                                                  int64_t rows, int64_t cols, int lane,
+                                                  int32_t *patch, float scale,
+                                                  const Correction16<FM, FN> &corr) {
+  static_assert(FN == 8 || FN == 4 || FN == 2, "rows of 32 to 128 words");
+  constexpr bool Q8 = MODE == 4;
+  constexpr bool ACCUMULATE = !Q8 && (MODE & 1);
+  constexpr int PITCH = Patch16<FN>::PITCH;
+  constexpr int LANES_PER_ROW = 4 * FN;              // four words each
+  constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;  // FN = 8: 2
+  constexpr int PASSES = 16 / ROWS_PER_PASS;
+  const FinishAs<Q8 ? 0 : MODE> fin{scale};
+  const int r0 = lane / LANES_PER_ROW, c0 = 4 * (lane % LANES_PER_ROW);
+  int32_t *C = static_cast<int32_t *>(Cv);
+  int8_t *Q = static_cast<int8_t *>(Cv);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    if (!FULL && i * 16 >= rows) break;  // wave-uniform
+    // an accumulating call has the old words of these sixteen rows in flight before the turn
+    v4i old[PASSES];
+    if (ACCUMULATE) {
+#pragma unroll
+      for (int t = 0; t < PASSES; ++t) {
+        const int row = i * 16 + t * ROWS_PER_PASS + r0;
+        old[t] = v4i{0, 0, 0, 0};
+        if (FULL || (row < rows && c0 + 3 < cols))
+          old[t] = __builtin_nontemporal_load(reinterpret_cast<const v4i_dword_aligned *>(C + row * ldc + c0));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) =
+          CORRECT ? acc[i][j] + corr.col_corr[j] + corr.row_corr[i] : acc[i][j];
+    // same wave wrote and reads: LDS operations of a wave complete in order
+    v4i val[PASSES];
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t)
+      val[t] = *reinterpret_cast<const v4i *>(patch + (t * ROWS_PER_PASS + r0) * PITCH + c0);
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t) {
+      const int row = i * 16 + t * ROWS_PER_PASS + r0;
+      const bool whole = FULL || (row < rows && c0 + 3 < cols);
+      if (Q8) {
+        const int word = requantise(val[t][0], scale) | requantise(val[t][1], scale) << 8 |
+                         requantise(val[t][2], scale) << 16 | requantise(val[t][3], scale) << 24;
+        int8_t *dst = Q + row * ldc + c0;
+        if (whole) {
+          reinterpret_cast<q8_word *>(dst)->w = word;
+        } else if (row < rows) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (c0 + e < cols) dst[e] = (int8_t)(word >> (8 * e));
+        }
+      } else {
+        int32_t *dst = C + row * ldc + c0;
+        if (whole) {
+          v4i out;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) out[e] = fin(val[t][e], old[t][e]);
+          __builtin_nontemporal_store(out, reinterpret_cast<v4i_dword_aligned *>(dst));
+        } else if (row < rows) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (c0 + e < cols) dst[e] = fin(val[t][e], ACCUMULATE ? dst[e] : 0);
+        }
+      }
+    }
+  }
+}
+
+// out_mode: 0 int32, 1 float, 2 int8 (the Problem's out_float).
+template <int FM, int FN, bool FULL, bool CORRECT>
+__device__ __forceinline__ void store_blocks16(const v4i (&acc)[FM][FN], void *C, int64_t ldc,
+                                               int64_t rows, int64_t cols, bool accumulate,
+                                               int out_mode, int lane, int32_t *patch, float scale,
+                                               const Correction16<FM, FN> &corr) {
+  const int mode = out_mode == 2 ? 4 : ((accumulate ? 1 : 0) | (out_mode == 1 ? 2 : 0));
+  switch (mode) {  // wave-uniform
+    case 0: store_blocks16_as<FM, FN, 0, FULL, CORRECT>(acc, C, ldc, rows, cols, lane, patch, scale, corr); break;
+    case 1: store_blocks16_as<FM, FN, 1, FULL, CORRECT>(acc, C, ldc, rows, cols, lane, patch, scale, corr); break;
+    case 2: store_blocks16_as<FM, FN, 2, FULL, CORRECT>(acc, C, ldc, rows, cols, lane, patch, scale, corr); break;
+    case 3: store_blocks16_as<FM, FN, 3, FULL, CORRECT>(acc, C, ldc, rows, cols, lane, patch, scale, corr); break;
+    default: store_blocks16_as<FM, FN, 4, FULL, CORRECT>(acc, C, ldc, rows, cols, lane, patch, scale, corr); break;
+  }
+}
+
+}  // namespace mip

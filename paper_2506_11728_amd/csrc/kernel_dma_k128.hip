@@ -10,6 +10,7 @@
 // packed operands of the library's own packing step); whole tiles are loaded and
 // multiplied, the write-back stops at the edge of C.
 #include "dma_common.h"
+#include "epilogue16.h"
 
 namespace mip {
 
@@ -37,32 +38,104 @@ struct DmaParams {
 };
 
 // ---------------------------------------------------------------------------
-// 256 x 256 tile, k blocks of 128, two LDS stages for A and three for B: half as many barriers per unit
-// of work as the 64-deep kernel, and every row of a k-contiguous operand is fetched as one full
-// 128-byte line.  A block is four sub-blocks of 32; the barrier that publishes
-// block t+1 sits before the last sub-block of block t, whose fragments are
-// already in registers, so the refill of the stage just read starts there.
+// 256 x 256 tile, k blocks of 128, two LDS stages for A and three for B (160 KB), one wave
+// per SIMD, each on a 128 x 128 sub-tile held as 8 x 8 blocks of v_mfma_i32_16x16x64_i8.
+//
+// Why the 16 x 16 x 64 form and not 32 x 32 x 32, which needs half as many instructions:
+// the device is power-limited on operands with random bits, and with everything in registers
+// the 16 x 16 x 64 form sustains about a fifth more operations per second on such operands
+// (it reads and writes a quarter of the accumulator registers per multiply-accumulate); the
+// LDS traffic is the same, since that depends on the wave's sub-tile only.
+//
+// The matrix instructions are written as inline assembly with the accumulators bound to
+// the accumulation registers: left to the register allocator, 64 four-register accumulators
+// plus two sets of sixteen fragments end up shuffled between the two register files inside
+// the loop.  The compiler therefore does not see them as matrix instructions and inserts no
+// wait states for them: the kernel never reads an accumulator before the loop has ended and
+// two s_nop 15 have passed, and consecutive matrix instructions never share an accumulator.
+//
+// A k block is two sub-blocks of 64; the barrier that publishes block t+1 sits between the
+// two sub-blocks of block t (the fragments of the second are in registers by then), so the A
+// stage just read is refilled from there on, while B, with its third stage, is fetched a
+// whole block earlier.  A wave issues at most one instruction every four clocks and a matrix
+// instruction occupies the pipe for sixteen, so what goes between two matrix instructions
+// has to stay within three instructions: the direct loads are spread one per four matrix
+// instructions over the first half of a sub-block, the fragment reads one per two over the
+// second half, and M0 is set by one scalar add placed before the matrix instruction, which
+// then also is the wait state the load needs.
 // ---------------------------------------------------------------------------
 constexpr int KD2 = 128;
 constexpr int A_STAGE_BYTES = DM * KD2;                // 32 KiB
 constexpr int B_STAGE_BYTES = DN * KD2;                // 32 KiB
 constexpr int A_STAGES = 2;
-// The B blocks have a third stage (160 KB of LDS in all): the loads of B for block t+2 go out
-// a whole block earlier than a second stage would allow, and the barrier of step t lets them
-// fly on.  What must have landed at a barrier was then issued at least one block of matrix
-// instructions before it (with two stages each, the B half had three quarters of a block
-// less, too little for a miss in L2).
 constexpr int B_STAGES = 3;
 constexpr int B_BASE = A_STAGES * A_STAGE_BYTES;
 constexpr int LDS2_BYTES = B_BASE + B_STAGES * B_STAGE_BYTES;  // 160 KiB
 constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
 constexpr int STAGGER_TICKS = 100;                     // 1 us between the rows of an XCD's patch
+constexpr int LOAD_EVERY = 4;    // matrix instructions per direct load, from the first on
+constexpr int READ_FROM = 24;    // first matrix instruction of a sub-block followed by a fragment read
+constexpr int READ_EVERY = 2;
+static_assert(LOAD_EVERY * LOADS2 <= 64 && READ_FROM + (16 + 3) * READ_EVERY <= 64, "slots of one sub-block");
+
+// One 256 x 128 operand block in LDS, laid out for the 16 x 16 x 64 instruction.
+//   KC (k contiguous in memory): 256 rows of 128 bytes; 16-byte chunk c of row r sits at
+//     r*128 + 16*(c ^ kswz(r)).
+//   strided (the index runs contiguously): 128 k-rows of 256 bytes; chunk c of k-row q sits
+//     at q*256 + 16*(c ^ swz(q)).
+// kswz spreads the sixteen rows one ds_read_b128 group touches over all banks; swz does the
+// same for the eight k-rows of one transposing read and, with its lowest bit, lets the lane
+// groups that read k-rows 16 apart take the other half of the banks.
+template <bool KC>
+struct Stage16 {
+  __device__ static __forceinline__ int kswz(int r) { return (r >> 1) & 7; }
+  __device__ static __forceinline__ int swz(int q) { return (2 * (q & 7)) ^ ((q >> 4) & 1); }
+  // chunk handled by this thread in direct load i: (row, chunk) for KC, (k-row, chunk) otherwise
+  __device__ static __forceinline__ void chunk_of(int i, int tid, int &a, int &c) {
+    const int q = tid + NTHREADS * i;
+    if (KC) { a = q >> 3; c = q & 7; } else { a = q >> 4; c = q & 15; }
+  }
+  __device__ static __forceinline__ uint32_t global_offset(int i, int tid, int64_t ld) {
+    int a, c;
+    chunk_of(i, tid, a, c);
+    return (uint32_t)(a * ld + ((c ^ (KC ? kswz(a) : swz(a))) << 4));
+  }
+  // The part of a fragment's LDS address that depends on the lane and on the fragment's first
+  // row (a multiple of 16); sub-block, stage and, for the transposing reads, the second half
+  // of the fragment are constant offsets from it.
+  __device__ static __forceinline__ int lane_base(int row0, int lane) {
+    if (KC) return (row0 + (lane & 15)) * 128;
+    const int s = lane & 15;
+    const int col = row0 + (s & 1) * 8;
+    const int q = (lane >> 4) * 16 + (s >> 1);
+    return q * 256 + (((col >> 4) ^ swz(q)) << 4) + (col & 15);
+  }
+  // Fragment for one operand of the instruction: lane l gets, for row (row0 + l % 16), the 16
+  // bytes k = 64*ks + 16*(l / 16) .. + 15 of the staged block.
+  __device__ static __forceinline__ v4i fragment(const uint8_t *stage, int base, int ks, int lane) {
+    if (KC) {
+      const int c = ks * 4 + (lane >> 4);
+      return *reinterpret_cast<const v4i *>(stage + base + ((c ^ kswz(lane & 15)) << 4));
+    }
+    // ds_read_b64_tr_b8: inside each group of 16 lanes, lane 2t+h supplies the address of
+    // half h of the 16 bytes of k-row t, and lane i receives byte i of k-rows 0..7
+    v4i f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      v2i h = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, stage + base + ks * 16384 + t * 2048));
+      f[2 * t] = h[0];
+      f[2 * t + 1] = h[1];
+    }
+    return f;
+  }
+};
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
 template <bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
-  using SA = Stage<DM, A_KC, KD2>;
-  using SB = Stage<DN, B_KC, KD2>;
+  using SA = Stage16<A_KC>;
+  using SB = Stage16<B_KC>;
+  using std::integral_constant;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -92,13 +165,8 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   uint32_t offA[LOADS2], offB[LOADS2];
 #pragma unroll
   for (int i = 0; i < LOADS2; ++i) {
-    int a, c;
-    SA::chunk_of(i, tid, a, c);
-    offA[i] = A_KC ? (uint32_t)(a * P.lda + ((c ^ SA::kswz(a)) << 4))
-                   : (uint32_t)(a * P.lda + ((c ^ SA::swz(a)) << 4));
-    SB::chunk_of(i, tid, a, c);
-    offB[i] = B_KC ? (uint32_t)(a * P.ldb + ((c ^ SB::kswz(a)) << 4))
-                   : (uint32_t)(a * P.ldb + ((c ^ SB::swz(a)) << 4));
+    offA[i] = SA::global_offset(i, tid, P.lda);
+    offB[i] = SB::global_offset(i, tid, P.ldb);
   }
   const uint8_t *gA = P.A + (A_KC ? m0 * P.lda : m0);
   const uint8_t *gB = P.B + (B_KC ? n0 * P.ldb : n0);
@@ -106,48 +174,54 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   const int64_t stepB = B_KC ? KD2 : KD2 * P.ldb;
 
   const uint32_t lds0 = lds_address(smem) + wave * 1024;
-  // direct load q (0..7) of the next A block / the next B block into the given stage
+  // direct load q (0..7) of an A block / a B block into the given stage (prologue only: in
+  // the loop the loads ride with the matrix instructions)
   auto issue_a = [&](int stage, int q) { dma16(offA[q], gA, lds0 + stage * A_STAGE_BYTES + q * 4096); };
   auto issue_b = [&](int stage, int q) {
     dma16(offB[q], gB, lds0 + B_BASE + stage * B_STAGE_BYTES + q * 4096);
   };
 
-  v16i acc[4][4];
+  v4i acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+    for (int j = 0; j < 8; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
-  int sumA[4] = {0, 0, 0, 0}, sumB[4] = {0, 0, 0, 0};  // k sums of the signed operand
-  v4i fa[2][4], fb[2][4];
-  // unsigned operand: bias its bytes to signed, and sum the other operand over k
-  auto prepare = [&](v4i (&a)[4], v4i (&b)[4]) {
-    if (UNS == 1) {
+  int sumA[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sumB[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // k sums of the signed operand
+  v4i fa[2][8], fb[2][8];
+  int baseA[8], baseB[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] ^= (int)0x80808080u;
+  for (int f = 0; f < 8; ++f) {
+    baseA[f] = SA::lane_base(wm * 128 + f * 16, lane);
+    baseB[f] = SB::lane_base(wn * 128 + f * 16, lane);
+  }
+  // read r (0..15) of a sub-block's sixteen fragments, B's first: the first row of matrix
+  // instructions needs all of B's and one of A's
+  auto read_frag = [&](int sa, int sb, int ks, int r, v4i (&a)[8], v4i (&b)[8]) {
+    if (r < 8) b[r] = SB::fragment(smem + B_BASE + sb * B_STAGE_BYTES, baseB[r], ks, lane);
+    else a[r - 8] = SA::fragment(smem + sa * A_STAGE_BYTES, baseA[r - 8], ks, lane);
+  };
+  // Unsigned operand: bias its bytes to signed and sum the other operand over k.  Done to
+  // fragment r of a set a few matrix instructions after its read was issued and well before
+  // the sub-block that uses the set begins: the matrix instructions are inline assembly, so
+  // nothing inserts the wait states they need after an ordinary instruction has written
+  // one of their operands.
+  auto fix_frag = [&](int r, v4i (&a)[8], v4i (&b)[8]) {
+    if (r < 8) {
+      if (UNS == 2) b[r] ^= (int)0x80808080u;
+      if (UNS == 1) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+        for (int e = 0; e < 4; ++e) sumB[r] = __builtin_amdgcn_sdot4(b[r][e], 0x01010101, sumB[r], false);
+      }
+    } else {
+      if (UNS == 1) a[r - 8] ^= (int)0x80808080u;
+      if (UNS == 2) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          sumB[j] = __builtin_amdgcn_sdot4(b[j][r], 0x01010101, sumB[j], false);
-    }
-    if (UNS == 2) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] ^= (int)0x80808080u;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          sumA[i] = __builtin_amdgcn_sdot4(a[i][r], 0x01010101, sumA[i], false);
+        for (int e = 0; e < 4; ++e) sumA[r - 8] = __builtin_amdgcn_sdot4(a[r - 8][e], 0x01010101, sumA[r - 8], false);
+      }
     }
   };
-  // fragment f (0..3 of A, 4..7 of B) of sub-block ks of the block in stages (sa, sb)
-  auto read_frag = [&](int sa, int sb, int ks, int f, v4i (&a)[4], v4i (&b)[4]) {
-    if (f < 4) a[f] = SA::fragment(smem + sa * A_STAGE_BYTES, wm * 128 + f * 32, ks, lane);
-    else b[f - 4] = SB::fragment(smem + B_BASE + sb * B_STAGE_BYTES, wn * 128 + (f - 4) * 32, ks, lane);
-  };
+  constexpr int FIX_LAG = 3;  // fragment reads between a read and its fix-up
 
   const int nkt = P.nkt;  // k / 128
   // prologue: block 0 whole, published; then A and B of block 1 (B of block 2 follows in step 0)
@@ -159,7 +233,14 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   gB += stepB;
   publish_barrier<0>();
 #pragma unroll
-  for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f, fa[0], fb[0]);
+  for (int r = 0; r < 16; ++r) read_frag(0, 0, 0, r, fa[0], fb[0]);
+  if (UNS != 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) fix_frag(r, fa[0], fb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 7" ::: "memory");  // k = 128: nothing else before the first matrix instruction
+    __builtin_amdgcn_sched_barrier(0);
+  }
   if (nkt > 1) {
 #pragma unroll
     for (int q = 0; q < LOADS2; ++q) issue_a(1, q);
@@ -169,19 +250,38 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     gB += stepB;
   }
 
-  // 16 MFMAs of one sub-block, with up to 8 fragment reads and 8 direct loads between them
-  auto phase = [&](int set, auto reader, auto loader) {
-    prepare(fa[set], fb[set]);
+  // The 64 matrix instructions of one sub-block on fragment set `set`, row by row of the 8 x 8
+  // blocks, odd rows backwards so that only one operand changes from one instruction to the
+  // next.  LOAD: eight of them carry one direct load each, into the stage at LDS address
+  // `ldsbase` from gbase + off[q].
+  auto phase = [&](int set, auto reader, auto fixer, auto load_tag, uint32_t ldsbase,
+                   const uint32_t (&off)[LOADS2], const uint8_t *gbase) {
+    constexpr bool LOAD = decltype(load_tag)::value;
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      acc[s >> 2][s & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-          fb[set][s & 3], fa[set][s >> 2], acc[s >> 2][s & 3], 0, 0, 0);
-      if (s < 8) reader(s);
-      else loader(s - 8);
+    for (int s = 0; s < 64; ++s) {
+      const int i = s >> 3, j = (i & 1) ? 7 - (s & 7) : (s & 7);
+      if (LOAD && s % LOAD_EVERY == 0 && s / LOAD_EVERY < LOADS2) {
+        asm volatile(
+            "s_add_u32 m0, %3, %4\n\t"
+            "v_mfma_i32_16x16x64_i8 %0, %1, %2, %0\n\t"
+            "global_load_lds_dwordx4 %5, %6"
+            : "+a"(acc[i][j])
+            : "v"(fb[set][j]), "v"(fa[set][i]), "s"(ldsbase), "i"((s / LOAD_EVERY) * 4096),
+              "v"(off[s / LOAD_EVERY]), "s"(gbase)
+            : "scc");
+      } else {
+        asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0"
+                     : "+a"(acc[i][j])
+                     : "v"(fb[set][j]), "v"(fa[set][i]));
+      }
+      if (s >= READ_FROM && (s - READ_FROM) % READ_EVERY == 0) {
+        const int r = (s - READ_FROM) / READ_EVERY;
+        if (r < 16) reader(r);
+        if (UNS != 0 && r >= FIX_LAG && r - FIX_LAG < 16) fixer(r - FIX_LAG);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto nothing = [](int) {};
 
   // Step t multiplies block t (A in stage t % 2, B in stage t % 3 = bcur).  On entry A and B
   // of block t+1 are on their way.  NEXT: block t+1 exists.  NEXT2: block t+2 exists.
@@ -192,24 +292,22 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     const int cur = t & 1, oth = cur ^ 1;
     const int bnext = bcur == B_STAGES - 1 ? 0 : bcur + 1;
     const int bfill = bnext == B_STAGES - 1 ? 0 : bnext + 1;  // held block t-1: free since the last barrier
-    // sub-block 0; fetch sub-block 1; B of block t+2
-    phase(0, [&](int f) { read_frag(cur, bcur, 1, f, fa[1], fb[1]); },
-          [&](int q) { if (NEXT2) issue_b(bfill, q); });
+    // first sub-block; fetch the second; B of block t+2
+    phase(0, [&](int r) { read_frag(cur, bcur, 1, r, fa[1], fb[1]); },
+          [&](int r) { fix_frag(r, fa[1], fb[1]); }, integral_constant<bool, NEXT2>{},
+          lds0 + B_BASE + bfill * B_STAGE_BYTES, offB, gB);
     if (NEXT2) gB += stepB;
-    phase(1, [&](int f) { read_frag(cur, bcur, 2, f, fa[0], fb[0]); }, nothing);
-    phase(0, [&](int f) { read_frag(cur, bcur, 3, f, fa[1], fb[1]); }, nothing);
     // block t+1 visible (only the B loads of block t+2 may still fly); the A stage of block t
     // may be refilled
     if (NEXT) {
       if (NEXT2) publish_barrier<LOADS2>();
       else publish_barrier<0>();
     }
-    phase(1, [&](int f) { if (NEXT) read_frag(oth, bnext, 0, f, fa[0], fb[0]); },
-          [&](int q) { if (NEXT2) issue_a(cur, q); });
+    phase(1, [&](int r) { if (NEXT) read_frag(oth, bnext, 0, r, fa[0], fb[0]); },
+          [&](int r) { if (NEXT) fix_frag(r, fa[0], fb[0]); }, integral_constant<bool, NEXT2>{}, lds0 + cur * A_STAGE_BYTES, offA, gA);
     if (NEXT2) gA += stepA;
     bcur = bnext;
   };
-  using std::integral_constant;
   using T = integral_constant<bool, true>;
   using F = integral_constant<bool, false>;
   int t = 0;
@@ -221,25 +319,22 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     P.clocks[2 * blockIdx.x] += __builtin_readcyclecounter() - clock0;
     P.clocks[2 * blockIdx.x + 1] += wall_clock64() - tick0;
   }
-  // the last step has no barrier of its own: wait until no wave reads the stages any more
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  unsigned_correction<4, 4>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
+  // The last matrix instructions have to leave the pipe before an accumulator is read (the
+  // compiler does not know that the statements above write them late); the last step has no
+  // barrier of its own: wait until no wave reads the stages any more.
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  const Correction16<8, 8> corr = unsigned_correction16<8, 8>(sumA, sumB, UNS == 1, UNS == 2, lane);
   const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;  // the wave's 128 x 128 patch
-  if (P.out_float == 2) {  // int8 output: C is a matrix of bytes
-    int8_t *Q = reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw;
-    if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
-      store_blocks_q8_via_lds<4, 4>(acc, Q, P.ldc, lane, smem + wave * STORE_PATCH_BYTES, P.scale);
-    else if (mw < P.m && nw < P.n)
-      store_blocks_q8<4, 4>(acc, Q, P.ldc, P.m - mw, P.n - nw, lane, P.scale);
-    return;
-  }
+  int32_t *patch = reinterpret_cast<int32_t *>(smem) + wave * Patch16<8>::WORDS;
+  // an int8 output is a matrix of bytes, ldc counted in bytes
+  void *C = P.out_float == 2 ? static_cast<void *>(reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw)
+                             : static_cast<void *>(P.C + mw * P.ldc + nw);
   if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
-    store_blocks_via_lds<4, 4>(acc, P.C + mw * P.ldc + nw, P.ldc, P.accumulate != 0, lane,
-                               reinterpret_cast<int32_t *>(smem + wave * STORE_PATCH_BYTES),
-                               Finish{P.scale, P.out_float});
+    store_blocks16<8, 8, true, UNS != 0>(acc, C, P.ldc, 128, 128, P.accumulate != 0, P.out_float, lane, patch,
+                                         P.scale, corr);
   else if (mw < P.m && nw < P.n)
-    store_blocks<4, 4, false>(acc, P.C + mw * P.ldc + nw, P.ldc, P.m - mw, P.n - nw,
-                              P.accumulate != 0, lane, Finish{P.scale, P.out_float});
+    store_blocks16<8, 8, false, UNS != 0>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate != 0, P.out_float,
+                                          lane, patch, P.scale, corr);
 }
 
 }  // namespace
