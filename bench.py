@@ -88,8 +88,7 @@ def cpu_baseline(case: W.Case, ops: W.Operands, rows: int):
     }, C
 
 
-KERNEL_SOURCES = ("dma_common.h", "dma_tile.h", "epilogue.h", "lds_layout.h",
-                  "kernel_dma_k128.hip", "kernel_dma_256x256.hip")
+KERNEL_SOURCES = ("dma_common.h", "epilogue.h", "epilogue16.h", "lds_layout.h", "kernel_dma_k128.hip")
 
 
 def kernel_fingerprint() -> str:
@@ -658,8 +657,11 @@ def main():
         # of matrix work) also bring the device out of its idle clocks, which the first tens
         # of milliseconds of any load otherwise run at (profiles/launch_timeline_*.txt).
         ceiling = {"unit": "TOPS"}
+        # (keys without a suffix: v_mfma_i32_32x32x32_i8; "_16x16x64": the instruction the
+        # kernel for large problems is built on)
         for key, pattern in (("near_zero_operands", 0), ("random_operands_rotated_by_valu", 1),
-                             ("random_operands_two_sets", 2), ("random_operands_six_sets", 3)):
+                             ("random_operands_two_sets", 2), ("random_operands_six_sets", 3),
+                             ("near_zero_operands_16x16x64", 4), ("random_operands_16x16x64", 5)):
             tops_p, mhz_p = M.mipgemm_mfma_ceiling_clocked(pattern, 20000)
             ceiling[key] = tops_p
             ceiling[key + "_shader_mhz"] = mhz_p
@@ -726,7 +728,8 @@ def main():
     }
 
     if ceiling is not None:
-        best_random = max(ceiling["random_operands_two_sets"], ceiling["random_operands_six_sets"])
+        best_random = max(ceiling["random_operands_two_sets"], ceiling["random_operands_six_sets"],
+                          ceiling["random_operands_16x16x64"])
         ceiling["kernel_frac_of_random_ceiling"] = kernel_tops / best_random
         out["mfma_only_ceiling"] = ceiling
 

@@ -510,7 +510,10 @@ int mipgemm_mfma_ceiling(int pattern, int iterations, void *stream, double *tops
  * rotated in registers between iterations, which puts 128 register moves between
  * the 32 matrix instructions of an iteration.  pattern 2: random bytes in two fixed
  * operand sets used in turn; pattern 3: random bytes in six fixed operand sets used
- * in turn; in both the loop holds nothing but matrix instructions.
+ * in turn; in both the loop holds nothing but matrix instructions.  Patterns 0 to 3
+ * run v_mfma_i32_32x32x32_i8; pattern 4 (near-zero constants) and pattern 5 (random
+ * bytes, one fixed operand set) run v_mfma_i32_16x16x64_i8, the instruction of the
+ * kernel for large problems, on the same 128 x 128 block per wave.
  */
 int mipgemm_mfma_ceiling_clocked(int pattern, int iterations, void *stream,
                                  double *tops, double *shader_mhz);

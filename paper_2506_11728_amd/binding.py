@@ -382,7 +382,7 @@ def mipgemm_mfma_ceiling(pattern: int, iterations: int = 20000, stream=None) -> 
 
 
 def mipgemm_mfma_ceiling_clocked(pattern: int, iterations: int = 20000, stream=None):
-    """(TOPS, shader MHz) of the register-resident int8 MFMA loop; patterns 0..3 as in the header."""
+    """(TOPS, shader MHz) of the register-resident int8 MFMA loop; patterns 0..5 as in the header."""
     tops, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
     rc = load_library().mipgemm_mfma_ceiling_clocked(pattern, iterations, _stream(stream),
                                                      ctypes.byref(tops), ctypes.byref(mhz))

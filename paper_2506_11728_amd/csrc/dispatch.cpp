@@ -53,13 +53,14 @@ const char *plan_name(const Plan &plan) {
     case KIND_SIMPLE: return "simple";
     case KIND_STAGED: return staged[plan.shape];
     case KIND_DMA: return dma[plan.shape];
-    case KIND_DMA_K128: return "mfma_dma256_k128";
+    case KIND_DMA_K128: return plan.shape == SHAPE_128 ? "mfma_dma128_k128" : "mfma_dma256_k128";
     case KIND_SLAB: return plan.splits == 2 ? "mfma_slab32" : "mfma_slab16";
     default: return "?";
   }
 }
 
 // The tuning value MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
+// "dma128k128" (the same kernel on 128 x 128 tiles),
 // "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
 // 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
@@ -72,6 +73,11 @@ static bool forced_plan(const Problem &p, Plan *plan) {
   if (!std::strcmp(e, "dma256k128")) {
     if (!dma_k128_eligible(p)) return false;
     *plan = {KIND_DMA_K128, SHAPE_256, 1};
+    return true;
+  }
+  if (!std::strcmp(e, "dma128k128")) {
+    if (!dma_k128_eligible(p, true)) return false;
+    *plan = {KIND_DMA_K128, SHAPE_128, 1};
     return true;
   }
   if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32")) {
@@ -160,6 +166,9 @@ Plan choose_plan(const Problem &p) {
     // cache lines of a row-major operand) win as soon as k is long enough to cut
     // into one range of 8 blocks or more per compute unit.
     Shape sh;
+    const Shape rect = (!p.conv && p.b_sn == 1 && p.a_sk == 1)   ? SHAPE_64X128
+                       : (!p.conv && p.a_sm == 1 && p.b_sk == 1) ? SHAPE_128X64
+                                                                 : (p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128);
     const int64_t ranges = p.k / 512 > 1 ? p.k / 512 : 1;
     auto enough = [&](Shape wide, int64_t short_side) {
       const int64_t t = tile_count(p, wide);
@@ -168,7 +177,17 @@ Plan choose_plan(const Problem &p) {
     // (With k under 512 a workgroup holds one to eight k blocks; 64 x 64 tiles then need
     // little LDS, many fit a compute unit, and they overtake the wide tiles:
     // (64, 100352, 64) 10.9 -> 9.4 us, (64, 100352, 256) 12.4 -> 11.7 us.)
-    if (p.m <= 64 && p.n > 128) sh = p.k >= 512 && enough(SHAPE_64X256, p.m) ? SHAPE_64X256 : SHAPE_64;
+    // (From 32 rows on, a weight matrix that does not fit the L2 caches streams better through
+    // 64 x 128 tiles, whole 128-byte lines of a row-major B, than through 64 x 64 ones; measured
+    // cold, us: (32, 11008, 4096) 18.9 -> 16.5, (64, 11008, 4096) 20.7 -> 18.7, (32, 4096, 11008)
+    // 18.9 -> 15.3, (64, 4096, 11008) 21.5 -> 18.9; warm within 0.5 us either way; at
+    // (64, 4096, 4096) the 64 x 64 tiles stay ahead, 11.6 against 12.7.)
+    if (p.m <= 64 && p.n > 128)
+      sh = p.k >= 512 && enough(SHAPE_64X256, p.m)
+               ? SHAPE_64X256
+               : (p.m >= 32 && p.k >= 512 && p.n * p.k >= ((int64_t)32 << 20) && dma_eligible(p, SHAPE_64X128)
+                      ? SHAPE_64X128
+                      : SHAPE_64);
     else if (p.n <= 64 && p.m > 128) sh = p.k >= 512 && enough(SHAPE_256X64, p.n) ? SHAPE_256X64 : SHAPE_64;
     // A large tile buys operand reuse, which only a long k turns into time: with a short
     // k the problem is a stream that ends in the write of C, and small tiles, several
@@ -183,10 +202,20 @@ Plan choose_plan(const Problem &p) {
     else if (p.k >= 1024 && tile_count(p, SHAPE_256) >= 192 &&
              !(tile_count(p, SHAPE_256) > kComputeUnits && tile_count(p, SHAPE_256) <= 320))
       sh = SHAPE_256;
-    else if (p.k >= 512 && tile_count(p, SHAPE_128) >= kComputeUnits) sh = SHAPE_128;
-    else if (p.k >= 512 && tile_count(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128) >= kComputeUnits &&
-             dma_eligible(p, p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128))
-      sh = p.m >= p.n ? SHAPE_128X64 : SHAPE_64X128;  // (measured on the direct-to-LDS kernels only)
+    // (128 x 128 tiles from three quarters of a round on: measured cold against the
+    // 8192-element tiles, us: (128, 25088, 1152) 15.2 -> 12.6, (256, 12544, 1152) 14.8 -> 11.2,
+    // (768, 4096, 2048) 17.9 -> 13.1, (1024, 3072, 3072) 26.6 -> 23.4, (1024, 3072, 768) 8.2 -> 7.9.)
+    else if (p.k >= 512 && !p.conv && tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
+    // (The long side of an 8192-element tile goes along a row-major B, whose rows it then
+    // fetches in whole 128-byte lines, or down a column-major A; with both operands
+    // k-contiguous or both strided, along the longer dimension of C.  (3072, 1024, 768)
+    // row-major: 128 x 64 8.9 us cold, 64 x 128 8.0; (6272, 256, 2304) 15.4 and 13.0.  They
+    // serve from three quarters of a round of tiles on: (256, 6272, 2304) 19.9 us on 64 x 64
+    // tiles, 13.3 on 196 tiles of 64 x 128.)
+    // (A gathered convolution keeps the order it was measured with: 8192-element tiles from a
+    // whole round on, long side along the longer dimension, then 128 x 128 tiles.)
+    else if (p.k >= 512 && tile_count(p, rect) >= (p.conv ? kComputeUnits : 192) && dma_eligible(p, rect))
+      sh = rect;  // (measured on the direct-to-LDS kernels only)
     else if (p.k >= 512 && tile_count(p, SHAPE_128) >= 192) sh = SHAPE_128;
     else sh = SHAPE_64;
     // deep k blocks pay off once the k loop is long enough to amortise their prologue
@@ -235,6 +264,11 @@ Plan choose_plan(const Problem &p) {
              p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
+    // (the same kernel on 128 x 128 tiles, where that is the shape and m, n, k are whole tiles
+    // and blocks: 5 to 15 % over the 64-deep kernel of that shape; measured warm/cold, us:
+    // 2048^3 14.6/15.1 -> 13.0/14.1, (1024, 3072, 3072) 17.1/23.2 -> 15.6/20.2,
+    // (768, 4096, 2048) 12.3/12.9 -> 10.8/12.3, (256, 12544, 1152) 9.1/11.2 -> 8.3/10.4)
+    else if (sh == SHAPE_128 && p.k >= 512 && dma_k128_eligible(p, true)) plan = {KIND_DMA_K128, sh, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
     // the register-staged kernel keeps its operands in flight in VGPRs, which a
     // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128

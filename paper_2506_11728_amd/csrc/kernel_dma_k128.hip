@@ -16,7 +16,7 @@ namespace mip {
 
 namespace {
 
-constexpr int DM = 256, DN = 256;  // workgroup tile
+constexpr int DM = 256, DN = 256;  // workgroup tile of the kernel for large problems (a 128 x 128 form serves mid-size ones)
 
 struct DmaParams {
   const uint8_t *A, *B;
@@ -65,35 +65,49 @@ struct DmaParams {
 // then also is the wait state the load needs.
 // ---------------------------------------------------------------------------
 constexpr int KD2 = 128;
-constexpr int A_STAGE_BYTES = DM * KD2;                // 32 KiB
-constexpr int B_STAGE_BYTES = DN * KD2;                // 32 KiB
 constexpr int A_STAGES = 2;
 constexpr int B_STAGES = 3;
-constexpr int B_BASE = A_STAGES * A_STAGE_BYTES;
-constexpr int LDS2_BYTES = B_BASE + B_STAGES * B_STAGE_BYTES;  // 160 KiB
-constexpr int LOADS2 = DM * KD2 / 16 / NTHREADS;       // 8 per operand per thread per block
 constexpr int STAGGER_TICKS = 100;                     // 1 us between the rows of an XCD's patch
-constexpr int LOAD_EVERY = 4;    // matrix instructions per direct load, from the first on
-constexpr int READ_FROM = 24;    // first matrix instruction of a sub-block followed by a fragment read
-constexpr int READ_EVERY = 2;
-static_assert(LOAD_EVERY * LOADS2 <= 64 && READ_FROM + (16 + 3) * READ_EVERY <= 64, "slots of one sub-block");
+constexpr int FIX_LAG = 3;  // fragment reads between a read and its fix-up (unsigned operands)
 
-// One 256 x 128 operand block in LDS, laid out for the 16 x 16 x 64 instruction.
-//   KC (k contiguous in memory): 256 rows of 128 bytes; 16-byte chunk c of row r sits at
+// Sizes and instruction slots of one tile shape (BM x BN, the four waves 2 x 2 over it).
+template <int BM, int BN>
+struct Tile16 {
+  static constexpr int FM = BM / 32, FN = BN / 32;       // 16 x 16 blocks of a wave's sub-tile
+  static constexpr int NMFMA = FM * FN;                   // matrix instructions per sub-block of 64
+  static constexpr int NREADS = FM + FN;                  // fragment reads per sub-block
+  static constexpr int A_STAGE_BYTES = BM * KD2, B_STAGE_BYTES = BN * KD2;
+  static constexpr int B_BASE = A_STAGES * A_STAGE_BYTES;
+  static constexpr int LDS_BYTES = B_BASE + B_STAGES * B_STAGE_BYTES;  // 256 x 256: 160 KiB
+  static constexpr int LOADS_A = BM * KD2 / 16 / NTHREADS, LOADS_B = BN * KD2 / 16 / NTHREADS;  // per thread and block
+  static constexpr int LOADS_MAX = LOADS_A > LOADS_B ? LOADS_A : LOADS_B;
+  // matrix instructions per direct load, from the first of a sub-block on (256 x 256: 4)
+  static constexpr int LOAD_EVERY = NMFMA / (2 * LOADS_MAX) > 0 ? NMFMA / (2 * LOADS_MAX) : 1;
+  // first matrix instruction of a sub-block that is followed by a fragment read, and their spacing
+  static constexpr int READ_EVERY = NMFMA >= 64 ? 2 : 1;
+  static constexpr int READ_FROM = NMFMA >= 64 ? 24 : NMFMA - (NREADS + FIX_LAG) - 1;
+  static_assert(LOAD_EVERY * LOADS_MAX <= NMFMA && READ_FROM >= 0 &&
+                READ_FROM + (NREADS + FIX_LAG) * READ_EVERY <= NMFMA, "slots of one sub-block");
+};
+
+// One R x 128 operand block in LDS (R = 256 or 128), laid out for the 16 x 16 x 64 instruction.
+//   KC (k contiguous in memory): R rows of 128 bytes; 16-byte chunk c of row r sits at
 //     r*128 + 16*(c ^ kswz(r)).
-//   strided (the index runs contiguously): 128 k-rows of 256 bytes; chunk c of k-row q sits
-//     at q*256 + 16*(c ^ swz(q)).
+//   strided (the index runs contiguously): 128 k-rows of R bytes; chunk c of k-row q sits
+//     at q*R + 16*(c ^ swz(q)).
 // kswz spreads the sixteen rows one ds_read_b128 group touches over all banks; swz does the
 // same for the eight k-rows of one transposing read and, with its lowest bit, lets the lane
 // groups that read k-rows 16 apart take the other half of the banks.
-template <bool KC>
+template <int R, bool KC>
 struct Stage16 {
+  static constexpr int ROW_CHUNKS = R / 16;  // strided: chunks per k-row
   __device__ static __forceinline__ int kswz(int r) { return (r >> 1) & 7; }
-  __device__ static __forceinline__ int swz(int q) { return (2 * (q & 7)) ^ ((q >> 4) & 1); }
+  // (k-rows 256 bytes apart share banks: R = 256 every row, R = 128 every other one)
+  __device__ static __forceinline__ int swz(int q) { return (2 * ((q / (256 / R)) % (R / 32))) ^ ((q >> 4) & 1); }
   // chunk handled by this thread in direct load i: (row, chunk) for KC, (k-row, chunk) otherwise
   __device__ static __forceinline__ void chunk_of(int i, int tid, int &a, int &c) {
     const int q = tid + NTHREADS * i;
-    if (KC) { a = q >> 3; c = q & 7; } else { a = q >> 4; c = q & 15; }
+    if (KC) { a = q >> 3; c = q & 7; } else { a = q / ROW_CHUNKS; c = q % ROW_CHUNKS; }
   }
   __device__ static __forceinline__ uint32_t global_offset(int i, int tid, int64_t ld) {
     int a, c;
@@ -108,7 +122,7 @@ struct Stage16 {
     const int s = lane & 15;
     const int col = row0 + (s & 1) * 8;
     const int q = (lane >> 4) * 16 + (s >> 1);
-    return q * 256 + (((col >> 4) ^ swz(q)) << 4) + (col & 15);
+    return q * R + (((col >> 4) ^ swz(q)) << 4) + (col & 15);
   }
   // Fragment for one operand of the instruction: lane l gets, for row (row0 + l % 16), the 16
   // bytes k = 64*ks + 16*(l / 16) .. + 15 of the staged block.
@@ -122,7 +136,7 @@ struct Stage16 {
     v4i f;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      v2i h = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, stage + base + ks * 16384 + t * 2048));
+      v2i h = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, stage + base + ks * (64 * R) + t * (8 * R)));
       f[2 * t] = h[0];
       f[2 * t + 1] = h[1];
     }
@@ -131,10 +145,15 @@ struct Stage16 {
 };
 
 // UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
-template <bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
+template <int BM, int BN, bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
-  using SA = Stage16<A_KC>;
-  using SB = Stage16<B_KC>;
+  using TS = Tile16<BM, BN>;
+  using SA = Stage16<BM, A_KC>;
+  using SB = Stage16<BN, B_KC>;
+  constexpr int FM = TS::FM, FN = TS::FN, NMFMA = TS::NMFMA, NREADS = TS::NREADS;
+  constexpr int A_STAGE_BYTES = TS::A_STAGE_BYTES, B_STAGE_BYTES = TS::B_STAGE_BYTES, B_BASE = TS::B_BASE;
+  constexpr int LOADS_A = TS::LOADS_A, LOADS_B = TS::LOADS_B, LOADS_MAX = TS::LOADS_MAX;
+  constexpr int WM = BM / 2, WN = BN / 2;  // a wave's sub-tile
   using std::integral_constant;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -144,7 +163,7 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
 
   int tm, tn;
   if (!tile_of_workgroup(P.tiles_m, P.tiles_n, &tm, &tn)) return;
-  const int64_t m0 = (int64_t)tm * DM, n0 = (int64_t)tn * DN;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
   // With several rounds of tiles all compute units would reach their write-backs at the
   // same moments, round after round, and the 32 of one XCD share one path to memory: a tile's
   // stores take about 7 us then, against 3.5 us when only four compute units of an XCD store
@@ -162,11 +181,11 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     tick0 = wall_clock64();
   }
 
-  uint32_t offA[LOADS2], offB[LOADS2];
+  uint32_t offA[LOADS_MAX], offB[LOADS_MAX];  // (entries past an operand's own count stay unused)
 #pragma unroll
-  for (int i = 0; i < LOADS2; ++i) {
-    offA[i] = SA::global_offset(i, tid, P.lda);
-    offB[i] = SB::global_offset(i, tid, P.ldb);
+  for (int i = 0; i < LOADS_MAX; ++i) {
+    offA[i] = i < LOADS_A ? SA::global_offset(i, tid, P.lda) : 0;
+    offB[i] = i < LOADS_B ? SB::global_offset(i, tid, P.ldb) : 0;
   }
   const uint8_t *gA = P.A + (A_KC ? m0 * P.lda : m0);
   const uint8_t *gB = P.B + (B_KC ? n0 * P.ldb : n0);
@@ -181,86 +200,90 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     dma16(offB[q], gB, lds0 + B_BASE + stage * B_STAGE_BYTES + q * 4096);
   };
 
-  v4i acc[8][8];
+  v4i acc[FM][FN];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+    for (int j = 0; j < FN; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
-  int sumA[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sumB[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // k sums of the signed operand
-  v4i fa[2][8], fb[2][8];
-  int baseA[8], baseB[8];
+  int sumA[FM], sumB[FN];  // k sums of the signed operand
+  v4i fa[2][FM], fb[2][FN];
+  int baseA[FM], baseB[FN];
 #pragma unroll
-  for (int f = 0; f < 8; ++f) {
-    baseA[f] = SA::lane_base(wm * 128 + f * 16, lane);
-    baseB[f] = SB::lane_base(wn * 128 + f * 16, lane);
+  for (int f = 0; f < FM; ++f) {
+    sumA[f] = 0;
+    baseA[f] = SA::lane_base(wm * WM + f * 16, lane);
   }
-  // read r (0..15) of a sub-block's sixteen fragments, B's first: the first row of matrix
+#pragma unroll
+  for (int f = 0; f < FN; ++f) {
+    sumB[f] = 0;
+    baseB[f] = SB::lane_base(wn * WN + f * 16, lane);
+  }
+  // read r of a sub-block's FN + FM fragments, B's first: the first row of matrix
   // instructions needs all of B's and one of A's
-  auto read_frag = [&](int sa, int sb, int ks, int r, v4i (&a)[8], v4i (&b)[8]) {
-    if (r < 8) b[r] = SB::fragment(smem + B_BASE + sb * B_STAGE_BYTES, baseB[r], ks, lane);
-    else a[r - 8] = SA::fragment(smem + sa * A_STAGE_BYTES, baseA[r - 8], ks, lane);
+  auto read_frag = [&](int sa, int sb, int ks, int r, v4i (&a)[FM], v4i (&b)[FN]) {
+    if (r < FN) b[r] = SB::fragment(smem + B_BASE + sb * B_STAGE_BYTES, baseB[r], ks, lane);
+    else a[r - FN] = SA::fragment(smem + sa * A_STAGE_BYTES, baseA[r - FN], ks, lane);
   };
   // Unsigned operand: bias its bytes to signed and sum the other operand over k.  Done to
   // fragment r of a set a few matrix instructions after its read was issued and well before
   // the sub-block that uses the set begins: the matrix instructions are inline assembly, so
   // nothing inserts the wait states they need after an ordinary instruction has written
   // one of their operands.
-  auto fix_frag = [&](int r, v4i (&a)[8], v4i (&b)[8]) {
-    if (r < 8) {
+  auto fix_frag = [&](int r, v4i (&a)[FM], v4i (&b)[FN]) {
+    if (r < FN) {
       if (UNS == 2) b[r] ^= (int)0x80808080u;
       if (UNS == 1) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) sumB[r] = __builtin_amdgcn_sdot4(b[r][e], 0x01010101, sumB[r], false);
       }
     } else {
-      if (UNS == 1) a[r - 8] ^= (int)0x80808080u;
+      if (UNS == 1) a[r - FN] ^= (int)0x80808080u;
       if (UNS == 2) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) sumA[r - 8] = __builtin_amdgcn_sdot4(a[r - 8][e], 0x01010101, sumA[r - 8], false);
+        for (int e = 0; e < 4; ++e) sumA[r - FN] = __builtin_amdgcn_sdot4(a[r - FN][e], 0x01010101, sumA[r - FN], false);
       }
     }
   };
-  constexpr int FIX_LAG = 3;  // fragment reads between a read and its fix-up
-
   const int nkt = P.nkt;  // k / 128
   // prologue: block 0 whole, published; then A and B of block 1 (B of block 2 follows in step 0)
 #pragma unroll
-  for (int q = 0; q < LOADS2; ++q) issue_a(0, q);
+  for (int q = 0; q < LOADS_A; ++q) issue_a(0, q);
 #pragma unroll
-  for (int q = 0; q < LOADS2; ++q) issue_b(0, q);
+  for (int q = 0; q < LOADS_B; ++q) issue_b(0, q);
   gA += stepA;
   gB += stepB;
   publish_barrier<0>();
 #pragma unroll
-  for (int r = 0; r < 16; ++r) read_frag(0, 0, 0, r, fa[0], fb[0]);
+  for (int r = 0; r < NREADS; ++r) read_frag(0, 0, 0, r, fa[0], fb[0]);
   if (UNS != 0) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) fix_frag(r, fa[0], fb[0]);
+    for (int r = 0; r < NREADS; ++r) fix_frag(r, fa[0], fb[0]);
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_nop 7" ::: "memory");  // k = 128: nothing else before the first matrix instruction
     __builtin_amdgcn_sched_barrier(0);
   }
   if (nkt > 1) {
 #pragma unroll
-    for (int q = 0; q < LOADS2; ++q) issue_a(1, q);
+    for (int q = 0; q < LOADS_A; ++q) issue_a(1, q);
 #pragma unroll
-    for (int q = 0; q < LOADS2; ++q) issue_b(1, q);
+    for (int q = 0; q < LOADS_B; ++q) issue_b(1, q);
     gA += stepA;
     gB += stepB;
   }
 
-  // The 64 matrix instructions of one sub-block on fragment set `set`, row by row of the 8 x 8
+  // The FM x FN matrix instructions of one sub-block on fragment set `set`, row by row of the
   // blocks, odd rows backwards so that only one operand changes from one instruction to the
-  // next.  LOAD: eight of them carry one direct load each, into the stage at LDS address
-  // `ldsbase` from gbase + off[q].
-  auto phase = [&](int set, auto reader, auto fixer, auto load_tag, uint32_t ldsbase,
-                   const uint32_t (&off)[LOADS2], const uint8_t *gbase) {
-    constexpr bool LOAD = decltype(load_tag)::value;
+  // next.  LOADS > 0: that many of them carry one direct load each, into the stage at LDS
+  // address `ldsbase` from gbase + off[q].
+  auto phase = [&](int set, auto reader, auto fixer, auto loads_tag, uint32_t ldsbase,
+                   const uint32_t (&off)[LOADS_MAX], const uint8_t *gbase) {
+    constexpr int LOADS = decltype(loads_tag)::value;
+    constexpr int LOAD_EVERY = TS::LOAD_EVERY, READ_FROM = TS::READ_FROM, READ_EVERY = TS::READ_EVERY;
 #pragma unroll
-    for (int s = 0; s < 64; ++s) {
-      const int i = s >> 3, j = (i & 1) ? 7 - (s & 7) : (s & 7);
-      if (LOAD && s % LOAD_EVERY == 0 && s / LOAD_EVERY < LOADS2) {
+    for (int s = 0; s < NMFMA; ++s) {
+      const int i = s / FN, j = (i & 1) ? FN - 1 - (s % FN) : (s % FN);
+      if (s % LOAD_EVERY == 0 && s / LOAD_EVERY < LOADS) {
         asm volatile(
             "s_add_u32 m0, %3, %4\n\t"
             "v_mfma_i32_16x16x64_i8 %0, %1, %2, %0\n\t"
@@ -276,8 +299,8 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
       }
       if (s >= READ_FROM && (s - READ_FROM) % READ_EVERY == 0) {
         const int r = (s - READ_FROM) / READ_EVERY;
-        if (r < 16) reader(r);
-        if (UNS != 0 && r >= FIX_LAG && r - FIX_LAG < 16) fixer(r - FIX_LAG);
+        if (r < NREADS) reader(r);
+        if (UNS != 0 && r >= FIX_LAG && r - FIX_LAG < NREADS) fixer(r - FIX_LAG);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -294,17 +317,18 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
     const int bfill = bnext == B_STAGES - 1 ? 0 : bnext + 1;  // held block t-1: free since the last barrier
     // first sub-block; fetch the second; B of block t+2
     phase(0, [&](int r) { read_frag(cur, bcur, 1, r, fa[1], fb[1]); },
-          [&](int r) { fix_frag(r, fa[1], fb[1]); }, integral_constant<bool, NEXT2>{},
+          [&](int r) { fix_frag(r, fa[1], fb[1]); }, integral_constant<int, NEXT2 ? LOADS_B : 0>{},
           lds0 + B_BASE + bfill * B_STAGE_BYTES, offB, gB);
     if (NEXT2) gB += stepB;
     // block t+1 visible (only the B loads of block t+2 may still fly); the A stage of block t
     // may be refilled
     if (NEXT) {
-      if (NEXT2) publish_barrier<LOADS2>();
+      if (NEXT2) publish_barrier<LOADS_B>();
       else publish_barrier<0>();
     }
     phase(1, [&](int r) { if (NEXT) read_frag(oth, bnext, 0, r, fa[0], fb[0]); },
-          [&](int r) { if (NEXT) fix_frag(r, fa[0], fb[0]); }, integral_constant<bool, NEXT2>{}, lds0 + cur * A_STAGE_BYTES, offA, gA);
+          [&](int r) { if (NEXT) fix_frag(r, fa[0], fb[0]); }, integral_constant<int, NEXT2 ? LOADS_A : 0>{},
+          lds0 + cur * A_STAGE_BYTES, offA, gA);
     if (NEXT2) gA += stepA;
     bcur = bnext;
   };
@@ -323,36 +347,44 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   // compiler does not know that the statements above write them late); the last step has no
   // barrier of its own: wait until no wave reads the stages any more.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  const Correction16<8, 8> corr = unsigned_correction16<8, 8>(sumA, sumB, UNS == 1, UNS == 2, lane);
-  const int64_t mw = m0 + wm * 128, nw = n0 + wn * 128;  // the wave's 128 x 128 patch
-  int32_t *patch = reinterpret_cast<int32_t *>(smem) + wave * Patch16<8>::WORDS;
+  const Correction16<FM, FN> corr = unsigned_correction16<FM, FN>(sumA, sumB, UNS == 1, UNS == 2, lane);
+  const int64_t mw = m0 + wm * WM, nw = n0 + wn * WN;  // the wave's sub-tile
+  int32_t *patch = reinterpret_cast<int32_t *>(smem) + wave * Patch16<FN>::WORDS;
   // an int8 output is a matrix of bytes, ldc counted in bytes
   void *C = P.out_float == 2 ? static_cast<void *>(reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw)
                              : static_cast<void *>(P.C + mw * P.ldc + nw);
-  if (!RAGGED || (mw + 128 <= P.m && nw + 128 <= P.n))
-    store_blocks16<8, 8, true, UNS != 0>(acc, C, P.ldc, 128, 128, P.accumulate != 0, P.out_float, lane, patch,
-                                         P.scale, corr);
+  if (!RAGGED || (mw + WM <= P.m && nw + WN <= P.n))
+    store_blocks16<FM, FN, true, UNS != 0>(acc, C, P.ldc, WM, WN, P.accumulate != 0, P.out_float, lane, patch,
+                                           P.scale, corr);
   else if (mw < P.m && nw < P.n)
-    store_blocks16<8, 8, false, UNS != 0>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate != 0, P.out_float,
-                                          lane, patch, P.scale, corr);
+    store_blocks16<FM, FN, false, UNS != 0>(acc, C, P.ldc, P.m - mw, P.n - nw, P.accumulate != 0, P.out_float,
+                                            lane, patch, P.scale, corr);
 }
 
 }  // namespace
 
-bool dma_k128_eligible(const Problem &p) {
+// small: the 128 x 128 form (whole tiles only)
+bool dma_k128_eligible(const Problem &p, bool small) {
   if (p.conv || p.batch != 1 || p.k % KD2 || p.k < KD2) return false;
-  // ragged m or n: only on k-contiguous operands padded to whole tiles of rows
-  if ((p.m % DM || p.n % DN) && !(p.rows_padded_to_256 && p.a_sk == 1 && p.b_sk == 1)) return false;
+  if (small) {
+    if (p.m % 128 || p.n % 128) return false;
+  } else if ((p.m % DM || p.n % DN) && !(p.rows_padded_to_256 && p.a_sk == 1 && p.b_sk == 1)) {
+    return false;  // ragged m or n: only on k-contiguous operands padded to whole tiles of rows
+  }
   const int64_t lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
   const int64_t ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
   if (lda % 16 || ldb % 16) return false;
   if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
   if (256 * lda >= ((int64_t)1 << 31) || 256 * ldb >= ((int64_t)1 << 31)) return false;
-  if (((p.m + DM - 1) / DM) * ((p.n + DN - 1) / DN) > ((int64_t)1 << 30)) return false;
+  const int64_t bm = small ? 128 : DM, bn = small ? 128 : DN;
+  if (((p.m + bm - 1) / bm) * ((p.n + bn - 1) / bn) > ((int64_t)1 << 30)) return false;
   return true;
 }
 
-hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks) {
+namespace {
+
+template <int BM, int BN>
+hipError_t launch_for(const Problem &p, hipStream_t s, unsigned long long *clocks) {
   DmaParams P;
   P.clocks = clocks;
   P.A = static_cast<const uint8_t *>(p.A);
@@ -363,8 +395,8 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
   P.ldc = p.ldc;
   P.m = p.m;
   P.n = p.n;
-  P.tiles_m = (int)((p.m + DM - 1) / DM);
-  P.tiles_n = (int)((p.n + DN - 1) / DN);
+  P.tiles_m = (int)((p.m + BM - 1) / BM);
+  P.tiles_n = (int)((p.n + BN - 1) / BN);
   P.nkt = (int)(p.k / KD2);
   P.accumulate = p.accumulate;
   P.out_float = p.out_float;
@@ -372,19 +404,21 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
   const int ntiles = P.tiles_m * P.tiles_n;
   dim3 grid((unsigned)(((ntiles + 7) / 8) * 8));
   // (measured at 8192^3, four rounds: 326 -> 310 us on constant operands, 452 -> 444 us on
-  // random ones; the 7 us of late start are not earned back by a single round)
+  // random ones; the 7 us of late start are not earned back by a single round; the 128 x 128
+  // form, two workgroups to a compute unit and a short write-back, starts all at once)
   P.first_round = (int)compute_units();
-  P.stagger_ticks = ntiles >= 2 * P.first_round ? STAGGER_TICKS : 0;
-  const size_t lds = (size_t)LDS2_BYTES;
+  P.stagger_ticks = BM == DM && ntiles >= 2 * P.first_round ? STAGGER_TICKS : 0;
+  const size_t lds = (size_t)Tile16<BM, BN>::LDS_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
   void (*kern)(DmaParams) = nullptr;
-#define MIP_PICK(AK, BKC)                                                        \
-  kern = uns == 0 ? dma128_kernel<AK, BKC, 0>                                    \
-                  : (uns == 1 ? dma128_kernel<AK, BKC, 1> : dma128_kernel<AK, BKC, 2>)
-  if (p.m % DM || p.n % DN)
-    kern = uns == 0 ? dma128_kernel<true, true, 0, true>
-                    : (uns == 1 ? dma128_kernel<true, true, 1, true> : dma128_kernel<true, true, 2, true>);
+#define MIP_PICK(AK, BKC)                                                                    \
+  kern = uns == 0 ? dma128_kernel<BM, BN, AK, BKC, 0>                                        \
+                  : (uns == 1 ? dma128_kernel<BM, BN, AK, BKC, 1> : dma128_kernel<BM, BN, AK, BKC, 2>)
+  if (BM == DM && (p.m % DM || p.n % DN))
+    kern = uns == 0 ? dma128_kernel<DM, DN, true, true, 0, true>
+                    : (uns == 1 ? dma128_kernel<DM, DN, true, true, 1, true>
+                                : dma128_kernel<DM, DN, true, true, 2, true>);
   else if (a_kc && b_kc) MIP_PICK(true, true);
   else if (a_kc) MIP_PICK(true, false);
   else if (b_kc) MIP_PICK(false, true);
@@ -394,6 +428,12 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks, bool small) {
+  return small ? launch_for<128, 128>(p, s, clocks) : launch_for<DM, DN>(p, s, clocks);
 }
 
 }  // namespace mip

@@ -1,7 +1,8 @@
-// Hardware characterisation: the rate of v_mfma_i32_32x32x32_i8 with every
-// operand already in registers (no LDS, no memory traffic), on a 128 x 128
-// accumulator block per wave, one wave per SIMD: the ceiling any GEMM kernel
-// built on this instruction can approach on this device.  The rate depends
+// Hardware characterisation: the rate of v_mfma_i32_32x32x32_i8 and of
+// v_mfma_i32_16x16x64_i8 with every operand already in registers (no LDS, no
+// memory traffic), on a 128 x 128 accumulator block per wave, one wave per SIMD:
+// the ceiling any GEMM kernel built on these instructions can approach on this
+// device.  The rate depends
 // strongly on the operand bits: the chip is power-limited, and random bytes
 // toggle far more logic than near-zero ones.  Every workgroup also reads the
 // shader clock counter and the constant 100 MHz counter around its loop, so the
@@ -28,7 +29,11 @@ __device__ __forceinline__ uint32_t mix(uint32_t x) {
 // PATTERN 3: random bytes, SETS = 6 fixed operand sets used in turn (192 operand
 //            registers beside the 256 accumulators): as 2, with three times as many
 //            distinct operand values passing through the matrix pipe.
-// One iteration is always 32 matrix instructions = 128 x 128 x 64 multiply-accumulates.
+// PATTERN 4: as 0, PATTERN 5: as 2 with one operand set, on v_mfma_i32_16x16x64_i8 (64
+//            four-register accumulators, 8 + 8 operand fragments): the same multiply-
+//            accumulates per clock on paper, but a quarter of the accumulator registers
+//            read and written per multiply-accumulate.
+// One iteration is always 128 x 128 x 64 multiply-accumulates (32 or 64 matrix instructions).
 template <int PATTERN>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, int *sink,
                                                         unsigned long long *clocks) {
@@ -79,11 +84,44 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iterations, int *sin
   }
 }
 
+template <int RANDOM>
+__global__ __launch_bounds__(256) void mfma16_rate_kernel(int iterations, int *sink,
+                                                          unsigned long long *clocks) {
+  v4i acc[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) acc[i] = v4i{0, 0, 0, 0};
+  v4i a[8], b[8];
+  const uint32_t seed = (blockIdx.x * 256 + threadIdx.x) * 977u;
+#pragma unroll
+  for (int f = 0; f < 8; ++f)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      a[f][r] = RANDOM ? (int)mix(seed + f * 8 + r) : r;
+      b[f][r] = RANDOM ? (int)mix(seed + f * 8 + r + 4) : r + 4;
+    }
+  const unsigned long long c0 = __builtin_readcyclecounter(), r0 = wall_clock64();
+  for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+    for (int q = 0; q < 64; ++q)
+      acc[q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(b[q & 7], a[q >> 3], acc[q], 0, 0, 0);
+  }
+  int sum = 0;
+#pragma unroll
+  for (int i = 0; i < 64; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sum += acc[i][j];
+  if (sum == 0x7fffffff) *sink = sum;  // keeps the accumulators live
+  if (clocks && threadIdx.x == 0) {
+    clocks[2 * blockIdx.x] = __builtin_readcyclecounter() - c0;
+    clocks[2 * blockIdx.x + 1] = wall_clock64() - r0;
+  }
+}
+
 }  // namespace mip
 
 extern "C" int mipgemm_mfma_ceiling_clocked(int pattern, int iterations, void *stream,
                                             double *tops, double *shader_mhz) {
-  if (pattern < 0 || pattern > 3) return -1;
+  if (pattern < 0 || pattern > 5) return -1;
   if (iterations < 1 || iterations > 1000000) return -2;
   if (!tops) return -4;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -98,6 +136,8 @@ extern "C" int mipgemm_mfma_ceiling_clocked(int pattern, int iterations, void *s
       pattern == 0 ? mip::mfma_rate_kernel<0>
                    : (pattern == 1 ? mip::mfma_rate_kernel<1>
                                    : (pattern == 2 ? mip::mfma_rate_kernel<2> : mip::mfma_rate_kernel<3>));
+  if (pattern == 4) kern = mip::mfma16_rate_kernel<0>;
+  if (pattern == 5) kern = mip::mfma16_rate_kernel<1>;
   int *sink = nullptr;
   unsigned long long *clocks = nullptr;
   hipEvent_t e0 = nullptr, e1 = nullptr;

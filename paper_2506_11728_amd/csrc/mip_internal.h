@@ -63,7 +63,7 @@ enum Kind {
   KIND_SIMPLE,    // one thread per C element, any layout
   KIND_STAGED,    // MFMA tiles, operands staged through registers: any alignment, any size
   KIND_DMA,       // MFMA tiles, operands streamed global -> LDS directly (aligned, k % 64 == 0)
-  KIND_DMA_K128,  // 256 x 256 tiles, 128-deep k blocks: large aligned problems
+  KIND_DMA_K128,  // 256 x 256 (or, shape SHAPE_128, 128 x 128) tiles, 128-deep k blocks: large aligned problems
   KIND_SLAB       // m <= 64: one workgroup per 16- or 32-column slab of B, all of k (splits = 1 or 2: slab width / 16)
 };
 
@@ -86,10 +86,11 @@ hipError_t launch_fill_zero(const Problem &p, hipStream_t s);
 hipError_t launch_simple(const Problem &p, hipStream_t s);
 hipError_t launch_staged(const Problem &p, Shape shape, int splits, hipStream_t s);
 
-bool dma_k128_eligible(const Problem &p);
+bool dma_k128_eligible(const Problem &p, bool small = false);  // small: its 128 x 128 form
 // clocks: null, or room for two counters per workgroup (one per 256 x 256 tile, rounded up to a
 // multiple of 8) that the kernel adds its shader clocks and 10 ns ticks to
-hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks = nullptr);
+hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks = nullptr,
+                           bool small = false);
 
 bool slab_eligible(const Problem &p, int nt);  // nt: slab width in blocks of 16 columns, 1 or 2
 hipError_t launch_slab(const Problem &p, int nt, hipStream_t s);

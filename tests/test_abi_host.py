@@ -117,7 +117,7 @@ def test_variant_choice(M):
     assert name(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
     assert name(4096, 4096, 1024, 1024, 0, 4096, 0, 4096, 0) == "mfma_dma256_k128"
     assert name(4096, 4096, 1088, 1088, 0, 4096, 0, 4096, 0) == "mfma_dma256"        # k % 128 != 0
-    assert name(4352, 4352, 4096, 4096, 0, 4352, 0, 4352, 0) == "mfma_dma128"        # 289 tiles of 256 x 256: a second round for 33
+    assert name(4352, 4352, 4096, 4096, 0, 4352, 0, 4352, 0) == "mfma_dma128_k128"      # 289 tiles of 256 x 256: a second round for 33
     assert name(4608, 4608, 4096, 4096, 0, 4608, 0, 4608, 0) == "mfma_dma256_k128"
     # unaligned operands cannot use the direct-to-LDS kernels
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128x64"
@@ -141,7 +141,13 @@ def test_variant_choice(M):
     # column-major C swaps the operand roles
     assert name(64, 100352, 576, 576, 0, 100352, 0, 64, 1) == "mfma_dma256x64"
     # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
-    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma64x128"
+    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    # whole 128 x 128 tiles and 128-deep k blocks: the kernel for large problems on that tile shape
+    assert name(1024, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128_k128"
+    assert name(2048, 2048, 2048, 2048, 0, 2048, 0, 2048, 0) == "mfma_dma128_k128"
+    # three quarters of a round of 64 x 128 tiles, long side along the row-major B
+    assert name(256, 6272, 2304, 2304, 0, 6272, 0, 6272, 0) == "mfma_dma64x128"
+    assert name(6272, 256, 2304, 2304, 0, 256, 0, 256, 0) == "mfma_dma64x128"
     # k not a multiple of 64 does not
     assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128x64"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"

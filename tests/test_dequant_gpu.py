@@ -48,7 +48,7 @@ def _cases():
     return out
 
 
-VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128", "slab16", "slab32"]
+VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128", "dma128k128", "slab16", "slab32"]
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

@@ -85,7 +85,7 @@ def kernel_that_runs(M, case, variant):
         assert name == "simple"
     elif variant.startswith("tile"):
         assert name == "mfma_" + variant
-    elif variant.startswith("dma") and variant != "dma256k128":
+    elif variant.startswith("dma") and not variant.endswith("k128"):
         assert name in ("mfma_" + variant, "mfma_tile" + variant[3:])
     _ran.setdefault(variant, set()).add(name)
     return name
@@ -118,7 +118,15 @@ def test_small_cases_every_variant(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
 
 
-@pytest.mark.parametrize("variant", ["auto", "tile256", "dma256", "dma256k128"])
+@pytest.mark.parametrize("variant", ["dma256k128", "dma128k128"])
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: c.name)
+def test_small_cases_deep_k_kernel(gpu, oracle, case, variant):
+    """The kernel for large aligned problems in both its tile shapes, forced on every small case
+    (those it cannot take fall back to whatever the dispatcher picks)."""
+    check_case(gpu, oracle, case, variant)
+
+
+@pytest.mark.parametrize("variant", ["auto", "tile256", "dma256", "dma256k128", "dma128k128"])
 @pytest.mark.parametrize("case", LARGE, ids=lambda c: c.name)
 def test_large_cases(gpu, oracle, case, variant):
     check_case(gpu, oracle, case, variant)
@@ -134,6 +142,7 @@ def test_every_forced_variant_ran_its_own_kernel_on_some_case():
         own = "simple" if variant == "simple" else "mfma_" + variant
         assert own in _ran.get(variant, set()), (variant, _ran.get(variant))
     assert "mfma_dma256_k128" in _ran.get("dma256k128", set())
+    assert "mfma_dma128_k128" in _ran.get("dma128k128", set())
     assert "mfma_dma256_k128" in _ran.get("auto", set())      # the 4096^3 cases as dispatched
 
 
@@ -326,13 +335,13 @@ def test_mfma_ceiling_probe(gpu):
     with pytest.raises(gpu.MipGemmError):
         gpu.mipgemm_mfma_ceiling(2, 2000)
     # the clocked form: more patterns, and a shader clock between idle and the maximum
-    for pattern in range(4):
+    for pattern in range(6):
         tops, mhz = gpu.mipgemm_mfma_ceiling_clocked(pattern, 3000)
         assert 500 < tops < 5600 and 300 < mhz < 2600, (pattern, tops, mhz)
         # the rate follows from the clock: 4 SIMDs x 2048 operations per clock and compute unit
         assert tops <= 256 * 4 * 2048 * mhz * 1e6 / 1e12 * 1.03
     with pytest.raises(gpu.MipGemmError):
-        gpu.mipgemm_mfma_ceiling_clocked(4, 2000)
+        gpu.mipgemm_mfma_ceiling_clocked(6, 2000)
 
 
 def test_clocked_entry_point_matches_the_plain_one(gpu, oracle):
