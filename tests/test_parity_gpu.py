@@ -159,6 +159,32 @@ def test_split_k_is_exact(gpu, oracle, case, variant, splits):
     check_case(gpu, oracle, case, variant, splits)
 
 
+@pytest.mark.parametrize("variant,splits", [("dma64", 2), ("dma64", 16), ("dma128", 4), ("dma64x256", 8),
+                                            ("tile64", 5), ("tile128x64", 3), ("dma64", 64)])
+def test_split_k_overwrite_on_garbage(gpu, oracle, variant, splits):
+    """An overwriting call with split k must not depend on what C held: many tiles and ragged
+    edges, C full of a different garbage before each of four calls in a row on the same
+    buffers, padded ld (the padding keeps its sentinels)."""
+    import torch
+    case = W.Case("turns_%s_%d" % (variant, splits), 8, 3, 200, 328, 4096, pad=16, seed=41)
+    ops = W.materialize(case)
+    want = oracle_result(oracle, case, ops)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+    inside = np.zeros((case.m, case.ldc), dtype=bool)
+    inside[:, :case.n] = True
+    inside = torch.from_numpy(inside.reshape(-1)).cuda()
+    with VariantEnv(variant, splits):
+        for call in range(4):
+            garbage = torch.full_like(dC, 0x01010101 * (call + 3))
+            dC.copy_(torch.where(inside, garbage, torch.from_numpy(ops.C).cuda()))
+            gpu.mipgemm_s8s8s32(case.m, case.n, case.k, dA, case.lda, case.orderA, dB, case.ldb,
+                                case.orderB, dC, case.ldc, case.orderC, W.OVERWRITE)
+            torch.cuda.synchronize()
+            assert np.array_equal(dC.cpu().numpy(), want), "call %d" % call
+
+
 @pytest.mark.parametrize("case", W.config3(), ids=lambda c: c.name)
 def test_conv_cases_through_swapped_u8s8(gpu, oracle, case):
     """The same buffers through mipgemm_u8s8s32 with A and B swapped (C^T = B^T A^T)."""
