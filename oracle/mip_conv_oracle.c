@@ -151,3 +151,28 @@ int oracle_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, int order
                                                   : B[(size_t)(p + j * ldb)];
     return 0;
 }
+
+/*
+ * The k-sums of a signed 8-bit weight matrix: s(j) = sum over p of B(p, j), one per column,
+ * kept with the packed weights (Section 4.1's packed buffer carried to constant weights: what
+ * depends on B alone is computed once).  With activations that are unsigned bytes the integer
+ * product can be formed from the activations moved into the signed range,
+ *     sum_p a(p) b(p, j) = sum_p (a(p) - 128) b(p, j) + 128 s(j),
+ * which is the identity the pins check against the GEMM oracle.  The sums are kept in 32
+ * bits and wrap modulo 2^32 like every other sum here.  order as in oracle_pack_b.
+ */
+int oracle_column_sums_s8(int64_t k, int64_t n, const int8_t *B, int64_t ldb, int order,
+                          int32_t *s)
+{
+    if (k < 0 || n < 0 || (order != 0 && order != 1)) return -1;
+    if (ldb < (order == 0 ? n : k)) return -1;
+    for (int64_t j = 0; j < n; ++j) {
+        uint32_t sum = 0;
+        for (int64_t p = 0; p < k; ++p) {
+            const int8_t b = order == 0 ? B[(size_t)(p * ldb + j)] : B[(size_t)(p + j * ldb)];
+            sum += (uint32_t)(int32_t)b;
+        }
+        s[j] = (int32_t)sum;
+    }
+    return 0;
+}

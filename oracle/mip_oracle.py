@@ -65,6 +65,8 @@ def _load():
             lib.oracle_conv_direct.argtypes = [i64] * 9 + [vp, vp, vp, ci]
             lib.oracle_pack_b.restype = ci
             lib.oracle_pack_b.argtypes = [i64, i64, vp, i64, ci, vp, i64]
+            lib.oracle_column_sums_s8.restype = ci
+            lib.oracle_column_sums_s8.argtypes = [i64, i64, vp, i64, ci, vp]
             lib.oracle_im2col_u8.restype = ci
             lib.oracle_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64]
             _lib = lib
@@ -247,3 +249,36 @@ def pack_b(k, n, B, ldb, orderB, ldp=None, fill=0x5A):
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return P
+
+
+def column_sums(k, n, B, ldb, orderB):
+    """int32 array of n: the sum over k of every column of the signed k x n matrix in ``B``."""
+    B = np.ascontiguousarray(B).view(np.int8).reshape(-1)
+    if B.size < _min_len(k, n, ldb, orderB):
+        raise ValueError("buffer shorter than the matrix it is said to hold")
+    s = np.zeros(n, dtype=np.int32)
+    rc = _load().oracle_column_sums_s8(k, n, B.ctypes.data, ldb, orderB, s.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return s
+
+
+def packed_weights_layout(k, n):
+    """(pitch of a column, columns held, byte offset of the k-sums, total bytes) of the packed
+    form of a k x n weight matrix: columns k-contiguous, each padded with zeros to a whole
+    number of k blocks (128 bytes from k = 1024 on, 64 below), the column count padded with
+    zero columns to a multiple of 256, then one int32 k-sum per (real) column."""
+    block = 128 if k >= 1024 else 64
+    kp = max(block, -(-k // block) * block)
+    cols = max(256, -(-n // 256) * 256)
+    return kp, cols, kp * cols, kp * cols + 4 * n
+
+
+def pack_weights(k, n, B, ldb, orderB):
+    """The packed form of the signed k x n matrix in ``B`` as a flat uint8 array: oracle_pack_b
+    into a zeroed buffer with the pitch above, followed by oracle_column_sums_s8."""
+    kp, cols, at, total = packed_weights_layout(k, n)
+    out = np.zeros(total, dtype=np.uint8)
+    out[:n * kp] = pack_b(k, n, B, ldb, orderB, ldp=kp, fill=0).reshape(-1)
+    out[at:] = column_sums(k, n, B, ldb, orderB).view(np.uint8)
+    return out

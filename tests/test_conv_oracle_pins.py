@@ -235,3 +235,72 @@ def test_pack_b_is_the_numpy_transpose_and_leaves_the_product_unchanged(oracle, 
     oracle.gemm(False, False, m, n, k, A, k, 0, P.reshape(-1).view(np.int8), k + 2, 1, C2, n, 0, 0)
     assert np.array_equal(C1, C2)
     assert np.array_equal(C1.reshape(m, n), A.reshape(m, k).astype(np.int64) @ dense.astype(np.int64))
+
+
+# ---------------------------------------------------------------------------
+# k-sums of the weights and the packed-weights object (oracle_column_sums_s8, pack_weights)
+# ---------------------------------------------------------------------------
+
+def test_column_sums_hand_worked(oracle):
+    # B = [[1, -2, 3], [-4, 5, -6], [7, -8, 127]] (k = 3, n = 3): columns sum to 4, -5, 124
+    Brow = np.array([1, -2, 3, 99, -4, 5, -6, 99, 7, -8, 127, 99], dtype=np.int8)       # ldb = 4
+    assert oracle.column_sums(3, 3, Brow, 4, oracle.ROW_MAJOR).tolist() == [4, -5, 124]
+    Bcol = np.array([1, -4, 7, 2, -8, 2, 5 - 7, 0, -6 + 9, 127 - 3], dtype=np.int8)
+    # column-major with ldb = 3 and nothing between the columns: (1,-4,7), (2,-8,2), (-2,0,3); the 10th byte is not read
+    assert oracle.column_sums(3, 3, Bcol, 3, oracle.COL_MAJOR).tolist() == [4, -4, 1]
+    assert oracle.column_sums(0, 2, np.zeros(0, dtype=np.int8), 2, oracle.ROW_MAJOR).tolist() == [0, 0]
+
+
+@pytest.mark.parametrize("k,n,order,pad", [(7, 5, 0, 0), (64, 64, 1, 3), (300, 37, 0, 5), (1, 9, 1, 0),
+                                           (1030, 20, 0, 17)])
+def test_column_sums_are_a_row_of_ones_times_b(oracle, k, n, order, pad):
+    """Pinned by the GEMM oracle (1^T B, a 1 x k matrix of ones as A), by numpy in 64 bits, and
+    by the identity they exist for: with unsigned activations a,
+    sum_p a b = sum_p (a - 128) b + 128 s, checked through three GEMM oracle calls."""
+    rng = np.random.default_rng([k, n, order, pad, 5])
+    dense = rng.integers(-128, 128, size=(k, n), dtype=np.int8)
+    ldb = (n if order == 0 else k) + pad
+    flat = np.full(((k if order == 0 else n), ldb), 0x5A, dtype=np.uint8)
+    if order == 0:
+        flat[:, :n] = dense.view(np.uint8)
+    else:
+        flat[:, :k] = dense.T.view(np.uint8)
+    flat = flat.reshape(-1).view(np.int8)
+    s = oracle.column_sums(k, n, flat, ldb, order)
+    assert np.array_equal(s.astype(np.int64), dense.astype(np.int64).sum(axis=0))
+    ones = np.ones(k, dtype=np.int8)
+    C = np.zeros(n, dtype=np.int32)
+    oracle.gemm(False, False, 1, n, k, ones, k, 0, flat, ldb, order, C, n, 0, 0)
+    assert np.array_equal(C, s)
+    m = 5
+    Au = rng.integers(0, 256, size=m * k, dtype=np.uint8)
+    As = (Au ^ 0x80).view(np.int8)                 # a - 128 as a signed byte
+    Cu = np.zeros(m * n, dtype=np.int32)
+    Cs = np.zeros(m * n, dtype=np.int32)
+    oracle.gemm(True, False, m, n, k, Au, k, 0, flat, ldb, order, Cu, n, 0, 0)
+    oracle.gemm(False, False, m, n, k, As, k, 0, flat, ldb, order, Cs, n, 0, 0)
+    assert np.array_equal(Cu.reshape(m, n), Cs.reshape(m, n) + 128 * s[None, :])
+
+
+def test_column_sums_wrap(oracle):
+    # 2^24 + 5 entries of -128 in one column: -(2^31) - 640, which wraps to 2^31 - 640
+    k = (1 << 24) + 5
+    B = np.full(k, -128, dtype=np.int8)
+    assert oracle.column_sums(k, 1, B, 1, oracle.ROW_MAJOR).tolist() == [(1 << 31) - 640]
+
+
+def test_packed_weights_layout_and_contents(oracle):
+    assert oracle.packed_weights_layout(1, 1) == (64, 256, 64 * 256, 64 * 256 + 4)
+    assert oracle.packed_weights_layout(1000, 256) == (1024, 256, 1024 * 256, 1024 * 256 + 1024)
+    assert oracle.packed_weights_layout(1024, 257) == (1024, 512, 1024 * 512, 1024 * 512 + 4 * 257)
+    assert oracle.packed_weights_layout(1025, 300) == (1152, 512, 1152 * 512, 1152 * 512 + 1200)
+    # B = [[1, 2, 3], [4, 5, -6]] row-major: columns (1,4), (2,5), (3,-6), each padded to 64 bytes,
+    # 253 zero columns, then the sums 5, 7, -3
+    B = np.array([1, 2, 3, 4, 5, -6], dtype=np.int8)
+    P = oracle.pack_weights(2, 3, B, 3, oracle.ROW_MAJOR)
+    kp, cols, at, total = oracle.packed_weights_layout(2, 3)
+    assert P.size == total == 64 * 256 + 12
+    body = P[:at].reshape(cols, kp).view(np.int8)
+    assert body[0, :2].tolist() == [1, 4] and body[1, :2].tolist() == [2, 5] and body[2, :2].tolist() == [3, -6]
+    assert not body[:, 2:].any() and not body[3:].any()
+    assert P[at:].view(np.int32).tolist() == [5, 7, -3]
