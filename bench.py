@@ -450,6 +450,58 @@ def run_pack_table(M):
                                                         ev0.elapsed_time(ev1) / 10 * 1e3), flush=True)
 
 
+def run_packed_weights_table(M):
+    """Unsigned activations against signed weights: the weights as stored, and as a packed-weights
+    object (mipgemm_pack_weights: k-contiguous, padded, with their k-sums), warm, graph replays."""
+    import torch
+    print()
+    print("Packed weights with cached k-sums (Section 4.1 carried to constant weights), u8 activations x s8")
+    print("weights -> s32, us per call (warm; 8192^3 as 60 launches per replay, the others 24):")
+    print()
+    print("| m | n | k | s8 x s8, B as stored (for reference) | u8 x s8, B row-major as stored | u8 x s8, B k-contiguous "
+          "| u8 x s8 on packed weights | s8 x s8 on packed weights | packing (once) |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    rng = np.random.default_rng(7)
+
+    def replay_us(fn, calls, replays=6):
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(calls):
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(replays):
+            graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / (replays * calls) * 1e3
+
+    R, C_, OVW = W.ROW_MAJOR, W.COL_MAJOR, W.OVERWRITE
+    for (m, n, k) in ((8192, 8192, 8192), (4096, 4096, 4096), (2048, 2048, 2048), (1024, 3072, 768),
+                      (100352, 64, 576), (25088, 128, 1152), (6272, 256, 2304), (1568, 512, 4608),
+                      (16, 11008, 4096), (1, 4096, 4096)):
+        calls = 60 if m * n * k > 2e11 else 24
+        dA = torch.from_numpy(rng.integers(0, 256, size=m * k, dtype=np.uint8)).cuda()
+        dB = torch.from_numpy(rng.integers(-128, 128, size=k * n, dtype=np.int8).view(np.uint8)).cuda()
+        dC = torch.zeros(m * n, dtype=torch.int32, device="cuda")
+        dP = torch.zeros(M.mipgemm_packed_weights_bytes(k, n), dtype=torch.uint8, device="cuda")
+        M.mipgemm_pack_weights(k, n, dB, n, R, dP)
+        dBc = torch.zeros(k * n, dtype=torch.uint8, device="cuda")
+        M.mipgemm_pack_b(k, n, dB, n, R, dBc, k)
+        t = [replay_us(lambda: M.mipgemm_s8s8s32(m, n, k, dA, k, R, dB, n, R, dC, n, R, OVW), calls),
+             replay_us(lambda: M.mipgemm_u8s8s32(m, n, k, dA, k, R, dB, n, R, dC, n, R, OVW), calls),
+             replay_us(lambda: M.mipgemm_u8s8s32(m, n, k, dA, k, R, dBc, k, C_, dC, n, R, OVW), calls),
+             replay_us(lambda: M.mipgemm_u8s8s32_packed(m, n, k, dA, k, R, dP, dC, n, R, OVW), calls),
+             replay_us(lambda: M.mipgemm_s8s8s32_packed(m, n, k, dA, k, R, dP, dC, n, R, OVW), calls),
+             replay_us(lambda: M.mipgemm_pack_weights(k, n, dB, n, R, dP), 8)]
+        print("| %d | %d | %d | %s |" % (m, n, k, " | ".join("%.1f" % x for x in t)), flush=True)
+        del dA, dB, dC, dP, dBc
+
+
 def run_encoder_table(M):
     """The GEMMs of one transformer encoder block (the paper's second workload, Section 7.2),
     captured into one HIP graph in the order of the paper's table and replayed: once with
@@ -630,6 +682,7 @@ def main():
         run_conv_table(M)
         run_network_table(M)
         run_pack_table(M)
+        run_packed_weights_table(M)
         run_encoder_table(M)
         return
 

@@ -402,6 +402,56 @@ int mipgemm_pack_b(int64_t k, int64_t n,
                    void *stream);
 
 /*
+ * Pre-packed weights as an object of their own (Section 4.1 carried to constant
+ * weights: everything that depends on B alone is done once): the k x n signed
+ * matrix B, stored in either order, rewritten into `packed` as
+ *   - its columns with k contiguous, each padded with zeros to kp bytes (k rounded
+ *     up to a multiple of 128, of 64 when k < 1024; at least one such block), the
+ *     column count padded with zero columns to a multiple of 256 (at least 256), so
+ *     that every kernel may fetch whole blocks and whole tiles of it, then
+ *   - n int32 k-sums, s(j) = sum over p of B(p, j) (wrapping modulo 2^32): what a
+ *     product with unsigned activations needs of B beside the product itself,
+ *     sum_p a b = sum_p (a - 128) b + 128 s, the matrix instructions being signed.
+ *     Without them every call sums the fragments of B again as they pass through
+ *     the registers, which costs 12 to 25 % of the time of a large u8 x s8 product.
+ * mipgemm_packed_weights_bytes(k, n) is the size of that object (0 for invalid
+ * sizes); `packed` is DEVICE memory of at least that size, 16-byte aligned, owned
+ * by the caller, and must not overlap B.  Three small launches on `stream`.
+ * Argument numbers: k=1 n=2 B=3 ldb=4 orderB=5 packed=6 packed_bytes=7 stream=8.
+ */
+size_t mipgemm_packed_weights_bytes(int64_t k, int64_t n);
+int mipgemm_pack_weights(int64_t k, int64_t n,
+                         const int8_t *B, int64_t ldb, int orderB,
+                         void *packed, size_t packed_bytes,
+                         void *stream);
+
+/*
+ * C (+)= A B with B given as packed weights (mipgemm_pack_weights with the same k and
+ * n): mipgemm_s8s8s32 / mipgemm_u8s8s32 with `packed` in the place of B, ldb and
+ * orderB.  Same results, bit for bit, as the calls on the unpacked matrix; the
+ * unsigned form takes the k-sums from the packed object where the kernel it is
+ * dispatched to can use them (the direct-to-LDS tile kernels on an unsplit k) and
+ * computes them as usual elsewhere.  Everything else (orders of A and C, mode,
+ * workspace, stream, errors) as in mipgemm_s8s8s32.  Argument numbers: m=1 n=2 k=3
+ * A=4 lda=5 orderA=6 packed=7 C=8 ldc=9 orderC=10 mode=11 workspace=12
+ * workspace_bytes=13 stream=14.
+ */
+int mipgemm_s8s8s32_packed(int64_t m, int64_t n, int64_t k,
+                           const int8_t *A, int64_t lda, int orderA,
+                           const void *packed,
+                           int32_t *C, int64_t ldc, int orderC,
+                           int mode,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+int mipgemm_u8s8s32_packed(int64_t m, int64_t n, int64_t k,
+                           const uint8_t *A, int64_t lda, int orderA,
+                           const void *packed,
+                           int32_t *C, int64_t ldc, int orderC,
+                           int mode,
+                           void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
  * Bytes of device workspace with which a GEMM call of these sizes and orders
  * takes the packed route (see "Pointers" above), taking the tightest leading
  * dimensions and 16-byte aligned pointers: 0 when such operands are streamed as

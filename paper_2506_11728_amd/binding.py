@@ -51,7 +51,9 @@ def exported_symbols():
             "mipgemm_variant_name_for_mode", "mipgemm_set_tuning",
             "mipgemm_conv_workspace_size_unaligned", "mipgemm_mfma_ceiling_clocked",
             "mipgemm_s8s8s32_clocked", "mipgemm_s8s8s32_noalloc", "mipgemm_static_scratch_bytes",
-            "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8"]
+            "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8",
+            "mipgemm_packed_weights_bytes", "mipgemm_pack_weights", "mipgemm_s8s8s32_packed",
+            "mipgemm_u8s8s32_packed"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -111,6 +113,14 @@ def load_library() -> ctypes.CDLL:
                                + [i64, ctypes.c_int, vp, ctypes.c_size_t, vp])
             lib.mipgemm_pack_b.restype = ctypes.c_int
             lib.mipgemm_pack_b.argtypes = [i64, i64, vp, i64, ctypes.c_int, vp, i64, vp]
+            lib.mipgemm_packed_weights_bytes.restype = ctypes.c_size_t
+            lib.mipgemm_packed_weights_bytes.argtypes = [i64, i64]
+            lib.mipgemm_pack_weights.restype = ctypes.c_int
+            lib.mipgemm_pack_weights.argtypes = [i64, i64, vp, i64, ctypes.c_int, vp, ctypes.c_size_t, vp]
+            for fn in (lib.mipgemm_s8s8s32_packed, lib.mipgemm_u8s8s32_packed):
+                fn.restype = ctypes.c_int
+                fn.argtypes = ([i64] * 3 + [vp, i64, ctypes.c_int, vp, vp, i64, ctypes.c_int,
+                                            ctypes.c_int, vp, ctypes.c_size_t, vp])
             lib.mipgemm_im2col_u8.restype = ctypes.c_int
             lib.mipgemm_im2col_u8.argtypes = [i64] * 8 + [vp, vp, i64, vp]
             lib.mipgemm_mfma_ceiling.restype = ctypes.c_int
@@ -309,6 +319,45 @@ def mipgemm_pack_b(k, n, B, ldb, orderB, P, ldp, stream=None, check=True):
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc
+
+
+def mipgemm_packed_weights_bytes(k, n) -> int:
+    return int(load_library().mipgemm_packed_weights_bytes(k, n))
+
+
+def mipgemm_pack_weights(k, n, B, ldb, orderB, packed, packed_bytes=None, stream=None, check=True):
+    """The signed k x n matrix B as a packed-weights object in ``packed`` (a device buffer of
+    mipgemm_packed_weights_bytes(k, n) bytes): columns k-contiguous and zero-padded, then the k-sums."""
+    if packed_bytes is None:
+        packed_bytes = packed.numel() * packed.element_size()
+    rc = load_library().mipgemm_pack_weights(k, n, _ptr(B), ldb, orderB, _ptr(packed), packed_bytes,
+                                             _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def _call_packed(name, m, n, k, A, lda, orderA, packed, C, ldc, orderC, mode, workspace,
+                 workspace_bytes, stream, check):
+    rc = getattr(load_library(), name)(m, n, k, _ptr(A), lda, orderA, _ptr(packed), _ptr(C), ldc,
+                                       orderC, mode, _ptr(workspace), workspace_bytes, _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_s8s8s32_packed(m, n, k, A, lda, orderA, packed, C, ldc, orderC, mode,
+                           workspace=None, workspace_bytes=0, stream=None, check=True):
+    """mipgemm_s8s8s32 with B given as packed weights."""
+    return _call_packed("mipgemm_s8s8s32_packed", m, n, k, A, lda, orderA, packed, C, ldc, orderC,
+                        mode, workspace, workspace_bytes, stream, check)
+
+
+def mipgemm_u8s8s32_packed(m, n, k, A, lda, orderA, packed, C, ldc, orderC, mode,
+                           workspace=None, workspace_bytes=0, stream=None, check=True):
+    """mipgemm_u8s8s32 with B given as packed weights, which bring their k-sums."""
+    return _call_packed("mipgemm_u8s8s32_packed", m, n, k, A, lda, orderA, packed, C, ldc, orderC,
+                        mode, workspace, workspace_bytes, stream, check)
 
 
 def mipgemm_workspace_size(m, n, k, orderA, orderB, orderC) -> int:

@@ -32,6 +32,7 @@ hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s);
 int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
              int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb,
              int orderB, void *C, int64_t ldc, int orderC, int mode, void *workspace,
-             size_t workspace_bytes, void *stream, const Batch &batch = Batch());
+             size_t workspace_bytes, void *stream, const Batch &batch = Batch(),
+             const int32_t *ksum = nullptr);  // ksum: see Problem::ksum (pre-packed weights)
 
 }  // namespace mip

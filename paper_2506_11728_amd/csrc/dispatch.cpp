@@ -181,11 +181,13 @@ Plan choose_plan(const Problem &p) {
     // 64 x 128 tiles, whole 128-byte lines of a row-major B, than through 64 x 64 ones; measured
     // cold, us: (32, 11008, 4096) 18.9 -> 16.5, (64, 11008, 4096) 20.7 -> 18.7, (32, 4096, 11008)
     // 18.9 -> 15.3, (64, 4096, 11008) 21.5 -> 18.9; warm within 0.5 us either way; at
-    // (64, 4096, 4096) the 64 x 64 tiles stay ahead, 11.6 against 12.7.)
+    // (64, 4096, 4096) the 64 x 64 tiles stay ahead, 11.6 against 12.7.  A k-contiguous B has no
+    // lines to complete: (64, 11008, 4096) 13.3/19.2 us warm/cold on 64 x 64, 16.2/20.8 on 64 x 128.)
     if (p.m <= 64 && p.n > 128)
       sh = p.k >= 512 && enough(SHAPE_64X256, p.m)
                ? SHAPE_64X256
-               : (p.m >= 32 && p.k >= 512 && p.n * p.k >= ((int64_t)32 << 20) && dma_eligible(p, SHAPE_64X128)
+               : (p.m >= 32 && p.k >= 512 && p.b_sn == 1 && p.n * p.k >= ((int64_t)32 << 20) &&
+                          dma_eligible(p, SHAPE_64X128)
                       ? SHAPE_64X128
                       : SHAPE_64);
     else if (p.n <= 64 && p.m > 128) sh = p.k >= 512 && enough(SHAPE_256X64, p.n) ? SHAPE_256X64 : SHAPE_64;

@@ -46,6 +46,7 @@ struct DmaTileParams {
   int splits;
   int out_float;          // 1 dequantised output: float(sum) * scale; 2 requantised int8 output
   float scale;
+  const int32_t *ksum;    // UNS 3 and 4: the k sums of the signed operand (see Problem::ksum)
   ConvGeom conv;          // CONV kernels only
   int64_t a_sb, b_sb, c_sb;  // byte / element offsets of problem z of a batch (blockIdx.z)
 };
@@ -53,9 +54,13 @@ struct DmaTileParams {
 // what a tap outside the image contributes
 static __device__ __attribute__((aligned(16))) const uint8_t conv_zero_block[16] = {};
 
-// UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
+// UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned; 3 and 4: as 1 and 2 with the k sums
+// of the signed operand read from P.ksum instead of being accumulated from the fragments
+// (whole problem only: with split k every range would add them).
 template <int BM, int BN, bool A_KC, bool B_KC, int UNS, bool CONV = false>
 __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
+  constexpr bool FLIP_A = UNS == 1 || UNS == 3, FLIP_B = UNS == 2 || UNS == 4;
+  constexpr bool SUM_A = UNS == 2, SUM_B = UNS == 1;
   static_assert(!CONV || (A_KC && B_KC), "the lowered matrix and the filters are k-contiguous");
   using SA = Stage<BM, A_KC>;
   using SB = Stage<BN, B_KC>;
@@ -210,18 +215,22 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
   };
   // unsigned operand: bias its bytes to signed, and sum the other operand over k
   auto prepare = [&](v4i (&a)[FM], v4i (&b)[FN]) {
-    if (UNS == 1) {
+    if (FLIP_A) {
 #pragma unroll
       for (int i = 0; i < FM; ++i) a[i] ^= (int)0x80808080u;
+    }
+    if (SUM_B) {
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           sumB[j] = __builtin_amdgcn_sdot4(b[j][r], 0x01010101, sumB[j], false);
     }
-    if (UNS == 2) {
+    if (FLIP_B) {
 #pragma unroll
       for (int j = 0; j < FN; ++j) b[j] ^= (int)0x80808080u;
+    }
+    if (SUM_A) {
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -287,7 +296,23 @@ __global__ __launch_bounds__(NTHREADS) void dma_tile_kernel(DmaTileParams P) {
 
   // ---- write-back: unsigned-operand correction, then C = / += / atomic += ----
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // stages are dead from here on
-  unsigned_correction<FM, FN>(acc, sumA, sumB, UNS == 1, UNS == 2, lane);
+  // supplied k sums: the lane that would hold the first half of a column's (row's) sum takes
+  // the whole of it, its partner 32 lanes on zero
+  if (UNS == 3) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int64_t col = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+      sumB[j] = lane < 32 && col < P.n ? P.ksum[col] : 0;
+    }
+  }
+  if (UNS == 4) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int64_t row = m0 + wm * (BM / 2) + i * 32 + (lane & 31);
+      sumA[i] = lane < 32 && row < P.m ? P.ksum[row] : 0;
+    }
+  }
+  unsigned_correction<FM, FN>(acc, sumA, sumB, FLIP_A, FLIP_B, lane);
   if (P.slots) {  // only the workgroup that draws the tile's last ticket writes C
     const int64_t tile = ((int64_t)blockIdx.z * P.tiles_m + tm) * P.tiles_n + tn;
     if (!combine_k_ranges<FM, FN>(acc, P.slots + tile * P.splits * (int64_t)(BM * BN), blockIdx.y,
@@ -409,12 +434,21 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
   size_t lds = (size_t)stages * (BM + BN) * BK;
   if (lds < 4 * (size_t)STORE_PATCH_BYTES) lds = 4 * (size_t)STORE_PATCH_BYTES;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
+  // supplied k sums (pre-packed weights): for an unsplit k and a k-contiguous signed operand,
+  // which packed weights always are; otherwise the sums are accumulated in the loop as usual
+  const bool supplied = p.ksum != nullptr && splits == 1 && p.batch <= 1 && !p.conv &&
+                        ((uns == 1 && b_kc) || (uns == 2 && a_kc));
+  P.ksum = supplied ? p.ksum : nullptr;
   void (*kern)(DmaTileParams) = nullptr;
 #define MIP_PICK(AK, BKC)                                                          \
   kern = uns == 0 ? dma_tile_kernel<BM, BN, AK, BKC, 0>                            \
                   : (uns == 1 ? dma_tile_kernel<BM, BN, AK, BKC, 1>                \
                               : dma_tile_kernel<BM, BN, AK, BKC, 2>)
-  if (a_kc && b_kc) MIP_PICK(true, true);
+  if (supplied && uns == 1)
+    kern = a_kc ? dma_tile_kernel<BM, BN, true, true, 3> : dma_tile_kernel<BM, BN, false, true, 3>;
+  else if (supplied)
+    kern = b_kc ? dma_tile_kernel<BM, BN, true, true, 4> : dma_tile_kernel<BM, BN, true, false, 4>;
+  else if (a_kc && b_kc) MIP_PICK(true, true);
   else if (a_kc) MIP_PICK(true, false);
   else if (b_kc) MIP_PICK(false, true);
   else MIP_PICK(false, false);

@@ -31,6 +31,8 @@ struct DmaParams {
   // not null: workgroup w adds the shader clocks and the 10 ns ticks it ran for to
   // clocks[2 w], clocks[2 w + 1] (benchmarks: the clock the device sustained)
   unsigned long long *clocks;
+  // UNS 3 and 4: the k sums of the signed operand, one per column of B (3) or row of A (4)
+  const int32_t *ksum;
   // Workgroups of the first round (the first first_round workgroup numbers: one per compute
   // unit) start late by their row in the XCD's patch of tiles times stagger_ticks (10 ns
   // each); 0 = all at once.
@@ -144,9 +146,14 @@ struct Stage16 {
   }
 };
 
-// UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned.
+// UNS: 0 both operands signed, 1 A unsigned, 2 B unsigned; 3 and 4: as 1 and 2 with the k sums
+// of the signed operand read from P.ksum (pre-packed weights carry them) instead of being
+// accumulated from the fragments in the loop, which costs four dot-product instructions per
+// fragment of the signed operand between the matrix instructions.
 template <int BM, int BN, bool A_KC, bool B_KC, int UNS, bool RAGGED = false>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
+  constexpr bool FLIP_A = UNS == 1 || UNS == 3, FLIP_B = UNS == 2 || UNS == 4;
+  constexpr bool SUM_A = UNS == 2, SUM_B = UNS == 1;
   using TS = Tile16<BM, BN>;
   using SA = Stage16<BM, A_KC>;
   using SB = Stage16<BN, B_KC>;
@@ -232,19 +239,36 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   // one of their operands.
   auto fix_frag = [&](int r, v4i (&a)[FM], v4i (&b)[FN]) {
     if (r < FN) {
-      if (UNS == 2) b[r] ^= (int)0x80808080u;
-      if (UNS == 1) {
+      if (FLIP_B) b[r] ^= (int)0x80808080u;
+      if (SUM_B) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) sumB[r] = __builtin_amdgcn_sdot4(b[r][e], 0x01010101, sumB[r], false);
       }
     } else {
-      if (UNS == 1) a[r - FN] ^= (int)0x80808080u;
-      if (UNS == 2) {
+      if (FLIP_A) a[r - FN] ^= (int)0x80808080u;
+      if (SUM_A) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) sumA[r - FN] = __builtin_amdgcn_sdot4(a[r - FN][e], 0x01010101, sumA[r - FN], false);
       }
     }
   };
+  // Supplied k sums: the lane that would hold the first quarter of a row's (column's) sum takes
+  // the whole of it, the other three lane groups zero, and the correction below adds them up
+  // as it does the accumulated ones.  Read here, ahead of the loop, which hides the latency.
+  if (UNS == 3) {
+#pragma unroll
+    for (int f = 0; f < FN; ++f) {
+      const int64_t col = n0 + wn * WN + f * 16 + (lane & 15);
+      sumB[f] = lane < 16 && (!RAGGED || col < P.n) ? P.ksum[col] : 0;
+    }
+  }
+  if (UNS == 4) {
+#pragma unroll
+    for (int f = 0; f < FM; ++f) {
+      const int64_t row = m0 + wm * WM + f * 16 + (lane & 15);
+      sumA[f] = lane < 16 && (!RAGGED || row < P.m) ? P.ksum[row] : 0;
+    }
+  }
   const int nkt = P.nkt;  // k / 128
   // prologue: block 0 whole, published; then A and B of block 1 (B of block 2 follows in step 0)
 #pragma unroll
@@ -347,7 +371,7 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   // compiler does not know that the statements above write them late); the last step has no
   // barrier of its own: wait until no wave reads the stages any more.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  const Correction16<FM, FN> corr = unsigned_correction16<FM, FN>(sumA, sumB, UNS == 1, UNS == 2, lane);
+  const Correction16<FM, FN> corr = unsigned_correction16<FM, FN>(sumA, sumB, FLIP_A, FLIP_B, lane);
   const int64_t mw = m0 + wm * WM, nw = n0 + wn * WN;  // the wave's sub-tile
   int32_t *patch = reinterpret_cast<int32_t *>(smem) + wave * Patch16<FN>::WORDS;
   // an int8 output is a matrix of bytes, ldc counted in bytes
@@ -411,14 +435,24 @@ hipError_t launch_for(const Problem &p, hipStream_t s, unsigned long long *clock
   const size_t lds = (size_t)Tile16<BM, BN>::LDS_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
+  // supplied k sums (pre-packed weights): instantiated for a k-contiguous signed operand,
+  // which packed weights always are; otherwise the sums are accumulated in the loop as usual
+  const bool supplied = p.ksum != nullptr && ((uns == 1 && b_kc) || (uns == 2 && a_kc));
+  P.ksum = supplied ? p.ksum : nullptr;
   void (*kern)(DmaParams) = nullptr;
 #define MIP_PICK(AK, BKC)                                                                    \
   kern = uns == 0 ? dma128_kernel<BM, BN, AK, BKC, 0>                                        \
                   : (uns == 1 ? dma128_kernel<BM, BN, AK, BKC, 1> : dma128_kernel<BM, BN, AK, BKC, 2>)
   if (BM == DM && (p.m % DM || p.n % DN))
     kern = uns == 0 ? dma128_kernel<DM, DN, true, true, 0, true>
-                    : (uns == 1 ? dma128_kernel<DM, DN, true, true, 1, true>
-                                : dma128_kernel<DM, DN, true, true, 2, true>);
+           : supplied ? (uns == 1 ? dma128_kernel<DM, DN, true, true, 3, true>
+                                  : dma128_kernel<DM, DN, true, true, 4, true>)
+                      : (uns == 1 ? dma128_kernel<DM, DN, true, true, 1, true>
+                                  : dma128_kernel<DM, DN, true, true, 2, true>);
+  else if (supplied && uns == 1)
+    kern = a_kc ? dma128_kernel<BM, BN, true, true, 3> : dma128_kernel<BM, BN, false, true, 3>;
+  else if (supplied)
+    kern = b_kc ? dma128_kernel<BM, BN, true, true, 4> : dma128_kernel<BM, BN, true, false, 4>;
   else if (a_kc && b_kc) MIP_PICK(true, true);
   else if (a_kc) MIP_PICK(true, false);
   else if (b_kc) MIP_PICK(false, true);

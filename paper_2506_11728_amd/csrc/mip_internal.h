@@ -47,6 +47,10 @@ struct Problem {
   // caller's workspace): slots of partial sums for split k (16-byte aligned)
   void *ws = nullptr;
   size_t ws_bytes = 0;
+  // not null: the k sums of the signed operand of a product with one unsigned operand, one
+  // int32 per column of B (a_unsigned) or row of A (b_unsigned), as pre-packed weights carry
+  // them.  A kernel may use them in place of the sums it would accumulate, or ignore them.
+  const int32_t *ksum = nullptr;
   // not null: A is never materialised, the kernel gathers it from the image tensor
   // (only the direct-to-LDS tile kernels can; a_sm is then the nominal row length k)
   const ConvGeom *conv = nullptr;
@@ -117,6 +121,11 @@ hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8
 // as zeros (kfill <= k: nothing beyond k is written).
 hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
                          int64_t ldp, hipStream_t s, int64_t kfill = 0);
+
+// sums[j] = the sum of the kp bytes, read as signed 8-bit values, of column j of the
+// k-contiguous matrix P (pitch ldp; kp, ldp and P multiples of 16).
+hipError_t launch_column_sums(int64_t kp, int64_t n, const uint8_t *P, int64_t ldp, int32_t *sums,
+                              hipStream_t s);
 
 // The convolution (p.conv set, image unsigned, filters k-contiguous with pitch k) with the
 // augmented matrix gathered from image row segments staged in LDS: any channel count.

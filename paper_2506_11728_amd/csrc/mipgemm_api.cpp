@@ -101,11 +101,13 @@ size_t packed_route_bytes(const Problem &p) {
 int run_gemm(int a_unsigned, int b_unsigned, int out_float, float scale, int64_t m, int64_t n,
         int64_t k, const void *A, int64_t lda, int orderA, const void *B, int64_t ldb, int orderB,
         void *C, int64_t ldc, int orderC, int mode, void *workspace, size_t workspace_bytes,
-        void *stream, const Batch &batch) {
+        void *stream, const Batch &batch, const int32_t *ksum) {
   Problem p;
   int rc = validate_and_normalise(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB,
                                   C, ldc, orderC, mode, workspace, workspace_bytes, &p);
   if (rc != 0) return rc;
+  // (the sums belong to the signed operand whichever role the normalisation has given it)
+  p.ksum = (a_unsigned != 0) != (b_unsigned != 0) ? ksum : nullptr;
   p.out_float = out_float;
   p.scale = scale;
   p.batch = batch.count;
@@ -201,6 +203,100 @@ int mipgemm_u8s8s32(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t l
                     int mode, void *workspace, size_t workspace_bytes, void *stream) {
   return mip::run_gemm(1, 0, 0, 1.0f, m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode, workspace,
              workspace_bytes, stream);
+}
+
+// ---- pre-packed weights ----
+
+static int64_t round_up_to(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
+
+// Layout of the packed weights: columns k-contiguous with pitch kp (k rounded up to whole k
+// blocks: 128 bytes from k = 1024 on, 64 below, at least one block), `cols` columns (n rounded
+// up to a multiple of 256, at least 256; the added ones zero), then n int32 k-sums.
+struct PackedLayout { int64_t kp, cols; size_t sums_at, total; };
+static bool packed_layout(int64_t k, int64_t n, PackedLayout *L) {
+  if (k < 0 || n < 0 || k > MIPGEMM_MAX_DIM || n > MIPGEMM_MAX_DIM) return false;
+  const int64_t block = k >= 1024 ? 128 : 64;
+  L->kp = k > 0 ? round_up_to(k, block) : block;
+  L->cols = n > 0 ? round_up_to(n, 256) : 256;
+  if (L->kp > MIPGEMM_MAX_DIM || (double)L->kp * (double)L->cols > 4.0e18) return false;
+  L->sums_at = (size_t)L->kp * (size_t)L->cols;
+  L->total = L->sums_at + 4 * (size_t)n;
+  return true;
+}
+
+size_t mipgemm_packed_weights_bytes(int64_t k, int64_t n) {
+  PackedLayout L;
+  return packed_layout(k, n, &L) ? L.total : 0;
+}
+
+int mipgemm_pack_weights(int64_t k, int64_t n, const int8_t *B, int64_t ldb, int orderB,
+                         void *packed, size_t packed_bytes, void *stream) {
+  PackedLayout L;
+  if (k < 0 || k > MIPGEMM_MAX_DIM) return -1;
+  if (n < 0 || n > MIPGEMM_MAX_DIM) return -2;
+  if (!B && k > 0 && n > 0) return -3;
+  if (!mip::order_ok(orderB)) return -5;
+  {
+    const int64_t need = orderB == MIPGEMM_ROW_MAJOR ? n : k;
+    if (ldb < (need > 1 ? need : 1) || ldb > MIPGEMM_MAX_DIM) return -4;
+  }
+  if (!packed || reinterpret_cast<uintptr_t>(packed) % 16 != 0) return -6;
+  if (!packed_layout(k, n, &L) || packed_bytes < L.total) return -7;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t *body = static_cast<uint8_t *>(packed);
+  // the columns, each with its k tail zeroed up to the pitch
+  hipError_t e = mip::launch_pack_b(k, n, reinterpret_cast<const uint8_t *>(B), ldb,
+                                    orderB == MIPGEMM_COL_MAJOR, body, L.kp, s, L.kp);
+  if (e != hipSuccess) return static_cast<int>(e);
+  if (k == 0 && n > 0) {  // nothing was moved: the one block of every column is all padding
+    mip::Problem z;
+    z.m = 1; z.n = n * L.kp / 4; z.k = 0;
+    z.C = reinterpret_cast<int32_t *>(body); z.ldc = z.n;
+    e = mip::launch_fill_zero(z, s);
+    if (e != hipSuccess) return static_cast<int>(e);
+  }
+  if (L.cols > n) {  // the added columns (a fill kernel, not a memset: the call may be under graph capture)
+    mip::Problem z;
+    z.m = 1; z.n = (L.cols - n) * L.kp / 4; z.k = 0;
+    z.C = reinterpret_cast<int32_t *>(body + (size_t)n * (size_t)L.kp); z.ldc = z.n;
+    e = mip::launch_fill_zero(z, s);
+    if (e != hipSuccess) return static_cast<int>(e);
+  }
+  e = mip::launch_column_sums(L.kp, n, body, L.kp, reinterpret_cast<int32_t *>(body + L.sums_at), s);
+  return static_cast<int>(e);
+}
+
+// The GEMM on packed weights: they are B, column-major with the pitch of the layout, and
+// bring the k sums an unsigned A needs.  Error numbers follow this prototype (m=1 n=2 k=3 A=4
+// lda=5 orderA=6 packed=7 C=8 ldc=9 orderC=10 mode=11 workspace=12).
+static int run_packed(int a_unsigned, int64_t m, int64_t n, int64_t k, const void *A, int64_t lda,
+                      int orderA, const void *packed, void *C, int64_t ldc, int orderC, int mode,
+                      void *workspace, size_t workspace_bytes, void *stream) {
+  PackedLayout L;
+  if (m < 0 || m > MIPGEMM_MAX_DIM) return -1;
+  if (!packed_layout(k, n, &L)) return n < 0 || n > MIPGEMM_MAX_DIM ? -2 : -3;
+  if (!packed || reinterpret_cast<uintptr_t>(packed) % 16 != 0) return -7;
+  const uint8_t *body = static_cast<const uint8_t *>(packed);
+  const int rc = mip::run_gemm(a_unsigned, 0, 0, 1.0f, m, n, k, A, lda, orderA, body, L.kp,
+                               MIPGEMM_COL_MAJOR, C, ldc, orderC, mode, workspace, workspace_bytes,
+                               stream, mip::Batch(),
+                               reinterpret_cast<const int32_t *>(body + L.sums_at));
+  if (rc >= -7) return rc;    // success, a hipError_t, or one of the first seven arguments
+  return rc + 2;              // C, ldc, orderC, mode, workspace: two places earlier here
+}
+
+int mipgemm_s8s8s32_packed(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
+                           const void *packed, int32_t *C, int64_t ldc, int orderC, int mode,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+  return run_packed(0, m, n, k, A, lda, orderA, packed, C, ldc, orderC, mode, workspace,
+                    workspace_bytes, stream);
+}
+
+int mipgemm_u8s8s32_packed(int64_t m, int64_t n, int64_t k, const uint8_t *A, int64_t lda, int orderA,
+                           const void *packed, int32_t *C, int64_t ldc, int orderC, int mode,
+                           void *workspace, size_t workspace_bytes, void *stream) {
+  return run_packed(1, m, n, k, A, lda, orderA, packed, C, ldc, orderC, mode, workspace,
+                    workspace_bytes, stream);
 }
 
 int mipgemm_s8u8s32(int64_t m, int64_t n, int64_t k, const int8_t *A, int64_t lda, int orderA,
