@@ -374,11 +374,12 @@ def run_network_table(M):
     print("All 53 convolutions of a ResNet-50 v1.5-type network on 224 x 224 images (23 distinct layers),")
     print("u8 activations x s8 filters -> s32, each layer on its own synthetic tensors:")
     print()
-    print("| batch | us, all convolutions | of which the 7 x 7 stem (3 channels: row-segment kernel) | GMAC | TOPS |")
-    print("|---|---|---|---|---|")
+    print("| batch | us, all convolutions | of which the 7 x 7 stem (3 channels: row-segment kernel) | GMAC | TOPS "
+          "| us with the filters' k-sums supplied (computed once) | TOPS |")
+    print("|---|---|---|---|---|---|---|")
     layers = W.resnet50_conv_layers()
     for b in W.CONV_BATCHES:
-        calls, macs, stem_call = [], 0, None
+        calls, calls_sums, macs, stem_call = [], [], 0, None
         for name, geo, count in layers:
             hi, ci, co, hf, stride, pad = geo
             image, filt = W.conv_tensors(b, geo)
@@ -391,7 +392,13 @@ def run_network_table(M):
             call = (lambda args=args, dF=dF, dI=dI, dO=dO, ws=ws, need=need:
                     M.mipgemm_conv_s8u8s32(*args, dF, dI, dO, W.OVERWRITE, workspace=ws,
                                            workspace_bytes=need))
+            dS = torch.zeros(co, dtype=torch.int32, device="cuda")
+            M.mipgemm_conv_filter_sums(co, hf * hf * ci, dF, dS)
+            call_sums = (lambda args=args, dF=dF, dI=dI, dO=dO, ws=ws, need=need, dS=dS:
+                         M.mipgemm_conv_s8u8s32_with_sums(*args, dF, dI, dO, W.OVERWRITE, dS, workspace=ws,
+                                                          workspace_bytes=need))
             calls += [call] * count
+            calls_sums += [call_sums] * count
             macs += count * b * ho * ho * co * ci * hf * hf
             if name == "stem":
                 stem_call = call
@@ -417,8 +424,9 @@ def run_network_table(M):
 
         total = timed(calls, 2)
         stem = timed([stem_call], 8)
-        print("| %d | %.0f | %.0f | %.2f | %.1f |" % (b, total, stem, macs / 1e9,
-                                                      2 * macs / total / 1e6), flush=True)
+        total_sums = timed(calls_sums, 2)
+        print("| %d | %.0f | %.0f | %.2f | %.1f | %.0f | %.1f |" % (b, total, stem, macs / 1e9, 2 * macs / total / 1e6,
+                                                                 total_sums, 2 * macs / total_sums / 1e6), flush=True)
 
 
 def run_pack_table(M):

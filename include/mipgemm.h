@@ -344,6 +344,32 @@ int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci,
                          void *stream, float scale);
 
 /*
+ * The same convolutions with the k-sums of the filters supplied (Section 4.1 carried to
+ * constant weights, as mipgemm_pack_weights does for a GEMM): the image is unsigned, the
+ * matrix instructions are signed, so the kernels multiply `pixel - 128` and add
+ * 128 * sum over k of F(o, k) per filter o; without the sums every call adds the filter
+ * fragments up again as they pass through the registers.  mipgemm_conv_filter_sums
+ * computes sums[o] (DEVICE memory, c_o int32) from the filter tensor, k = h_f w_f c_i, once;
+ * argument numbers co=1 k=2 F=3 sums=4 stream=5.  The *_with_sums calls take it as their
+ * last argument (number 17 for the s32 form, 18 for the f32 form; must not be null) and
+ * give the same results as the plain calls; the kernels that gather through the tile
+ * kernels and the written-out route use the sums, the row-segment kernel computes its own.
+ */
+int mipgemm_conv_filter_sums(int64_t co, int64_t k, const int8_t *F, int32_t *sums, void *stream);
+int mipgemm_conv_s8u8s32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                   int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                                   const int8_t *F, const uint8_t *I, int32_t *O,
+                                   int mode,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *stream, const int32_t *filter_sums);
+int mipgemm_conv_s8u8f32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                                   int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                                   const int8_t *F, const uint8_t *I, float *O,
+                                   int mode,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *stream, float scale, const int32_t *filter_sums);
+
+/*
  * Bytes of workspace mipgemm_conv_s8u8s32 / mipgemm_conv_s8u8f32 need for these sizes when its pointers
  * are 16-byte aligned: 0 when the augmented matrix is gathered on the fly (see
  * above), else room for it.  Returns 0 for invalid sizes.

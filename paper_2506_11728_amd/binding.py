@@ -53,7 +53,8 @@ def exported_symbols():
             "mipgemm_s8s8s32_clocked", "mipgemm_s8s8s32_noalloc", "mipgemm_static_scratch_bytes",
             "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8",
             "mipgemm_packed_weights_bytes", "mipgemm_pack_weights", "mipgemm_s8s8s32_packed",
-            "mipgemm_u8s8s32_packed"]
+            "mipgemm_u8s8s32_packed", "mipgemm_conv_filter_sums",
+            "mipgemm_conv_s8u8s32_with_sums", "mipgemm_conv_s8u8f32_with_sums"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -95,6 +96,14 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_conv_s8u8f32.restype = ctypes.c_int
             lib.mipgemm_conv_s8u8f32.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
                                                              ctypes.c_size_t, vp, ctypes.c_float]
+            lib.mipgemm_conv_filter_sums.restype = ctypes.c_int
+            lib.mipgemm_conv_filter_sums.argtypes = [i64, i64, vp, vp, vp]
+            lib.mipgemm_conv_s8u8s32_with_sums.restype = ctypes.c_int
+            lib.mipgemm_conv_s8u8s32_with_sums.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
+                                                                       ctypes.c_size_t, vp, vp]
+            lib.mipgemm_conv_s8u8f32_with_sums.restype = ctypes.c_int
+            lib.mipgemm_conv_s8u8f32_with_sums.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
+                                                                       ctypes.c_size_t, vp, ctypes.c_float, vp]
             lib.mipgemm_conv_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
             lib.mipgemm_conv_workspace_size_unaligned.restype = ctypes.c_size_t
@@ -247,6 +256,36 @@ def mipgemm_conv_s8u8f32(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode,
     rc = load_library().mipgemm_conv_s8u8f32(
         b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
         _ptr(workspace), workspace_bytes, _stream(stream), scale)
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_filter_sums(co, k, F, sums, stream=None, check=True):
+    """sums[o] = the sum over k of filter o (F: c_o filters of k = h_f w_f c_i signed bytes each)."""
+    rc = load_library().mipgemm_conv_filter_sums(co, k, _ptr(F), _ptr(sums), _stream(stream))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_s8u8s32_with_sums(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, filter_sums,
+                                   workspace=None, workspace_bytes=0, stream=None, check=True):
+    """mipgemm_conv_s8u8s32 with the filters' k-sums (mipgemm_conv_filter_sums) supplied."""
+    rc = load_library().mipgemm_conv_s8u8s32_with_sums(
+        b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
+        _ptr(workspace), workspace_bytes, _stream(stream), _ptr(filter_sums))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_s8u8f32_with_sums(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, filter_sums,
+                                   workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """mipgemm_conv_s8u8f32 with the filters' k-sums supplied."""
+    rc = load_library().mipgemm_conv_s8u8f32_with_sums(
+        b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
+        _ptr(workspace), workspace_bytes, _stream(stream), scale, _ptr(filter_sums))
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc

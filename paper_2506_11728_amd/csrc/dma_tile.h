@@ -455,7 +455,10 @@ hipError_t launch_dma_tile_for(const Problem &p, int splits, hipStream_t s) {
 #undef MIP_PICK
   if (p.conv) {
     P.conv = *p.conv;
-    kern = dma_tile_kernel<BM, BN, true, true, 1, true>;
+    // (the gathered matrix is the unsigned A, the filters the signed, k-contiguous B)
+    const bool filter_sums = p.ksum != nullptr && splits == 1;
+    P.ksum = filter_sums ? p.ksum : nullptr;
+    kern = filter_sums ? dma_tile_kernel<BM, BN, true, true, 3, true> : dma_tile_kernel<BM, BN, true, true, 1, true>;
   } else {
     P.conv = ConvGeom{};
   }

@@ -153,19 +153,25 @@ bool make_job(int64_t k, int64_t kfill, int64_t n, const uint8_t *B, int64_t ldb
   return true;
 }
 
-// One wave per column of a k-contiguous matrix: the sum of its kp bytes read as signed 8-bit
-// values (kp a multiple of 16, the column 16-byte aligned; zero padding adds nothing).
-__global__ __launch_bounds__(256) void column_sums_kernel(const uint8_t *P, int64_t ldp, int64_t kp,
+// One wave per column of a k-contiguous matrix: the sum of its k bytes read as signed 8-bit
+// values.  WIDE: k a multiple of 16 and every column 16-byte aligned.
+template <bool WIDE>
+__global__ __launch_bounds__(256) void column_sums_kernel(const uint8_t *P, int64_t ldp, int64_t k,
                                                           int64_t n, int32_t *sums) {
   const int lane = threadIdx.x & 63;
   const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (col >= n) return;
-  const v4i_pack *src = reinterpret_cast<const v4i_pack *>(P + col * ldp);
   int sum = 0;
-  for (int64_t c = lane; c < kp / 16; c += 64) {
-    const v4i_pack v = src[c];
+  if (WIDE) {
+    const v4i_pack *src = reinterpret_cast<const v4i_pack *>(P + col * ldp);
+    for (int64_t c = lane; c < k / 16; c += 64) {
+      const v4i_pack v = src[c];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_sdot4(v[e], 0x01010101, sum, false);
+      for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_sdot4(v[e], 0x01010101, sum, false);
+    }
+  } else {
+    const int8_t *src = reinterpret_cast<const int8_t *>(P + col * ldp);
+    for (int64_t c = lane; c < k; c += 64) sum += src[c];
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
@@ -174,12 +180,14 @@ __global__ __launch_bounds__(256) void column_sums_kernel(const uint8_t *P, int6
 
 }  // namespace
 
-hipError_t launch_column_sums(int64_t kp, int64_t n, const uint8_t *P, int64_t ldp, int32_t *sums,
+hipError_t launch_column_sums(int64_t k, int64_t n, const uint8_t *P, int64_t ldp, int32_t *sums,
                               hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  if (kp % 16 || ldp % 16 || reinterpret_cast<uintptr_t>(P) % 16 || (n + 3) / 4 > 0x7fffffff)
-    return hipErrorInvalidValue;
-  hipLaunchKernelGGL(column_sums_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, P, ldp, kp, n, sums);
+  if ((n + 3) / 4 > 0x7fffffff) return hipErrorInvalidValue;
+  const bool wide = k % 16 == 0 && ldp % 16 == 0 && reinterpret_cast<uintptr_t>(P) % 16 == 0;
+  const dim3 grid((unsigned)((n + 3) / 4));
+  if (wide) hipLaunchKernelGGL(column_sums_kernel<true>, grid, dim3(256), 0, s, P, ldp, k, n, sums);
+  else hipLaunchKernelGGL(column_sums_kernel<false>, grid, dim3(256), 0, s, P, ldp, k, n, sums);
   return hipGetLastError();
 }
 

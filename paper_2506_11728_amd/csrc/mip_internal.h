@@ -122,9 +122,9 @@ hipError_t launch_im2col(const ConvGeom &g, int64_t rows, int64_t k, const uint8
 hipError_t launch_pack_b(int64_t k, int64_t n, const uint8_t *B, int64_t ldb, bool b_kc, uint8_t *P,
                          int64_t ldp, hipStream_t s, int64_t kfill = 0);
 
-// sums[j] = the sum of the kp bytes, read as signed 8-bit values, of column j of the
-// k-contiguous matrix P (pitch ldp; kp, ldp and P multiples of 16).
-hipError_t launch_column_sums(int64_t kp, int64_t n, const uint8_t *P, int64_t ldp, int32_t *sums,
+// sums[j] = the sum of the k bytes, read as signed 8-bit values, of column j of the
+// k-contiguous matrix P (pitch ldp; 16 bytes at a time where k, ldp and P are multiples of 16).
+hipError_t launch_column_sums(int64_t k, int64_t n, const uint8_t *P, int64_t ldp, int32_t *sums,
                               hipStream_t s);
 
 // The convolution (p.conv set, image unsigned, filters k-contiguous with pitch k) with the

@@ -182,7 +182,7 @@ int mipgemm_im2col_u8(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t hf,
 static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t wi, int64_t ci,
                     int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad, const int8_t *F,
                     const uint8_t *I, void *O, int mode, void *workspace, size_t workspace_bytes,
-                    void *stream) {
+                    void *stream, const int32_t *filter_sums = nullptr) {
   ConvCall c;
   int rc = conv_sizes(b, hi, wi, ci, co, true, hf, wf, stride, pad, &c);
   if (rc != 0) return rc;
@@ -197,6 +197,7 @@ static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t w
   Problem p = conv_problem(c, co, F, I, O, mode, true, nullptr, out_float, scale);
   const Route route = conv_route(c, p, &plan);
   p.conv = &c.geom;
+  p.ksum = filter_sums;  // the filters are the signed B of the lowered product: one sum per column
   if (route == ROUTE_TILES) return static_cast<int>(mip::launch_dma(p, plan.shape, plan.splits, s));
   if (route == ROUTE_ROWS) return static_cast<int>(mip::launch_conv_rows(p, s));
   const size_t need = written_out_bytes(c, co);
@@ -209,6 +210,7 @@ static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t w
   hipError_t e = mip::launch_im2col(c.geom, c.rows, c.k, I, Mp, c.kp, s, c.kp);
   if (e != hipSuccess) return static_cast<int>(e);
   p = conv_problem(c, co, F, I, O, mode, false, Mp, out_float, scale);
+  p.ksum = filter_sums;
   if (c.kp == c.k && reinterpret_cast<uintptr_t>(F) % 16 == 0) {
     p.B = F;  // the filters can be streamed where they are
     p.b_sn = c.k;
@@ -226,6 +228,35 @@ int mipgemm_conv_s8u8s32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t 
                          void *stream) {
   return run_conv(0, 1.0f, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
                   workspace_bytes, stream);
+}
+
+int mipgemm_conv_filter_sums(int64_t co, int64_t k, const int8_t *F, int32_t *sums, void *stream) {
+  if (co < 0 || co >= ((int64_t)1 << 31)) return -1;
+  if (k < 0 || k >= ((int64_t)1 << 31)) return -2;
+  if (!F && co > 0 && k > 0) return -3;
+  if (!sums && co > 0) return -4;
+  return static_cast<int>(mip::launch_column_sums(k, co, reinterpret_cast<const uint8_t *>(F), k, sums,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
+int mipgemm_conv_s8u8s32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
+                                   int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                                   const int8_t *F, const uint8_t *I, int32_t *O, int mode,
+                                   void *workspace, size_t workspace_bytes, void *stream,
+                                   const int32_t *filter_sums) {
+  if (!filter_sums && co > 0) return -17;
+  return run_conv(0, 1.0f, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream, filter_sums);
+}
+
+int mipgemm_conv_s8u8f32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co,
+                                   int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                                   const int8_t *F, const uint8_t *I, float *O, int mode,
+                                   void *workspace, size_t workspace_bytes, void *stream, float scale,
+                                   const int32_t *filter_sums) {
+  if (!filter_sums && co > 0) return -18;
+  return run_conv(1, scale, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream, filter_sums);
 }
 
 int mipgemm_conv_s8u8f32(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,

@@ -413,3 +413,102 @@ def test_seeded_sweep_of_random_convolutions(gpu, oracle):
             got = run_conv(gpu, shape, I, F, O0, mode, MIPGEMM_CONV=route)
             assert np.array_equal(got, want), (shape, mode, route, name)
         done += 1
+
+
+# ---------------------------------------------------------------------------
+# the filters' k-sums supplied (mipgemm_conv_filter_sums, mipgemm_conv_*_with_sums)
+# ---------------------------------------------------------------------------
+
+def _filter_sums(M, oracle, F):
+    """The sums on the device, checked against the oracle's column sums of the filter matrix
+    (c_o columns of k = h_f w_f c_i signed bytes, k contiguous)."""
+    import torch
+    co, k = F.shape[0], int(np.prod(F.shape[1:]))
+    dF = torch.from_numpy(F.view(np.uint8)).cuda()
+    dS = torch.full((co + 4,), 0x55555555, dtype=torch.int32, device="cuda")
+    M.mipgemm_conv_filter_sums(co, k, dF, dS)
+    torch.cuda.synchronize()
+    got = dS.cpu().numpy()
+    want = oracle.column_sums(k, co, F.reshape(-1), k, oracle.COL_MAJOR)
+    assert np.array_equal(got[:co], want) and (got[co:] == 0x55555555).all()
+    return dS
+
+
+def _run_conv_with_sums(M, shape, I, F, O0, mode, dS, **env):
+    import torch
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    dI, dF = torch.from_numpy(I).cuda(), torch.from_numpy(F.view(np.uint8)).cuda()
+    dO = torch.from_numpy(O0.copy()).cuda()
+    with Env(**env):
+        need = M.mipgemm_conv_workspace_size(*shape)
+        ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda") if need else None
+        M.mipgemm_conv_s8u8s32_with_sums(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, mode, dS,
+                                         workspace=ws, workspace_bytes=need)
+    torch.cuda.synchronize()
+    return dO.cpu().numpy()
+
+
+@pytest.mark.parametrize("path", ["implicit", "im2col"])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_with_filter_sums(gpu, oracle, shape, mode, path):
+    print("conv with sums", shape, "mode", mode, "path", path, flush=True)
+    I, F = tensors(shape, 1)
+    dS = _filter_sums(gpu, oracle, F)
+    ho = oracle.conv_out_extent(shape[1], shape[5], shape[7], shape[8])
+    wo = oracle.conv_out_extent(shape[2], shape[6], shape[7], shape[8])
+    rng = np.random.default_rng(3)
+    O0 = rng.integers(-1000, 1000, size=(shape[0], ho, wo, shape[4]), dtype=np.int32)
+    want = oracle.conv_direct(I, F, shape[7], shape[8], O=O0.copy() if mode else None, mode=mode)
+    got = _run_conv_with_sums(gpu, shape, I, F, O0, mode, dS,
+                              MIPGEMM_CONV=None if path == "implicit" else "im2col")
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("variant,splits", [("dma256", None), ("dma128", None), ("dma64", None), ("dma64", 3),
+                                            ("dma64x256", None), ("dma256x64", None), ("dma128x64", None),
+                                            ("dma64x128", None)])
+def test_conv_with_filter_sums_under_every_tile_shape(gpu, oracle, variant, splits):
+    """The gathering tile kernel in its form that takes the sums (and, with split k, the form
+    that ignores them), ragged tiles in both dimensions."""
+    shape = (1, 17, 23, 64, 96, 3, 5, 2, 2)
+    I, F = tensors(shape, 2)
+    dS = _filter_sums(gpu, oracle, F)
+    want = oracle.conv_direct(I, F, shape[7], shape[8])
+    with Env(MIPGEMM_VARIANT=variant, MIPGEMM_SPLITK=splits):
+        assert gpu.mipgemm_conv_variant_name(*shape) == "implicit:mfma_" + variant
+    got = _run_conv_with_sums(gpu, shape, I, F, np.full(want.shape, 77, dtype=np.int32), 0, dS,
+                              MIPGEMM_VARIANT=variant, MIPGEMM_SPLITK=splits)
+    assert np.array_equal(got, want)
+
+
+def test_conv_with_filter_sums_odd_channels_and_float_output(gpu, oracle):
+    """Routes that compute their own sums (row-segment kernel), filters whose k is not a multiple
+    of 16 (byte-wise sums), and the float-output form."""
+    import torch
+    for shape in ((2, 20, 300, 3, 10, 3, 3, 1, 1), (1, 12, 12, 24, 70, 3, 3, 1, 1)):
+        I, F = tensors(shape, 5)
+        dS = _filter_sums(gpu, oracle, F)
+        want = oracle.conv_direct(I, F, shape[7], shape[8])
+        got = _run_conv_with_sums(gpu, shape, I, F, np.zeros(want.shape, dtype=np.int32), 0, dS)
+        assert np.array_equal(got, want)
+    shape = (2, 14, 14, 64, 96, 3, 3, 1, 1)
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    I, F = tensors(shape, 6)
+    dS = _filter_sums(gpu, oracle, F)
+    scale = np.float32(0.0123)
+    S = oracle.conv_direct(I, F, s, p)
+    want = (S.astype(np.float32) * scale).astype(np.float32)       # int -> float32, one float32 multiply
+    dO = torch.zeros(S.size, dtype=torch.float32, device="cuda")
+    gpu.mipgemm_conv_s8u8f32_with_sums(b, hi, wi, ci, co, hf, wf, s, p, torch.from_numpy(F.view(np.uint8)).cuda(),
+                                       torch.from_numpy(I).cuda(), dO, 0, dS, scale=float(scale))
+    torch.cuda.synchronize()
+    assert np.array_equal(dO.cpu().numpy(), want.reshape(-1))
+    # a null pointer for the sums is argument 17
+    dI = torch.from_numpy(I).cuda()
+    dF = torch.from_numpy(F.view(np.uint8)).cuda()
+    dOi = torch.full((S.size,), 5, dtype=torch.int32, device="cuda")
+    assert gpu.mipgemm_conv_s8u8s32_with_sums(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dOi, 0, None,
+                                              check=False) == -17
+    torch.cuda.synchronize()
+    assert (dOi.cpu().numpy() == 5).all()
