@@ -135,16 +135,23 @@ def copy_calibration():
     print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
 
 
-def time_case(M, case, steps, warmup, dequant=False):
+def time_case(M, case, steps, warmup, dequant=False, requant=False):
     """Average milliseconds per call, operands resident, events on the launch stream.
 
-    dequant: time the float-output entry point (scale fused into the write-back) instead."""
+    dequant: time the float-output entry point (scale fused into the write-back) instead;
+    requant: the int8-output entry point (the sum requantised for the next layer)."""
     import torch
     ops = W.materialize(case)
     dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
     dB = torch.from_numpy(ops.B.view(np.uint8)).cuda()
     stream = torch.cuda.current_stream()
-    if dequant:
+    if requant:
+        dC = torch.zeros(ops.C.size, dtype=torch.int8, device="cuda")      # ldc counts bytes here
+        entry = getattr(M, "mipgemm_" + case.entry.replace("s32", "s8"))
+
+        def fn(*a, **kw):
+            return entry(*a, scale=0.00013, **kw)
+    elif dequant:
         dC = torch.zeros(ops.C.size, dtype=torch.float32, device="cuda")
         entry = getattr(M, "mipgemm_" + case.entry.replace("s32", "f32"))
 
@@ -238,18 +245,20 @@ def run_suite(M, args):
             case.algorithmic_bytes / cold / 1e3,
             "mfma" if t_mfma >= t_hbm else "hbm", max(t_mfma, t_hbm) / (cold * 1e-6)), flush=True)
     print()
-    print("Float output with the dequantising scale fused into the write-back (f32 entry points;")
-    print("no split k there, float sums are not combined out of order):")
+    print("Float output with the dequantising scale fused into the write-back (f32 entry points), and int8")
+    print("output requantised for the next layer (s8 entry points, a quarter of the bytes of C); no split k")
+    print("without a workspace there (float sums are not combined out of order); eager launches:")
     print()
-    print("| case | entry | us (s32) | us (f32) |")
-    print("|---|---|---|---|")
-    for name in ("c2_8192_rand", "c2_4096_rand", "c3_b32_64x100352x576", "c3_b32_256x6272x2304",
-                 "c4_enc_1024x3072x768", "c4_dec_16x4096x4096"):
+    print("| case | entry | us (s32) | us (f32) | us (s8) |")
+    print("|---|---|---|---|---|")
+    for name in ("c2_8192_rand", "c2_4096_rand", "c3_b32_64x100352x576", "c3_b32_128x25088x1152",
+                 "c3_b32_256x6272x2304", "c3_b32_2048x1568x512", "c4_enc_1024x3072x768", "c4_dec_16x4096x4096"):
         case = next(c for c in W.all_cases() if c.name == name)
         a = time_case(M, case, args.steps, args.warmup)
         b = time_case(M, case, args.steps, args.warmup, dequant=True)
-        print("| %s | %s | %.1f | %.1f |" % (name, case.entry.replace("s32", "f32"), a * 1e3, b * 1e3),
-              flush=True)
+        q = time_case(M, case, args.steps, args.warmup, requant=True)
+        print("| %s | %s | %.1f | %.1f | %.1f |" % (name, case.entry.replace("s32", "f32"), a * 1e3, b * 1e3,
+                                                    q * 1e3), flush=True)
 
 
 def run_packed_table(M):
@@ -375,11 +384,12 @@ def run_network_table(M):
     print("u8 activations x s8 filters -> s32, each layer on its own synthetic tensors:")
     print()
     print("| batch | us, all convolutions | of which the 7 x 7 stem (3 channels: row-segment kernel) | GMAC | TOPS "
-          "| us with the filters' k-sums supplied (computed once) | TOPS |")
-    print("|---|---|---|---|---|---|---|")
+          "| us with the filters' k-sums supplied (computed once) | TOPS "
+          "| us with the sums and an int8 output (requantised for the next layer) | TOPS |")
+    print("|---|---|---|---|---|---|---|---|---|")
     layers = W.resnet50_conv_layers()
     for b in W.CONV_BATCHES:
-        calls, calls_sums, macs, stem_call = [], [], 0, None
+        calls, calls_sums, calls_q8, macs, stem_call = [], [], [], 0, None
         for name, geo, count in layers:
             hi, ci, co, hf, stride, pad = geo
             image, filt = W.conv_tensors(b, geo)
@@ -397,8 +407,13 @@ def run_network_table(M):
             call_sums = (lambda args=args, dF=dF, dI=dI, dO=dO, ws=ws, need=need, dS=dS:
                          M.mipgemm_conv_s8u8s32_with_sums(*args, dF, dI, dO, W.OVERWRITE, dS, workspace=ws,
                                                           workspace_bytes=need))
+            dQ = torch.zeros(b * ho * ho * co, dtype=torch.int8, device="cuda")
+            call_q8 = (lambda args=args, dF=dF, dI=dI, dQ=dQ, ws=ws, need=need, dS=dS:
+                       M.mipgemm_conv_s8u8s8(*args, dF, dI, dQ, W.OVERWRITE, dS, workspace=ws,
+                                             workspace_bytes=need, scale=0.0004))
             calls += [call] * count
             calls_sums += [call_sums] * count
+            calls_q8 += [call_q8] * count
             macs += count * b * ho * ho * co * ci * hf * hf
             if name == "stem":
                 stem_call = call
@@ -425,8 +440,10 @@ def run_network_table(M):
         total = timed(calls, 2)
         stem = timed([stem_call], 8)
         total_sums = timed(calls_sums, 2)
-        print("| %d | %.0f | %.0f | %.2f | %.1f | %.0f | %.1f |" % (b, total, stem, macs / 1e9, 2 * macs / total / 1e6,
-                                                                 total_sums, 2 * macs / total_sums / 1e6), flush=True)
+        total_q8 = timed(calls_q8, 2)
+        print("| %d | %.0f | %.0f | %.2f | %.1f | %.0f | %.1f | %.0f | %.1f |" % (
+            b, total, stem, macs / 1e9, 2 * macs / total / 1e6, total_sums, 2 * macs / total_sums / 1e6,
+            total_q8, 2 * macs / total_q8 / 1e6), flush=True)
 
 
 def run_pack_table(M):

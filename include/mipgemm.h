@@ -370,6 +370,22 @@ int mipgemm_conv_s8u8f32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci
                                    void *stream, float scale, const int32_t *filter_sums);
 
 /*
+ * The convolution with an int8 output requantised for the next quantized layer, as
+ * mipgemm_s8u8s8 does for a GEMM: O(g, oy, ox, o) = clip(rint(scale * sum), -128, 127),
+ * the sum converted to float32, one float32 multiplication, ties to even, O a tensor
+ * of b x h_o x w_o x c_o BYTES.  At large batch most layers are bound by the write of
+ * their output, which this form cuts to a quarter.  `mode` must be MIPGEMM_OVERWRITE
+ * (-13); `scale` (argument 17) must be finite; `filter_sums` (argument 18) is the result
+ * of mipgemm_conv_filter_sums or NULL.  Workspace as for mipgemm_conv_s8u8s32.
+ */
+int mipgemm_conv_s8u8s8(int64_t b, int64_t hi, int64_t wi, int64_t ci,
+                        int64_t co, int64_t hf, int64_t wf, int64_t stride, int64_t pad,
+                        const int8_t *F, const uint8_t *I, int8_t *O,
+                        int mode,
+                        void *workspace, size_t workspace_bytes,
+                        void *stream, float scale, const int32_t *filter_sums);
+
+/*
  * Bytes of workspace mipgemm_conv_s8u8s32 / mipgemm_conv_s8u8f32 need for these sizes when its pointers
  * are 16-byte aligned: 0 when the augmented matrix is gathered on the fly (see
  * above), else room for it.  Returns 0 for invalid sizes.

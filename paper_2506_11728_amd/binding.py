@@ -54,7 +54,7 @@ def exported_symbols():
             "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8",
             "mipgemm_packed_weights_bytes", "mipgemm_pack_weights", "mipgemm_s8s8s32_packed",
             "mipgemm_u8s8s32_packed", "mipgemm_conv_filter_sums",
-            "mipgemm_conv_s8u8s32_with_sums", "mipgemm_conv_s8u8f32_with_sums"]
+            "mipgemm_conv_s8u8s32_with_sums", "mipgemm_conv_s8u8f32_with_sums", "mipgemm_conv_s8u8s8"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -104,6 +104,9 @@ def load_library() -> ctypes.CDLL:
             lib.mipgemm_conv_s8u8f32_with_sums.restype = ctypes.c_int
             lib.mipgemm_conv_s8u8f32_with_sums.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
                                                                        ctypes.c_size_t, vp, ctypes.c_float, vp]
+            lib.mipgemm_conv_s8u8s8.restype = ctypes.c_int
+            lib.mipgemm_conv_s8u8s8.argtypes = [i64] * 9 + [vp, vp, vp, ctypes.c_int, vp,
+                                                            ctypes.c_size_t, vp, ctypes.c_float, vp]
             lib.mipgemm_conv_workspace_size.restype = ctypes.c_size_t
             lib.mipgemm_conv_workspace_size.argtypes = [i64] * 9
             lib.mipgemm_conv_workspace_size_unaligned.restype = ctypes.c_size_t
@@ -284,6 +287,17 @@ def mipgemm_conv_s8u8f32_with_sums(b, hi, wi, ci, co, hf, wf, stride, pad, F, I,
                                    workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
     """mipgemm_conv_s8u8f32 with the filters' k-sums supplied."""
     rc = load_library().mipgemm_conv_s8u8f32_with_sums(
+        b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
+        _ptr(workspace), workspace_bytes, _stream(stream), scale, _ptr(filter_sums))
+    if check and rc != 0:
+        raise MipGemmError(rc, mipgemm_strerror(rc))
+    return rc
+
+
+def mipgemm_conv_s8u8s8(b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, filter_sums=None,
+                        workspace=None, workspace_bytes=0, stream=None, scale=1.0, check=True):
+    """O (int8) = clip(rint(scale * CONV(F, I))): the lowered convolution requantised for the next layer."""
+    rc = load_library().mipgemm_conv_s8u8s8(
         b, hi, wi, ci, co, hf, wf, stride, pad, _ptr(F), _ptr(I), _ptr(O), mode,
         _ptr(workspace), workspace_bytes, _stream(stream), scale, _ptr(filter_sums))
     if check and rc != 0:

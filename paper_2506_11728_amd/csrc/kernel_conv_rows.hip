@@ -300,7 +300,10 @@ __global__ __launch_bounds__(NTHREADS_ROWS) void conv_rows_kernel(RowsParams P) 
     if (oxw < P.G.wo) {
       int32_t *C = P.O + (T.orow * P.G.wo + oxw) * (int64_t)P.n + n0;
       const int rows = P.G.wo - oxw < 32 ? P.G.wo - oxw : 32;
-      if (P.n - n0 >= TN)  // all 64 filters: full lines through the wave's LDS patch
+      if (P.out_float == 2) {  // int8 output (overwrite only): O is a tensor of bytes
+        int8_t *Q = reinterpret_cast<int8_t *>(P.O) + (T.orow * P.G.wo + oxw) * (int64_t)P.n + n0;
+        store_blocks_q8<1, 2>(acc, Q, P.n, rows, P.n - n0, lane, P.scale);
+      } else if (P.n - n0 >= TN)  // all 64 filters: full lines through the wave's LDS patch
         store_rows_via_lds(acc, C, P.n, rows, ACCUMULATE, lane, patch, fin);
       else
         store_blocks<1, 2, false>(acc, C, P.n, rows, P.n - n0, ACCUMULATE, lane, fin);
@@ -401,7 +404,10 @@ hipError_t launch_conv_rows(const Problem &p, hipStream_t s) {
   dim3 grid((unsigned)wgs, (unsigned)((P.n + TN - 1) / TN), 1);
   const size_t lds = 2 * (size_t)P.stage_bytes + (size_t)P.ksteps * 2048 + FIXED_LDS;
   const dim3 block(NTHREADS_ROWS);
-  if (P.out_float && P.accumulate) hipLaunchKernelGGL((conv_rows_kernel<true, true>), grid, block, lds, s, P);
+  if (P.out_float == 2) {  // (the integer instance: its int8 branch is taken at run time)
+    if (P.accumulate) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_rows_kernel<false, false>), grid, block, lds, s, P);
+  } else if (P.out_float && P.accumulate) hipLaunchKernelGGL((conv_rows_kernel<true, true>), grid, block, lds, s, P);
   else if (P.out_float) hipLaunchKernelGGL((conv_rows_kernel<true, false>), grid, block, lds, s, P);
   else if (P.accumulate) hipLaunchKernelGGL((conv_rows_kernel<false, true>), grid, block, lds, s, P);
   else hipLaunchKernelGGL((conv_rows_kernel<false, false>), grid, block, lds, s, P);

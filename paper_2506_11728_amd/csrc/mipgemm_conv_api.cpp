@@ -190,6 +190,7 @@ static int run_conv(int out_float, float scale, int64_t b, int64_t hi, int64_t w
   if (!I && b > 0) return -11;
   if (!O && c.rows > 0 && co > 0) return -12;
   if (mode != MIPGEMM_OVERWRITE && mode != MIPGEMM_ACCUMULATE) return -13;
+  if (out_float == 2 && mode != MIPGEMM_OVERWRITE) return -13;  // a quantized output has no running sum
   if (out_float && (!(scale == scale) || scale - scale != 0.0f)) return -17;  // NaN or infinity
   if (c.rows == 0 || co == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -256,6 +257,14 @@ int mipgemm_conv_s8u8f32_with_sums(int64_t b, int64_t hi, int64_t wi, int64_t ci
                                    const int32_t *filter_sums) {
   if (!filter_sums && co > 0) return -18;
   return run_conv(1, scale, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
+                  workspace_bytes, stream, filter_sums);
+}
+
+int mipgemm_conv_s8u8s8(int64_t b, int64_t hi, int64_t wi, int64_t ci, int64_t co, int64_t hf,
+                        int64_t wf, int64_t stride, int64_t pad, const int8_t *F, const uint8_t *I,
+                        int8_t *O, int mode, void *workspace, size_t workspace_bytes, void *stream,
+                        float scale, const int32_t *filter_sums) {
+  return run_conv(2, scale, b, hi, wi, ci, co, hf, wf, stride, pad, F, I, O, mode, workspace,
                   workspace_bytes, stream, filter_sums);
 }
 

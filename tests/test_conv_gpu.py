@@ -512,3 +512,51 @@ def test_conv_with_filter_sums_odd_channels_and_float_output(gpu, oracle):
                                               check=False) == -17
     torch.cuda.synchronize()
     assert (dOi.cpu().numpy() == 5).all()
+
+
+# ---------------------------------------------------------------------------
+# int8 output requantised for the next layer (mipgemm_conv_s8u8s8)
+# ---------------------------------------------------------------------------
+
+def _conv_requant_oracle(oracle, shape, I, F, scale):
+    """clip(rint(scale * conv)) through two pinned oracle functions: the augmented matrix, then
+    the requantising GEMM oracle on it (O is the column-major c_o x (b h_o w_o) result)."""
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    Mx = oracle.im2col_u8(I, hf, wf, s, p)                 # rows = output positions, k contiguous
+    rows, k = Mx.shape
+    Q = np.zeros(rows * co, dtype=np.int8)
+    oracle.gemm_requant(False, True, co, rows, k, F.reshape(-1), k, oracle.ROW_MAJOR,
+                        Mx.reshape(-1), k, oracle.COL_MAJOR, scale, Q, co, oracle.COL_MAJOR)
+    return Q
+
+
+@pytest.mark.parametrize("env", [{}, {"MIPGEMM_CONV": "im2col"}], ids=["as_dispatched", "written_out"])
+@pytest.mark.parametrize("shape", CONV_SHAPES + ROWS_SHAPES[:6], ids=lambda s: "x".join(map(str, s)))
+def test_conv_with_int8_output(gpu, oracle, shape, env):
+    import torch
+    print("conv s8 out", shape, env, flush=True)
+    b, hi, wi, ci, co, hf, wf, s, p = shape
+    I, F = tensors(shape, 7)
+    S = oracle.conv_direct(I, F, s, p)
+    scale = np.float32(100.0 / max(1.0, float(np.percentile(np.abs(S), 90))))   # about a tenth saturates
+    want = _conv_requant_oracle(oracle, shape, I, F, scale)
+    assert (want == 127).any() or (want == -128).any() or S.size < 50
+    dI, dF = torch.from_numpy(I).cuda(), torch.from_numpy(F.view(np.uint8)).cuda()
+    for with_sums in (False, True):
+        dS = _filter_sums(gpu, oracle, F) if with_sums else None
+        dO = torch.full((S.size + 32,), 0x11, dtype=torch.int8, device="cuda")
+        with Env(**env):
+            need = max(gpu.mipgemm_conv_workspace_size(*shape), gpu.mipgemm_conv_workspace_size_unaligned(*shape))
+            ws = torch.zeros(need, dtype=torch.uint8, device="cuda") if need else None
+            gpu.mipgemm_conv_s8u8s8(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 0, dS, workspace=ws,
+                                    workspace_bytes=need, scale=float(scale))
+        torch.cuda.synchronize()
+        got = dO.cpu().numpy()
+        assert np.array_equal(got[:S.size], want), "with_sums=%s" % with_sums
+        assert (got[S.size:] == 0x11).all()
+    # accumulate mode is rejected, nothing touched
+    dO = torch.full((S.size,), 0x11, dtype=torch.int8, device="cuda")
+    assert gpu.mipgemm_conv_s8u8s8(b, hi, wi, ci, co, hf, wf, s, p, dF, dI, dO, 1, None, scale=1.0,
+                                   check=False) == -13
+    torch.cuda.synchronize()
+    assert (dO.cpu().numpy() == 0x11).all()
