@@ -54,6 +54,8 @@
  *     MIPGEMM_SPLITK   number of k ranges of the tile kernels
  *     MIPGEMM_PACK     "always" / "never": the packed route whenever / never
  *     MIPGEMM_CONV     "im2col" / "rows": the convolution route
+ *     MIPGEMM_STAGGER  10 ns ticks by which the tile rows of an XCD's patch start apart
+ *                      in the kernel for large problems (tuning runs)
  *
  * Return value.  0 on success.  A negative value -i means that the i-th
  * argument (counted from 1 in the order of the prototype) is invalid: a

@@ -442,7 +442,7 @@ def mipgemm_variant_name_for_mode(m, n, k, lda, orderA, ldb, orderB, ldc, orderC
 
 def mipgemm_set_tuning(name: str, value) -> None:
     """Sets one of the dispatcher's tuning values (MIPGEMM_VARIANT, MIPGEMM_SPLITK, MIPGEMM_PACK,
-    MIPGEMM_CONV) for the whole process; None or "" clears it."""
+    MIPGEMM_CONV, MIPGEMM_STAGGER) for the whole process; None or "" clears it."""
     rc = load_library().mipgemm_set_tuning(name.encode(), None if value is None else str(value).encode())
     if rc != 0:
         raise ValueError("mipgemm_set_tuning(%r, %r) rejected" % (name, value))

@@ -11,6 +11,7 @@
 // multiplied, the write-back stops at the edge of C.
 #include "dma_common.h"
 #include "epilogue16.h"
+#include "tuning.h"
 
 namespace mip {
 
@@ -432,6 +433,7 @@ hipError_t launch_for(const Problem &p, hipStream_t s, unsigned long long *clock
   // form, two workgroups to a compute unit and a short write-back, starts all at once)
   P.first_round = (int)compute_units();
   P.stagger_ticks = BM == DM && ntiles >= 2 * P.first_round ? STAGGER_TICKS : 0;
+  if (tuning().stagger >= 0 && BM == DM) P.stagger_ticks = tuning().stagger;  // tuning runs
   const size_t lds = (size_t)Tile16<BM, BN>::LDS_BYTES;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);

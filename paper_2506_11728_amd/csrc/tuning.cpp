@@ -36,6 +36,12 @@ bool apply(Tuning *t, const char *name, const char *value) {
     else return false;
     return true;
   }
+  if (!std::strcmp(name, "MIPGEMM_STAGGER")) {
+    const int n = std::atoi(v);
+    if (*v && (n < 0 || n > 100000)) return false;
+    t->stagger = *v ? n : -1;
+    return true;
+  }
   if (!std::strcmp(name, "MIPGEMM_CONV")) {
     if (!*v) t->conv = 0;
     else if (!std::strcmp(v, "im2col")) t->conv = 1;
@@ -48,7 +54,7 @@ bool apply(Tuning *t, const char *name, const char *value) {
 
 const Tuning *from_environment() {
   Tuning *t = new Tuning();
-  for (const char *name : {"MIPGEMM_VARIANT", "MIPGEMM_SPLITK", "MIPGEMM_PACK", "MIPGEMM_CONV"})
+  for (const char *name : {"MIPGEMM_VARIANT", "MIPGEMM_SPLITK", "MIPGEMM_PACK", "MIPGEMM_CONV", "MIPGEMM_STAGGER"})
     if (const char *v = std::getenv(name)) (void)apply(t, name, v);  // an unparsable value is ignored
   return t;
 }

@@ -12,6 +12,8 @@ struct Tuning {
   int splitk = 0;         // MIPGEMM_SPLITK: 0 = the dispatcher decides
   int pack = 0;           // MIPGEMM_PACK: 0 by size, 1 "always", -1 "never"
   int conv = 0;           // MIPGEMM_CONV: 0 by shape, 1 "im2col", 2 "rows"
+  int stagger = -1;       // MIPGEMM_STAGGER: 10 ns ticks between the tile rows of an XCD's patch in the
+                          // kernel for large problems; -1 = the built-in value
 };
 
 // The current set: immutable, valid for the life of the process.

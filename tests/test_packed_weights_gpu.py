@@ -176,3 +176,47 @@ def test_packed_weights_error_paths_touch_nothing(gpu):
     assert gpu.mipgemm_s8s8s32_packed(m, n, k, dA, k, R, dP, dC, n, R, 3, check=False) == -11
     torch.cuda.synchronize()
     assert (dC.cpu().numpy() == 9).all()
+
+
+def test_packed_weights_seeded_sweep(gpu, oracle):
+    """Forty random products as dispatched: sizes from a few rows to several tiles, ragged or
+    whole, both signednesses of A, every order of A, B and C, both modes, aligned and padded ld."""
+    rng = np.random.default_rng(20260)
+    for i in range(40):
+        m = int(rng.choice([1, 3, 16, 40, 64, 100, 128, 200, 256, 333, 512]))
+        n = int(rng.choice([16, 48, 64, 100, 128, 256, 300, 384, 512, 1000]))
+        k = int(rng.choice([64, 128, 192, 256, 320, 512, 1024, 1088, 2048, 77, 500]))
+        pad = int(rng.choice([0, 0, 16, 5]))
+        _check_gemm(gpu, oracle, m, n, k, bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
+                    int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2)), pad, "auto",
+                    seed=100 + i)
+
+
+def test_packed_weights_replay_from_a_hip_graph(gpu, oracle):
+    """A captured u8 x s8 call on packed weights gives the oracle's result on every replay."""
+    import torch
+    m, n, k = 256, 384, 1024
+    dense, flatB, ldb = _weights(k, n, W.ROW_MAJOR, 0, 21)
+    case = W.Case("packed_graph", 8, 21, m, n, k, a_unsigned=True, a_dist=("uniform", 0, 255), seed=21)
+    ops = W.materialize(case)
+    want = ops.C.copy()
+    oracle.gemm(True, False, m, n, k, ops.A, case.lda, 0, flatB, ldb, 0, want, case.ldc, 0, W.OVERWRITE)
+    dP, _ = _pack_on_gpu(gpu, k, n, flatB, ldb, W.ROW_MAJOR)
+    dA = torch.from_numpy(ops.A.view(np.uint8)).cuda()
+    dC = torch.from_numpy(ops.C).cuda()
+
+    def call():
+        gpu.mipgemm_u8s8s32_packed(m, n, k, dA, case.lda, 0, dP, dC, case.ldc, 0, W.OVERWRITE)
+
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for replay in range(3):
+        dC.fill_(replay + 11)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy(), want), "replay %d" % replay
