@@ -54,7 +54,7 @@ const char *plan_name(const Plan &plan) {
     case KIND_STAGED: return staged[plan.shape];
     case KIND_DMA: return dma[plan.shape];
     case KIND_DMA_K128: return plan.shape == SHAPE_128 ? "mfma_dma128_k128" : "mfma_dma256_k128";
-    case KIND_SLAB: return plan.splits == 2 ? "mfma_slab32" : "mfma_slab16";
+    case KIND_SLAB: return plan.splits == 4 ? "mfma_slab64" : (plan.splits == 2 ? "mfma_slab32" : "mfma_slab16");
     default: return "?";
   }
 }
@@ -80,8 +80,8 @@ static bool forced_plan(const Problem &p, Plan *plan) {
     *plan = {KIND_DMA_K128, SHAPE_128, 1};
     return true;
   }
-  if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32")) {
-    const int nt = e[4] == '3' ? 2 : 1;
+  if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32") || !std::strcmp(e, "slab64")) {
+    const int nt = e[4] == '6' ? 4 : (e[4] == '3' ? 2 : 1);
     if (!slab_eligible(p, nt)) return false;
     *plan = {KIND_SLAB, SHAPE_64, nt};
     return true;
@@ -253,8 +253,15 @@ Plan choose_plan(const Problem &p) {
     // (1, 1024, 2048) 4.9/5.6 -> 3.6/4.5, (16, 2048, 2048) 5.3/6.1 -> 4.5/5.5,
     // (64, 4096, 1024) 6.3/7.2 -> 5.1/5.7.
     const bool short_k = p.k * (p.m > 16 ? p.m : 16) <= 65536 && (p.b_sk == 1 || p.k <= 2048);
+    // Slabs of 64 columns re-read A a quarter as often, which is what several rows of A cost a
+    // narrow slab; they need n / 64 workgroups to be enough.  Measured on a k-contiguous B, us
+    // warm/cold against the narrower choice: (16, 11008, 4096) 14.2/16.2 -> 12.1/15.1,
+    // (16, 16384, 4096) 14.8/19.6 -> 13.2/18.0, (16, 32000, 4096) 26.7/33.0 -> 22.6/31.8,
+    // (1, 16384, 4096) 12.6/18.3 -> 12.3/17.1; not (1, 11008, 4096) 10.4/12.2 -> 10.5/12.8, nor
+    // n = 4096 at any m (64 workgroups: (16, 4096, 4096) 6.3/8.2 -> 11.2/13.1).
+    const bool slabs_of_64 = slab_eligible(p, 4) && p.n / 64 >= 160 && (p.m > 4 || p.n / 64 >= 256);
     if (slab_ok && p.b_sk == 1 && p.m <= 16 && p.n / 16 >= 192)
-      plan = {KIND_SLAB, SHAPE_64, wide_slabs ? 2 : 1};
+      plan = {KIND_SLAB, SHAPE_64, slabs_of_64 ? 4 : (wide_slabs ? 2 : 1)};
     // (Float output cannot split k at all, sums of floats not being combined out of order:
     // there the slab kernel takes every such problem, whatever k.  Measured, us warm/cold:
     // (16, 2048, 8192) 17.8/29.2 -> 9.7/11.2, with a row-major B 17.7/35.3 -> 10.5/26.6;

@@ -4,7 +4,7 @@
 // by the matrix cores, and there are too few C tiles to give every compute unit
 // one.  The tiled kernels answer that by splitting k over workgroups, which costs
 // a zero-fill launch and atomic traffic on C.  Here a workgroup instead owns a
-// narrow slab of B, 16 or 32 columns wide and all of k deep, so that n / 16
+// narrow slab of B, 16, 32 or 64 columns wide and all of k deep, so that n / 16
 // workgroups exist and nothing is shared between them: one launch, plain stores.
 // Inside the workgroup the four waves split k (wave w takes the 64-deep steps
 // w, w + 4, ...), each wave streams its steps through a private ring in LDS with
@@ -26,8 +26,9 @@ namespace mip {
 
 namespace {
 
-constexpr int DB = 8;  // steps of B in flight per wave (memory latency)
 constexpr int DA = 4;  // steps of A in flight per wave (A is small: cache latency)
+// steps of B in flight per wave (memory latency): 8 KB of a narrow slab, 16 KB of a 64-column one
+constexpr int steps_of_b_in_flight(int nt) { return nt >= 4 ? 4 : 8; }
 
 struct SlabParams {
   const uint8_t *A, *B;
@@ -61,6 +62,7 @@ __device__ __forceinline__ void loads_landed() {  // all but the N newest direct
 template <int MT, int NT, bool B_KC, int UNS>
 __global__ __launch_bounds__(NTHREADS) void slab_kernel(SlabParams P) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  constexpr int DB = steps_of_b_in_flight(NT);
   constexpr int B_STEP = NT * 1024, A_STEP = MT * 1024;  // bytes of one 64-deep step
   constexpr int WAVE_BYTES = DB * B_STEP + DA * A_STEP;
 
@@ -261,7 +263,7 @@ void (*pick(bool b_kc, int uns))(SlabParams) {
 bool slab_eligible(const Problem &p, int nt) {
   if (p.conv || p.batch != 1 || p.m < 1 || p.m > 64 || p.a_sk != 1) return false;
   if (p.out_float == 2) return false;  // (no int8 write-back here)
-  if (nt != 1 && nt != 2) return false;
+  if (nt != 1 && nt != 2 && nt != 4) return false;
   if (p.n % (16 * nt) || p.k % 64 || p.k < 64) return false;
   if (p.b_sk != 1 && p.b_sn != 1) return false;
   const int64_t lda = p.a_sm, ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
@@ -291,8 +293,9 @@ hipError_t launch_slab(const Problem &p, int nt, hipStream_t s) {
   const int mt = p.m <= 16 ? 1 : (p.m <= 32 ? 2 : 4);
   void (*kern)(SlabParams) = nullptr;
   if (nt == 1) kern = mt == 1 ? pick<1, 1>(b_kc, uns) : (mt == 2 ? pick<2, 1>(b_kc, uns) : pick<4, 1>(b_kc, uns));
-  else kern = mt == 1 ? pick<1, 2>(b_kc, uns) : (mt == 2 ? pick<2, 2>(b_kc, uns) : pick<4, 2>(b_kc, uns));
-  const size_t lds = (size_t)4 * (DB * nt + DA * mt) * 1024;
+  else if (nt == 2) kern = mt == 1 ? pick<1, 2>(b_kc, uns) : (mt == 2 ? pick<2, 2>(b_kc, uns) : pick<4, 2>(b_kc, uns));
+  else kern = mt == 1 ? pick<1, 4>(b_kc, uns) : (mt == 2 ? pick<2, 4>(b_kc, uns) : pick<4, 4>(b_kc, uns));
+  const size_t lds = (size_t)4 * (steps_of_b_in_flight(nt) * nt + DA * mt) * 1024;
   {
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;

@@ -426,14 +426,15 @@ def test_deep_k_kernel_unsigned_and_accumulate(gpu, oracle, case):
 
 
 # ---------------------------------------------------------------------------
-# the skinny-m kernel: one workgroup per 16- or 32-column slab of B
+# the skinny-m kernel: one workgroup per 16-, 32- or 64-column slab of B
 # ---------------------------------------------------------------------------
 
 def _slab_cases():
     rng = np.random.default_rng(77)
     shapes = [(1, 4096, 4096), (16, 4096, 4096), (64, 4096, 4096), (1, 11008, 4096),
               (16, 4096, 11008), (64, 11008, 4096), (64, 3136, 576), (1, 16, 64), (64, 32, 64),
-              (3, 48, 128), (17, 80, 192), (33, 176, 1088), (48, 32, 2048), (5, 4112, 320)]
+              (3, 48, 128), (17, 80, 192), (33, 176, 1088), (48, 32, 2048), (5, 4112, 320),
+              (1, 64, 64), (9, 192, 4160), (40, 448, 704), (64, 128, 1024)]
     for _ in range(26):
         shapes.append((int(rng.integers(1, 65)), 16 * int(rng.integers(1, 40)),
                        64 * int(rng.integers(1, 24))))
@@ -452,12 +453,12 @@ def _slab_cases():
     return out
 
 
-@pytest.mark.parametrize("variant", ["slab16", "slab32", "auto"])
+@pytest.mark.parametrize("variant", ["slab16", "slab32", "slab64", "auto"])
 @pytest.mark.parametrize("case", _slab_cases(), ids=lambda c: c.name)
 def test_skinny_m_slab_kernel(gpu, oracle, case, variant):
     """Forced through either slab width, and as the dispatcher routes it (an accumulating call
     with a long k goes to tiles with split k instead)."""
-    width = 16 if variant == "slab16" else 32
+    width = {"slab16": 16, "slab32": 32, "slab64": 64}.get(variant, 0)
     if variant != "auto" and case.n % width == 0:
         with VariantEnv(variant):
             got = gpu.mipgemm_variant_name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb,
@@ -476,6 +477,9 @@ def test_skinny_m_slab_kernel_wraps(gpu, oracle):
     for variant in ("slab16", "slab32"):
         got = gpu_gemm(gpu, case, A, B, np.full(m * n, 7, dtype=np.int32), variant)
         assert (got == -2 ** 31).all()
+    case = W.Case("slab_wrap64", 8, 0, m, 64, k)
+    got = gpu_gemm(gpu, case, A, np.full(k * 64, -128, dtype=np.int8), np.full(m * 64, 7, dtype=np.int32), "slab64")
+    assert (got == -2 ** 31).all()
 
 
 def test_calls_replay_from_a_hip_graph(gpu, oracle):
