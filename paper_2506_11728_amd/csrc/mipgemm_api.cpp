@@ -250,14 +250,14 @@ int mipgemm_pack_weights(int64_t k, int64_t n, const int8_t *B, int64_t ldb, int
   if (e != hipSuccess) return static_cast<int>(e);
   if (k == 0 && n > 0) {  // nothing was moved: the one block of every column is all padding
     mip::Problem z;
-    z.m = 1; z.n = n * L.kp / 4; z.k = 0;
+    z.m = n; z.n = L.kp / 4; z.k = 0;  // one row of words per column
     z.C = reinterpret_cast<int32_t *>(body); z.ldc = z.n;
     e = mip::launch_fill_zero(z, s);
     if (e != hipSuccess) return static_cast<int>(e);
   }
   if (L.cols > n) {  // the added columns (a fill kernel, not a memset: the call may be under graph capture)
     mip::Problem z;
-    z.m = 1; z.n = (L.cols - n) * L.kp / 4; z.k = 0;
+    z.m = L.cols - n; z.n = L.kp / 4; z.k = 0;  // one row of words per column
     z.C = reinterpret_cast<int32_t *>(body + (size_t)n * (size_t)L.kp); z.ldc = z.n;
     e = mip::launch_fill_zero(z, s);
     if (e != hipSuccess) return static_cast<int>(e);
