@@ -223,3 +223,43 @@ int oracle_num_threads(void) { return omp_get_max_threads(); }
 #else
 int oracle_num_threads(void) { return 1; }
 #endif
+
+/*
+ * The same product with 16-bit operands, C (+)= A B with A and B of int16 and C of int32:
+ * the (i32, i16, i16) forms of the paper's table of matrix-oriented instructions
+ * (vpdpwssd, smopa).  Each int16 is widened to 32 bits before the multiply; products reach
+ * 2^30, so sums wrap modulo 2^32 much sooner than with bytes (same reading as above).
+ * lda, ldb count elements.
+ */
+int oracle_mip_gemm_s16(int64_t m, int64_t n, int64_t k,
+                        const int16_t *A, int64_t lda, int orderA,
+                        const int16_t *B, int64_t ldb, int orderB,
+                        int32_t *C, int64_t ldc, int orderC,
+                        int mode)
+{
+    if (m < 0 || n < 0 || k < 0) return -1;
+    if (orderA != ORACLE_ROW_MAJOR && orderA != ORACLE_COL_MAJOR) return -1;
+    if (orderB != ORACLE_ROW_MAJOR && orderB != ORACLE_COL_MAJOR) return -1;
+    if (orderC != ORACLE_ROW_MAJOR && orderC != ORACLE_COL_MAJOR) return -1;
+    if (mode != ORACLE_OVERWRITE && mode != ORACLE_ACCUMULATE) return -1;
+    if (lda < (orderA == ORACLE_ROW_MAJOR ? k : m)) return -1;
+    if (ldb < (orderB == ORACLE_ROW_MAJOR ? n : k)) return -1;
+    if (ldc < (orderC == ORACLE_ROW_MAJOR ? n : m)) return -1;
+
+    uint32_t *Cu = (uint32_t *)C;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        if (mode == ORACLE_OVERWRITE)
+            for (int64_t j = 0; j < n; ++j)
+                Cu[at(i, j, ldc, orderC)] = 0u;
+        for (int64_t p = 0; p < k; ++p) {
+            uint32_t a = (uint32_t)(int32_t)A[at(i, p, lda, orderA)];
+            for (int64_t j = 0; j < n; ++j) {
+                uint32_t b = (uint32_t)(int32_t)B[at(p, j, ldb, orderB)];
+                Cu[at(i, j, ldc, orderC)] += a * b;
+            }
+        }
+    }
+    return 0;
+}

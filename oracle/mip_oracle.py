@@ -52,6 +52,8 @@ def _load():
             lib.oracle_mip_gemm.argtypes = [ci, ci, i64, i64, i64,
                                             vp, i64, ci, vp, i64, ci,
                                             vp, i64, ci, ci]
+            lib.oracle_mip_gemm_s16.restype = ci
+            lib.oracle_mip_gemm_s16.argtypes = [i64, i64, i64, vp, i64, ci, vp, i64, ci, vp, i64, ci, ci]
             lib.oracle_mip_gemm_dequant.restype = ci
             lib.oracle_mip_gemm_dequant.argtypes = [ci, ci, i64, i64, i64, vp, i64, ci, vp, i64, ci,
                                                     ctypes.c_float, vp, i64, ci, ci, vp]
@@ -109,6 +111,28 @@ def gemm(a_unsigned, b_unsigned, m, n, k, A, lda, orderA, B, ldb, orderB,
         int(bool(a_unsigned)), int(bool(b_unsigned)), m, n, k,
         A.ctypes.data, lda, orderA, B.ctypes.data, ldb, orderB,
         C.ctypes.data, ldc, orderC, mode)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return C
+
+
+def gemm_s16(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode):
+    """C (m x n, int32) = [C +] A (m x k) * B (k x n) with int16 operands, in place on the flat
+    buffer ``C`` (the (i32, i16, i16) instruction forms of the paper's ISA table); sums wrap."""
+    A = np.asarray(A)
+    B = np.asarray(B)
+    if A.dtype != np.int16 or B.dtype != np.int16 or C.dtype != np.int32:
+        raise TypeError("operand dtypes do not match the entry point")
+    for X in (A, B, C):
+        if X.ndim != 1 or not X.flags.c_contiguous:
+            raise ValueError("operands must be flat contiguous buffers")
+    if not C.flags.writeable:
+        raise ValueError("C must be writeable")
+    if A.size < _min_len(m, k, lda, orderA) or B.size < _min_len(k, n, ldb, orderB) \
+            or C.size < _min_len(m, n, ldc, orderC):
+        raise ValueError("buffer shorter than the matrix it is said to hold")
+    rc = _load().oracle_mip_gemm_s16(m, n, k, A.ctypes.data, lda, orderA, B.ctypes.data, ldb, orderB,
+                                     C.ctypes.data, ldc, orderC, mode)
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return C

@@ -605,3 +605,94 @@ def test_requant_layouts_closed_forms_and_bad_scale(oracle):
     for bad in (float("nan"), float("inf")):
         with pytest.raises(ValueError):
             run_requant(oracle, A8, B8, bad)
+
+
+# ---------------------------------------------------------------------------
+# 16-bit operands (oracle_mip_gemm_s16)
+# ---------------------------------------------------------------------------
+
+def test_s16_hand_worked(oracle):
+    # A = [[300, -2], [-32768, 7]], B = [[1000, -1], [5, 32767]]
+    #   row 0: 300*1000 + (-2)*5 = 299990;      300*(-1) + (-2)*32767 = -65834
+    #   row 1: -32768*1000 + 7*5 = -32767965;   -32768*(-1) + 7*32767 = 262137
+    A = np.array([300, -2, -32768, 7], dtype=np.int16)
+    B = np.array([1000, -1, 5, 32767], dtype=np.int16)
+    C = np.full(4, 77, dtype=np.int32)
+    oracle.gemm_s16(2, 2, 2, A, 2, 0, B, 2, 0, C, 2, 0, oracle.OVERWRITE)
+    assert C.tolist() == [299990, -65834, -32767965, 262137]
+    oracle.gemm_s16(2, 2, 2, A, 2, 0, B, 2, 0, C, 2, 0, oracle.ACCUMULATE)
+    assert C.tolist() == [2 * 299990, 2 * -65834, 2 * -32767965, 2 * 262137]
+    # the same matrices stored column-major, result column-major
+    At = np.array([300, -32768, -2, 7], dtype=np.int16)
+    Bt = np.array([1000, 5, -1, 32767], dtype=np.int16)
+    Ct = np.zeros(4, dtype=np.int32)
+    oracle.gemm_s16(2, 2, 2, At, 2, 1, Bt, 2, 1, Ct, 2, 1, oracle.OVERWRITE)
+    assert Ct.tolist() == [299990, -32767965, -65834, 262137]
+
+
+def test_s16_wraps_and_closed_forms(oracle):
+    # (-32768)^2 = 2^30 per product: four of them are 2^32 = 0, three are 3 * 2^30 = -2^30 as int32
+    for k, want in ((1, 1 << 30), (2, -(1 << 31)), (3, -(1 << 30)), (4, 0), (7, -(1 << 30))):
+        A = np.full(k, -32768, dtype=np.int16)
+        C = np.zeros(1, dtype=np.int32)
+        oracle.gemm_s16(1, 1, k, A, k, 0, A, 1, 0, C, 1, 0, oracle.OVERWRITE)
+        assert C[0] == want
+    # all 32767: k * 32767^2 modulo 2^32
+    k = 100
+    A = np.full(3 * k, 32767, dtype=np.int16)
+    B = np.full(k * 2, 32767, dtype=np.int16)
+    C = np.zeros(6, dtype=np.int32)
+    oracle.gemm_s16(3, 2, k, A, k, 0, B, 2, 0, C, 2, 0, oracle.OVERWRITE)
+    want = (k * 32767 * 32767) % (1 << 32)
+    want = want - (1 << 32) if want >= (1 << 31) else want
+    assert (C == want).all()
+    C0 = np.arange(6, dtype=np.int32)
+    C = C0.copy()
+    oracle.gemm_s16(3, 2, 0, A, 1, 0, B, 2, 0, C, 2, 0, oracle.ACCUMULATE)      # k = 0: nothing added
+    assert np.array_equal(C, C0)
+
+
+@pytest.mark.parametrize("m,n,k,oa,ob,oc,pad", [(5, 7, 9, 0, 0, 0, 0), (16, 3, 40, 1, 0, 1, 3), (1, 33, 65, 0, 1, 0, 5),
+                                                (20, 20, 300, 1, 1, 1, 1)])
+def test_s16_against_python_integers_numpy_and_the_byte_oracle(oracle, m, n, k, oa, ob, oc, pad):
+    rng = np.random.default_rng([m, n, k, oa, ob, oc])
+    Ad = rng.integers(-32768, 32768, size=(m, k), dtype=np.int16)
+    Bd = rng.integers(-32768, 32768, size=(k, n), dtype=np.int16)
+    Ad[0, 0], Bd[0, 0] = -32768, -32768
+
+    def flat(X, order, pad):
+        r, c = X.shape
+        ld = (c if order == 0 else r) + pad
+        buf = np.full(((r if order == 0 else c), ld), 0x5A5A, dtype=np.int16)
+        if order == 0:
+            buf[:, :c] = X
+        else:
+            buf[:, :r] = X.T
+        return buf.reshape(-1), ld
+
+    A, lda = flat(Ad, oa, pad)
+    B, ldb = flat(Bd, ob, pad)
+    ldc = (n if oc == 0 else m) + pad
+    C0 = rng.integers(-1000, 1000, size=((m if oc == 0 else n), ldc), dtype=np.int32)
+    C = C0.reshape(-1).copy()
+    oracle.gemm_s16(m, n, k, A, lda, oa, B, ldb, ob, C, ldc, oc, oracle.ACCUMULATE)
+    exact = Ad.astype(object) @ Bd.astype(object)                    # Python integers: no overflow anywhere
+    got = C.reshape(C0.shape)
+    got2d = got[:, :n] if oc == 0 else got[:, :m].T
+    c02d = C0[:, :n] if oc == 0 else C0[:, :m].T
+    for i in range(m):
+        for j in range(n):
+            want = (int(exact[i, j]) + int(c02d[i, j])) % (1 << 32)
+            assert int(got2d[i, j]) % (1 << 32) == want
+    pad_cols = got[:, (n if oc == 0 else m):]
+    assert np.array_equal(pad_cols, C0[:, (n if oc == 0 else m):])    # padding untouched
+    # operands that fit a byte: the same numbers through the 8-bit oracle
+    A8 = rng.integers(-128, 128, size=(m, k), dtype=np.int8)
+    B8 = rng.integers(-128, 128, size=(k, n), dtype=np.int8)
+    C8 = np.zeros(m * n, dtype=np.int32)
+    C16 = np.zeros(m * n, dtype=np.int32)
+    oracle.gemm(False, False, m, n, k, A8.reshape(-1), k, 0, B8.reshape(-1), n, 0, C8, n, 0, oracle.OVERWRITE)
+    oracle.gemm_s16(m, n, k, A8.astype(np.int16).reshape(-1), k, 0, B8.astype(np.int16).reshape(-1), n, 0,
+                    C16, n, 0, oracle.OVERWRITE)
+    assert np.array_equal(C8, C16)
+    assert np.array_equal(C16.reshape(m, n), A8.astype(np.int64) @ B8.astype(np.int64))
