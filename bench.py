@@ -527,6 +527,51 @@ def run_packed_weights_table(M):
         del dA, dB, dC, dP, dBc
 
 
+def run_s16_table(M):
+    """int16 x int16 -> int32 through byte planes against the 8-bit product of the same size."""
+    import torch
+    print()
+    print("16-bit operands (int16 x int16 -> int32: byte planes, three s8 x s8 GEMMs and a combining pass),")
+    print("us per call (warm, graph replays), TOPS counted as 2 m n k:")
+    print()
+    print("| m | n | k | s8 x s8 -> s32 | s16 x s16 -> s32 | ratio | TOPS (s16) |")
+    print("|---|---|---|---|---|---|---|")
+    rng = np.random.default_rng(11)
+    R, OVW = W.ROW_MAJOR, W.OVERWRITE
+    for (m, n, k) in ((4096, 4096, 4096), (2048, 2048, 2048), (1024, 3072, 768), (1024, 1024, 1024), (16, 4096, 4096)):
+        dA8 = torch.from_numpy(rng.integers(-128, 128, size=m * k, dtype=np.int8).view(np.uint8)).cuda()
+        dB8 = torch.from_numpy(rng.integers(-128, 128, size=k * n, dtype=np.int8).view(np.uint8)).cuda()
+        dA = torch.from_numpy(rng.integers(-32768, 32768, size=m * k, dtype=np.int16)).cuda()
+        dB = torch.from_numpy(rng.integers(-32768, 32768, size=k * n, dtype=np.int16)).cuda()
+        dC = torch.zeros(m * n, dtype=torch.int32, device="cuda")
+        need = M.mipgemm_workspace_size_s16(m, n, k)
+        ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+
+        def replay_us(fn, calls=12, replays=5):
+            fn()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(calls):
+                    fn()
+            graph.replay()
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(replays):
+                graph.replay()
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / (replays * calls) * 1e3
+
+        t8 = replay_us(lambda: M.mipgemm_s8s8s32(m, n, k, dA8, k, R, dB8, n, R, dC, n, R, OVW))
+        t16 = replay_us(lambda: M.mipgemm_s16s16s32(m, n, k, dA, k, R, dB, n, R, dC, n, R, OVW,
+                                                    workspace=ws, workspace_bytes=need))
+        print("| %d | %d | %d | %.1f | %.1f | %.1f | %.0f |" % (m, n, k, t8, t16, t16 / t8,
+                                                           2.0 * m * n * k / t16 / 1e6), flush=True)
+        del dA8, dB8, dA, dB, dC, ws
+
+
 def run_encoder_table(M):
     """The GEMMs of one transformer encoder block (the paper's second workload, Section 7.2),
     captured into one HIP graph in the order of the paper's table and replayed: once with
@@ -708,6 +753,7 @@ def main():
         run_network_table(M)
         run_pack_table(M)
         run_packed_weights_table(M)
+        run_s16_table(M)
         run_encoder_table(M)
         return
 

@@ -446,6 +446,29 @@ int mipgemm_pack_b(int64_t k, int64_t n,
                    void *stream);
 
 /*
+ * C (+)= A B with 16-bit operands, int16 x int16 -> int32: the (i32, i16, i16) forms of
+ * the paper's table of matrix-oriented instructions (vpdpwssd, smopa).  This device has no
+ * integer matrix instruction for 16-bit operands, so the product is built from 8-bit ones:
+ * with x' = x - 128 every int16 is two signed bytes, x' = 256 h + l, and the sum over k of
+ * a b is 65536 (ah bh) + 256 (ah bl + al bh) + (al bl) + 128 (sum a' + sum b') + 16384 k,
+ * three s8 x s8 GEMMs of this library on the byte planes (the middle one of depth 2 k) and
+ * one pass that puts the pieces together: about four times the work of an 8-bit product of
+ * the same size.  Sums wrap modulo 2^32, which products of up to 2^30 reach much sooner
+ * than bytes do.  Arguments and their numbers as for mipgemm_s8s8s32 (lda, ldb count
+ * elements); the workspace is REQUIRED here for k > 0: mipgemm_workspace_size_s16(m, n, k)
+ * bytes of device memory (planes, plane sums, three m x n int32 products); a null
+ * workspace is -14, one that is too small -15, and nothing is touched.
+ */
+size_t mipgemm_workspace_size_s16(int64_t m, int64_t n, int64_t k);
+int mipgemm_s16s16s32(int64_t m, int64_t n, int64_t k,
+                      const int16_t *A, int64_t lda, int orderA,
+                      const int16_t *B, int64_t ldb, int orderB,
+                      int32_t *C, int64_t ldc, int orderC,
+                      int mode,
+                      void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/*
  * Pre-packed weights as an object of their own (Section 4.1 carried to constant
  * weights: everything that depends on B alone is done once): the k x n signed
  * matrix B, stored in either order, rewritten into `packed` as

@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     mipgemm_conv_s8u8s32, mipgemm_conv_s8u8f32, mipgemm_conv_workspace_size, mipgemm_conv_variant_name, mipgemm_im2col_u8, mipgemm_pack_b,
     mipgemm_packed_weights_bytes, mipgemm_pack_weights, mipgemm_s8s8s32_packed, mipgemm_u8s8s32_packed,
     mipgemm_conv_filter_sums, mipgemm_conv_s8u8s32_with_sums, mipgemm_conv_s8u8f32_with_sums, mipgemm_conv_s8u8s8,
+    mipgemm_s16s16s32, mipgemm_workspace_size_s16,
 )

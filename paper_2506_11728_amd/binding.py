@@ -54,7 +54,8 @@ def exported_symbols():
             "mipgemm_workspace_size_f32", "mipgemm_s8s8s8", "mipgemm_u8s8s8", "mipgemm_s8u8s8",
             "mipgemm_packed_weights_bytes", "mipgemm_pack_weights", "mipgemm_s8s8s32_packed",
             "mipgemm_u8s8s32_packed", "mipgemm_conv_filter_sums",
-            "mipgemm_conv_s8u8s32_with_sums", "mipgemm_conv_s8u8f32_with_sums", "mipgemm_conv_s8u8s8"]
+            "mipgemm_conv_s8u8s32_with_sums", "mipgemm_conv_s8u8f32_with_sums", "mipgemm_conv_s8u8s8",
+            "mipgemm_s16s16s32", "mipgemm_workspace_size_s16"]
 
 
 def load_library() -> ctypes.CDLL:
@@ -125,6 +126,10 @@ def load_library() -> ctypes.CDLL:
                                + [i64, ctypes.c_int, vp, ctypes.c_size_t, vp])
             lib.mipgemm_pack_b.restype = ctypes.c_int
             lib.mipgemm_pack_b.argtypes = [i64, i64, vp, i64, ctypes.c_int, vp, i64, vp]
+            lib.mipgemm_s16s16s32.restype = ctypes.c_int
+            lib.mipgemm_s16s16s32.argtypes = _GEMM_ARGTYPES
+            lib.mipgemm_workspace_size_s16.restype = ctypes.c_size_t
+            lib.mipgemm_workspace_size_s16.argtypes = [i64] * 3
             lib.mipgemm_packed_weights_bytes.restype = ctypes.c_size_t
             lib.mipgemm_packed_weights_bytes.argtypes = [i64, i64]
             lib.mipgemm_pack_weights.restype = ctypes.c_int
@@ -372,6 +377,18 @@ def mipgemm_pack_b(k, n, B, ldb, orderB, P, ldp, stream=None, check=True):
     if check and rc != 0:
         raise MipGemmError(rc, mipgemm_strerror(rc))
     return rc
+
+
+def mipgemm_workspace_size_s16(m, n, k) -> int:
+    return int(load_library().mipgemm_workspace_size_s16(m, n, k))
+
+
+def mipgemm_s16s16s32(m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC, mode,
+                      workspace=None, workspace_bytes=0, stream=None, check=True):
+    """C = [C +] A * B with int16 operands, through byte planes on the 8-bit kernels; needs a
+    workspace of mipgemm_workspace_size_s16(m, n, k) bytes."""
+    return _call("mipgemm_s16s16s32", m, n, k, A, lda, orderA, B, ldb, orderB, C, ldc, orderC,
+                 mode, workspace, workspace_bytes, stream, check)
 
 
 def mipgemm_packed_weights_bytes(k, n) -> int:

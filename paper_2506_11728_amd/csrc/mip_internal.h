@@ -139,6 +139,19 @@ hipError_t launch_pack_pair(int64_t k, int64_t kfill, int64_t m, const uint8_t *
                             bool a_kc, uint8_t *Ap, int64_t n, const uint8_t *B, int64_t ldb,
                             bool b_kc, uint8_t *Bp, int64_t ldp, hipStream_t s);
 
+// 16-bit operands as byte planes (kernel_s16.hip).  X: rows x k int16, element (r, p) at
+// X[r * s_r + p * s_k] with one stride 1; P: rows x 2 kp bytes, 16-byte aligned, kp a multiple
+// of 16: per row the high bytes then the low bytes minus 128 (hi_first) or the other way
+// round, zeros from p = k on.
+hipError_t launch_split_planes(const int16_t *X, int64_t s_r, int64_t s_k, int64_t rows, int64_t k,
+                               int64_t kp, uint8_t *P, bool hi_first, hipStream_t s);
+// C = [C +] 65536 T1 + 256 T2 + T3 + the terms in the plane sums (see kernel_s16.hip); T1..T3
+// dense m x n, C row-major with ldc.
+// sA, sB: the byte sums of the plane matrices taken as 2 m (2 n) columns of kp bytes.
+hipError_t launch_combine_planes(const int32_t *T1, const int32_t *T2, const int32_t *T3,
+                                 const int32_t *sA, const int32_t *sB, int64_t m, int64_t n, int64_t k,
+                                 int32_t *C, int64_t ldc, bool accumulate, hipStream_t s);
+
 // `count` zeroed 32-bit counters in device memory that no other call in flight uses: the
 // tickets of split k through partial-sum slots.  The kernels leave them zeroed.
 hipError_t splitk_tickets(int64_t count, unsigned **out);
