@@ -162,7 +162,10 @@ constexpr int STORE_PATCH_BYTES = STORE_PATCH_WORDS * 4;
 // it is writing, so that their latency hides behind the turns through LDS and the stores of
 // the blocks before (loaded only when needed, a store per load in turn, the 2048^3 case took
 // 25.1 us against 15.5 us for an overwriting call; one block ahead 18.7 us).
-template <int FM, int FN, int MODE>
+// STREAM: the stores are non-temporal.  That pays when the row pieces are whole cache lines; rows
+// of C that start at odd words leave every line to be completed by a neighbouring piece, which
+// only a store that stays in L2 until then can be merged with.
+template <int FM, int FN, int MODE, bool STREAM>
 __device__ __forceinline__ void store_blocks_via_lds_as(const v16i (&acc)[FM][FN], int32_t *C,
                                                         int64_t ldc, int lane, int32_t *patch,
                                                         const FinishAs<MODE> fin) {
@@ -201,7 +204,8 @@ __device__ __forceinline__ void store_blocks_via_lds_as(const v16i (&acc)[FM][FN
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) val[t][e] = fin(val[t][e], old[block % AHEAD][t][e]);
-      __builtin_nontemporal_store(val[t], piece(block, t));
+      if (STREAM) __builtin_nontemporal_store(val[t], piece(block, t));
+      else *piece(block, t) = val[t];
     }
     if (ACCUMULATE && block + AHEAD < NB) {  // the slot just used takes the block AHEAD further on
 #pragma unroll
@@ -214,11 +218,17 @@ template <int FM, int FN>
 __device__ __forceinline__ void store_blocks_via_lds(const v16i (&acc)[FM][FN], int32_t *C,
                                                      int64_t ldc, bool accumulate, int lane,
                                                      int32_t *patch, const Finish fin) {
-  switch (finish_mode(fin, accumulate)) {  // wave-uniform
-    case 0: store_blocks_via_lds_as<FM, FN, 0>(acc, C, ldc, lane, patch, FinishAs<0>{fin.scale}); break;
-    case 1: store_blocks_via_lds_as<FM, FN, 1>(acc, C, ldc, lane, patch, FinishAs<1>{fin.scale}); break;
-    case 2: store_blocks_via_lds_as<FM, FN, 2>(acc, C, ldc, lane, patch, FinishAs<2>{fin.scale}); break;
-    default: store_blocks_via_lds_as<FM, FN, 3>(acc, C, ldc, lane, patch, FinishAs<3>{fin.scale}); break;
+  // whole 128-byte lines per row piece: rows start on a line and are a whole number of lines apart
+  const bool lines = reinterpret_cast<uintptr_t>(C) % 128 == 0 && ldc % 32 == 0;
+  switch (finish_mode(fin, accumulate) + (lines ? 0 : 4)) {  // wave-uniform
+    case 0: store_blocks_via_lds_as<FM, FN, 0, true>(acc, C, ldc, lane, patch, FinishAs<0>{fin.scale}); break;
+    case 1: store_blocks_via_lds_as<FM, FN, 1, true>(acc, C, ldc, lane, patch, FinishAs<1>{fin.scale}); break;
+    case 2: store_blocks_via_lds_as<FM, FN, 2, true>(acc, C, ldc, lane, patch, FinishAs<2>{fin.scale}); break;
+    case 3: store_blocks_via_lds_as<FM, FN, 3, true>(acc, C, ldc, lane, patch, FinishAs<3>{fin.scale}); break;
+    case 4: store_blocks_via_lds_as<FM, FN, 0, false>(acc, C, ldc, lane, patch, FinishAs<0>{fin.scale}); break;
+    case 5: store_blocks_via_lds_as<FM, FN, 1, false>(acc, C, ldc, lane, patch, FinishAs<1>{fin.scale}); break;
+    case 6: store_blocks_via_lds_as<FM, FN, 2, false>(acc, C, ldc, lane, patch, FinishAs<2>{fin.scale}); break;
+    default: store_blocks_via_lds_as<FM, FN, 3, false>(acc, C, ldc, lane, patch, FinishAs<3>{fin.scale}); break;
   }
 }
 
