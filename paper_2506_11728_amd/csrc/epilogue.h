@@ -184,7 +184,7 @@ __device__ __forceinline__ void store_blocks_via_lds_as(const v16i (&acc)[FM][FN
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       old[b][t] = v4i{0, 0, 0, 0};
-      if (ACCUMULATE) old[b][t] = __builtin_nontemporal_load(piece(b, t));
+      if (ACCUMULATE) old[b][t] = STREAM ? __builtin_nontemporal_load(piece(b, t)) : *piece(b, t);
     }
 #pragma unroll
   for (int block = 0; block < NB; ++block) {
@@ -209,7 +209,8 @@ __device__ __forceinline__ void store_blocks_via_lds_as(const v16i (&acc)[FM][FN
     }
     if (ACCUMULATE && block + AHEAD < NB) {  // the slot just used takes the block AHEAD further on
 #pragma unroll
-      for (int t = 0; t < 4; ++t) old[block % AHEAD][t] = __builtin_nontemporal_load(piece(block + AHEAD, t));
+      for (int t = 0; t < 4; ++t)
+        old[block % AHEAD][t] = STREAM ? __builtin_nontemporal_load(piece(block + AHEAD, t)) : *piece(block + AHEAD, t);
     }
   }
 }
