@@ -88,7 +88,7 @@ def cpu_baseline(case: W.Case, ops: W.Operands, rows: int):
     }, C
 
 
-KERNEL_SOURCES = ("dma_common.h", "epilogue.h", "epilogue16.h", "lds_layout.h", "kernel_dma_k128.hip")
+KERNEL_SOURCES = ("dma_common.h", "epilogue.h", "epilogue16.h", "lds_layout.h", "dma_k128.h", "kernel_dma_k128.hip")
 
 
 def kernel_fingerprint() -> str:
@@ -311,6 +311,32 @@ def run_packed_table(M):
                 m, n, k, "row" if oa == W.ROW_MAJOR else "col", "row" if ob == W.ROW_MAJOR else "col",
                 names[0], times[0], ops / times[0] / 1e6, names[1], times[1], ops / times[1] / 1e6),
                 flush=True)
+
+
+def run_deep_k_table(M):
+    """A very long k over few tiles of C: the dispatcher's choice (128 x 128 tiles with 128-deep
+    blocks, k in ranges) against the 64 x 64 and 64 x 128 tiles the general scheme would pick,
+    unsplit and in the ranges it would give them when forced (HIP graph replay, warm / cold)."""
+    print()
+    print("Deep k over few tiles, s8 x s8 -> s32, row-major, us per call warm / cold:")
+    print()
+    print("| m | n | k | mode | as dispatched | us | 64x64 tiles | 64x128 tiles in 4 ranges |")
+    print("|---|---|---|---|---|---|---|---|")
+    for (m, n, k) in ((512, 512, 16384), (768, 768, 8192), (512, 1568, 8192), (1024, 1024, 8192),
+                      (1024, 1024, 16384), (768, 2048, 16384), (768, 768, 6144), (512, 1568, 4608)):
+        for mode in (W.OVERWRITE, W.ACCUMULATE):
+            case = W.Case("deepk_%dx%dx%d_m%d" % (m, n, k, mode), 8, 0, m, n, k, mode=mode, seed=3)
+            cells = []
+            for variant, splits in ((None, None), ("dma64", None), ("dma64x128", 4)):
+                with M.tuning(MIPGEMM_VARIANT=variant, MIPGEMM_SPLITK=splits):
+                    warm = time_case_graph(M, case)
+                    cold = time_case_graph(M, case, footprint=600 * 10 ** 6)
+                cells.append("%.1f / %.1f" % (warm, cold))
+            name = M.mipgemm_variant_name_for_mode(m, n, k, case.lda, 0, case.ldb, 0, case.ldc, 0, False, False,
+                                                   True, mode)
+            print("| %d | %d | %d | %s | %s | %s | %s | %s |" % (
+                m, n, k, "overwrite" if mode == W.OVERWRITE else "accumulate", name, cells[0], cells[1],
+                cells[2]), flush=True)
 
 
 def run_conv_table(M):
@@ -749,6 +775,7 @@ def main():
     if args.suite:
         run_suite(M, args)
         run_packed_table(M)
+        run_deep_k_table(M)
         run_conv_table(M)
         run_network_table(M)
         run_pack_table(M)

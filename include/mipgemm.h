@@ -46,7 +46,8 @@
  * afterwards only be changed with mipgemm_set_tuning():
  *     MIPGEMM_VARIANT  kernel variant for the GEMM calls: "simple" (one thread per
  *                      element of C: a cross-check, hundreds of times slower),
- *                      "dma256k128", "dma128k128", "slab16", "slab32", "slab64", "tile<shape>" or
+ *                      "dma256k128", "dma128k128", "dma128k128split" (its general form: ragged
+ *                      edges, k in MIPGEMM_SPLITK ranges), "slab16", "slab32", "slab64", "tile<shape>" or
  *                      "dma<shape>" with <shape> one of 256, 128, 64, 64x256,
  *                      256x64, 64x128, 128x64; a variant that cannot serve a
  *                      problem falls back (the names of mipgemm_variant_name say

@@ -54,18 +54,35 @@ const char *plan_name(const Plan &plan) {
     case KIND_STAGED: return staged[plan.shape];
     case KIND_DMA: return dma[plan.shape];
     case KIND_DMA_K128: return plan.shape == SHAPE_128 ? "mfma_dma128_k128" : "mfma_dma256_k128";
+    case KIND_DMA_K128_SPLIT: return "mfma_dma128_k128_split";
     case KIND_SLAB: return plan.splits == 4 ? "mfma_slab64" : (plan.splits == 2 ? "mfma_slab32" : "mfma_slab16");
     default: return "?";
   }
 }
 
 // The tuning value MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
-// "dma128k128" (the same kernel on 128 x 128 tiles),
+// "dma128k128" (the same kernel on 128 x 128 tiles), "dma128k128split" (its general form with k ranges),
 // "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
 // 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
 // eligible for; others fall back to the staged kernel of the same shape.
 // MIPGEMM_SPLITK pins the number of k ranges of the tile kernels.
+static int forced_splits() { return tuning().splitk; }
+
+// k ranges for the 128 x 128 tiles with 128-deep blocks: workgroups for about three quarters
+// of the compute units, at most eight ranges (every range adds a whole C through atomics), each
+// of at least eight blocks.  Measured best, ranges at tiles: 6-8 at 16, 6 at 24, 4 at 36 to 52,
+// 3-4 at 64, 2 at 96.
+static int k128_ranges(const Problem &p) {
+  if (forced_splits() > 0) return forced_splits();
+  const int64_t tiles = ((p.m + 127) / 128) * ((p.n + 127) / 128);
+  const int64_t blocks = p.k / 128;
+  int64_t sp = (3 * compute_units() / 4 + tiles / 2) / tiles;
+  if (sp > 8) sp = 8;
+  if (sp > blocks / 8) sp = blocks / 8;
+  return sp > 1 ? (int)sp : 1;
+}
+
 static bool forced_plan(const Problem &p, Plan *plan) {
   const char *e = tuning().variant;
   if (!*e) return false;
@@ -78,6 +95,11 @@ static bool forced_plan(const Problem &p, Plan *plan) {
   if (!std::strcmp(e, "dma128k128")) {
     if (!dma_k128_eligible(p, true)) return false;
     *plan = {KIND_DMA_K128, SHAPE_128, 1};
+    return true;
+  }
+  if (!std::strcmp(e, "dma128k128split")) {
+    if (!dma_k128_split_eligible(p)) return false;
+    *plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
     return true;
   }
   if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32") || !std::strcmp(e, "slab64")) {
@@ -97,8 +119,6 @@ static bool forced_plan(const Problem &p, Plan *plan) {
     }
   return false;
 }
-
-static int forced_splits() { return tuning().splitk; }
 
 hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
   if (bytes <= 64 * 1024) return hipSuccess;
@@ -272,6 +292,19 @@ Plan choose_plan(const Problem &p) {
     else if (slab_ok && (short_k || (p.out_float && !p.ws)) && tile_count(p, SHAPE_64) < kComputeUnits / 2 &&
              p.n / 16 >= 64)
       plan = {KIND_SLAB, SHAPE_64, 1};
+    // A very long k over few tiles: the 128 x 128 tiles with 128-deep blocks, k in ranges.
+    // The 64 x 64 tiles chosen above for such a shape (enough of them to need no split) run
+    // at 64 operations per operand byte; the wider tile halves the bytes, and the ranges give
+    // the compute units their workgroups.  Measured warm/cold, us, against the choice above:
+    // (768, 768, 8192) 22.8/31.0 -> 18.8/22.6, (512, 1568, 8192) 25.4/34.6 -> 21.5/25.2,
+    // (1024, 1024, 16384) 46.5/60.0 -> 32.7/37.4, (768, 2048, 16384) 54.6/73.4 -> 45.3/51.4,
+    // (512, 512, 16384) 19.0/23.1 -> 17.7/20.7; accumulating (no zero-fill launch) already from
+    // k = 6144: (768, 768, 6144) 18.1/18.5 -> 14.7/17.0, (512, 1568, 6144) 20.1/26.8 -> 16.9/19.8.
+    // Not below: at k = 4608 the atomics cost what the ranges save, (1024, 1024, 4608)
+    // 13.2/15.4 against 19.8/22.0, (512, 1568, 4608) 14.7/16.7 against 16.7/20.0.
+    else if (p.m > 64 && p.n > 64 && p.k >= (p.accumulate ? 6144 : 8192) && tile_count(p, SHAPE_128) >= 16 &&
+             tile_count(p, SHAPE_128) <= 3 * kComputeUnits / 8 && dma_k128_split_eligible(p))
+      plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     // (the same kernel on 128 x 128 tiles, where that is the shape and m, n, k are whole tiles
     // and blocks: 5 to 15 % over the 64-deep kernel of that shape; measured warm/cold, us:

@@ -143,6 +143,35 @@ __device__ __forceinline__ void store_blocks16_as(const v4i (&acc)[FM][FN], void
   }
 }
 
+// Split k: the wave's partial sums are added into an int32 C with integer atomics (any order
+// gives the same bits).  Sixteen rows at a time go through the wave's LDS patch, as in the
+// write-back above, so that the 64 lanes of one atomic instruction cover 64 consecutive
+// words of one row (two cache lines) instead of four words in each of sixteen rows.
+// rows, cols: how much of the sub-tile lies inside the matrix.
+template <int FM, int FN, bool CORRECT>
+__device__ __forceinline__ void add_blocks16_atomic(const v4i (&acc)[FM][FN], int32_t *C, int64_t ldc,
+                                                    int64_t rows, int64_t cols, int lane, int32_t *patch,
+                                                    const Correction16<FM, FN> &corr) {
+  static_assert(FN == 4, "rows of 64 words: one per lane");
+  constexpr int PITCH = Patch16<FN>::PITCH;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    if (i * 16 >= rows) break;  // wave-uniform
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) =
+          CORRECT ? acc[i][j] + corr.col_corr[j] + corr.row_corr[i] : acc[i][j];
+    // same wave wrote and reads: LDS operations of a wave complete in order
+    int val[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) val[r] = patch[r * PITCH + lane];
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (i * 16 + r < rows && lane < cols)
+        __hip_atomic_fetch_add(C + (i * 16 + r) * ldc + lane, val[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 // out_mode: 0 int32, 1 float, 2 int8 (the Problem's out_float).
 template <int FM, int FN, bool FULL, bool CORRECT>
 __device__ __forceinline__ void store_blocks16(const v4i (&acc)[FM][FN], void *C, int64_t ldc,

@@ -1,0 +1,74 @@
+// The kernel with 128-deep k blocks (dma_k128.h) in its general form on 128 x 128 tiles:
+// ragged m and n on unpadded operands, k cut into ranges.  For problems whose tiles are too
+// few to occupy the device while k is long: every range of a tile is a workgroup of its own,
+// and the ranges add their partial sums into C with integer atomics.
+#include "dma_k128.h"
+
+namespace mip {
+
+bool dma_k128_split_eligible(const Problem &p) {
+  if (p.conv || p.batch != 1 || p.out_float || p.k % KD2 || p.k < KD2) return false;
+  const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  if (!a_kc && (p.a_sm != 1 || p.m % 16)) return false;  // a strided operand comes in 16-byte chunks
+  if (!b_kc && (p.b_sn != 1 || p.n % 16)) return false;
+  const int64_t lda = a_kc ? p.a_sm : p.a_sk;
+  const int64_t ldb = b_kc ? p.b_sn : p.b_sk;
+  if (lda % 16 || ldb % 16) return false;
+  if (reinterpret_cast<uintptr_t>(p.A) % 16 || reinterpret_cast<uintptr_t>(p.B) % 16) return false;
+  if (128 * lda >= ((int64_t)1 << 31) || 128 * ldb >= ((int64_t)1 << 31)) return false;
+  if (((p.m + 127) / 128) * ((p.n + 127) / 128) > ((int64_t)1 << 30)) return false;
+  return true;
+}
+
+hipError_t launch_dma_k128_split(const Problem &p, int splits, hipStream_t s) {
+  constexpr int BM = 128, BN = 128;
+  DmaParams P;
+  P.clocks = nullptr;
+  P.A = static_cast<const uint8_t *>(p.A);
+  P.B = static_cast<const uint8_t *>(p.B);
+  P.C = p.C;
+  P.lda = p.a_sk == 1 ? p.a_sm : p.a_sk;
+  P.ldb = p.b_sk == 1 ? p.b_sn : p.b_sk;
+  P.ldc = p.ldc;
+  P.m = p.m;
+  P.n = p.n;
+  P.tiles_m = (int)((p.m + BM - 1) / BM);
+  P.tiles_n = (int)((p.n + BN - 1) / BN);
+  P.nkt = (int)(p.k / KD2);
+  if (splits < 1) splits = 1;
+  if (splits > P.nkt) splits = P.nkt;  // every range holds at least one block
+  if (splits > 65535) splits = 65535;
+  P.splits = splits;
+  P.atomic = splits > 1;
+  P.accumulate = p.accumulate;
+  P.out_float = 0;
+  P.scale = 1.0f;
+  P.ksum = nullptr;
+  P.first_round = (int)compute_units();
+  P.stagger_ticks = 0;
+  if (P.atomic && !p.accumulate) {
+    hipError_t e = launch_fill_zero(p, s);  // partial sums are added into C: start from zero
+    if (e != hipSuccess) return e;
+  }
+  const int ntiles = P.tiles_m * P.tiles_n;
+  dim3 grid((unsigned)(((ntiles + 7) / 8) * 8), (unsigned)splits);
+  const size_t lds = (size_t)Tile16<BM, BN>::LDS_BYTES;
+  const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
+  const int uns = p.a_unsigned ? 1 : (p.b_unsigned ? 2 : 0);
+  void (*kern)(DmaParams) = nullptr;
+#define MIP_PICK(AK, BKC)                                                                     \
+  kern = uns == 0 ? dma128_kernel<BM, BN, AK, BKC, 0, true, true>                             \
+                  : (uns == 1 ? dma128_kernel<BM, BN, AK, BKC, 1, true, true>                 \
+                              : dma128_kernel<BM, BN, AK, BKC, 2, true, true>)
+  if (a_kc && b_kc) MIP_PICK(true, true);
+  else if (a_kc) MIP_PICK(true, false);
+  else if (b_kc) MIP_PICK(false, true);
+  else MIP_PICK(false, false);
+#undef MIP_PICK
+  hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), lds, s, P);
+  return hipGetLastError();
+}
+
+}  // namespace mip

@@ -68,6 +68,7 @@ enum Kind {
   KIND_STAGED,    // MFMA tiles, operands staged through registers: any alignment, any size
   KIND_DMA,       // MFMA tiles, operands streamed global -> LDS directly (aligned, k % 64 == 0)
   KIND_DMA_K128,  // 256 x 256 (or, shape SHAPE_128, 128 x 128) tiles, 128-deep k blocks: large aligned problems
+  KIND_DMA_K128_SPLIT,  // the same kernel on 128 x 128 tiles, ragged edges allowed, k cut into `splits` ranges
   KIND_SLAB       // m <= 64: one workgroup per 16- or 32-column slab of B, all of k (splits = 1 or 2: slab width / 16)
 };
 
@@ -95,6 +96,11 @@ bool dma_k128_eligible(const Problem &p, bool small = false);  // small: its 128
 // multiple of 8) that the kernel adds its shader clocks and 10 ns ticks to
 hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *clocks = nullptr,
                            bool small = false);
+
+// The general 128 x 128 form of that kernel: any m and n (a strided operand's extent a multiple
+// of 16), int32 output, k in `splits` ranges that add into C (an overwriting call zeroes C first).
+bool dma_k128_split_eligible(const Problem &p);
+hipError_t launch_dma_k128_split(const Problem &p, int splits, hipStream_t s);
 
 bool slab_eligible(const Problem &p, int nt);  // nt: slab width in blocks of 16 columns, 1 or 2
 hipError_t launch_slab(const Problem &p, int nt, hipStream_t s);

@@ -163,6 +163,7 @@ hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s) {
     case KIND_STAGED: return launch_staged(p, plan.shape, plan.splits, s);
     case KIND_DMA: return launch_dma(p, plan.shape, plan.splits, s);
     case KIND_DMA_K128: return launch_dma_k128(p, s, nullptr, plan.shape == SHAPE_128);
+    case KIND_DMA_K128_SPLIT: return launch_dma_k128_split(p, plan.splits, s);
     case KIND_SLAB: return launch_slab(p, plan.splits, s);
   }
   return hipErrorInvalidValue;

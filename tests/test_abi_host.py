@@ -148,6 +148,15 @@ def test_variant_choice(M):
     # three quarters of a round of 64 x 128 tiles, long side along the row-major B
     assert name(256, 6272, 2304, 2304, 0, 6272, 0, 6272, 0) == "mfma_dma64x128"
     assert name(6272, 256, 2304, 2304, 0, 256, 0, 256, 0) == "mfma_dma64x128"
+    # a very long k over few tiles: the 128 x 128 tiles with 128-deep blocks, k in ranges (an
+    # accumulating call, which needs no zero-fill launch, from a shorter k on)
+    assert name(768, 768, 8192, 8192, 0, 768, 0, 768, 0) == "mfma_dma128_k128_split"
+    assert name(512, 1568, 16384, 16384, 0, 1568, 0, 1568, 0, b_unsigned=True) == "mfma_dma128_k128_split"
+    assert name(768, 768, 6144, 6144, 0, 768, 0, 768, 0) == "mfma_dma64"
+    assert M.mipgemm_variant_name_for_mode(768, 768, 6144, 6144, 0, 768, 0, 768, 0, False, False, True,
+                                           1) == "mfma_dma128_k128_split"
+    assert name(768, 776, 8192, 8192, 0, 776, 0, 776, 0) != "mfma_dma128_k128_split"   # n % 16 on a row-major B
+    assert name(2048, 2048, 8192, 8192, 0, 2048, 0, 2048, 0) == "mfma_dma128_k128"     # enough tiles
     # k not a multiple of 64 does not
     assert name(1000, 3072, 770, 784, 0, 3072, 0, 3072, 0) == "mfma_tile128x64"
     assert name(4, 4, 0, 1, 0, 4, 0, 4, 0) == "fill_zero"

@@ -85,6 +85,8 @@ def kernel_that_runs(M, case, variant):
         assert name == "simple"
     elif variant.startswith("tile"):
         assert name == "mfma_" + variant
+    elif variant == "dma128k128split":
+        assert name == "mfma_dma128_k128_split" or not case.m * case.n * case.k
     elif variant.startswith("dma") and not variant.endswith("k128"):
         assert name in ("mfma_" + variant, "mfma_tile" + variant[3:])
     _ran.setdefault(variant, set()).add(name)
@@ -423,6 +425,67 @@ def test_deep_k_kernel_unsigned_and_accumulate(gpu, oracle, case):
         assert name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB, case.ldc,
                     case.orderC, case.a_unsigned, case.b_unsigned, True) == "mfma_dma256_k128"
     check_case(gpu, oracle, case, "dma256k128")
+
+
+def _k128_split_cases():
+    out = []
+    idx = 0
+    shapes = ((208, 336, 640), (128, 128, 128), (400, 144, 1152), (96, 1568, 1024), (200, 330, 512))
+    for (m, n, k) in shapes:
+        for uns in (0, 1, 2):
+            for mode in (W.OVERWRITE, W.ACCUMULATE):
+                # extents that are no multiples of 16 need both operands k-contiguous
+                orders = ((0, 1, 0), (0, 1, 1)) if m % 16 or n % 16 else ((0, 0, 0), (0, 1, 0), (1, 0, 1), (1, 1, 0))
+                for (oa, ob, oc) in orders:
+                    out.append((W.Case(
+                        "k128split_%dx%dx%d_u%d_m%d_%d%d%d" % (m, n, k, uns, mode, oa, ob, oc), 8, idx,
+                        m, n, k, a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob,
+                        orderC=oc, pad=16 * (idx % 3), mode=mode,
+                        a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+                        b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+                        c_dist=("uniform", -1000, 1000), seed=10), (1, 2, 3, 5, 1000)[idx % 5]))
+                    idx += 1
+    return out
+
+
+@pytest.mark.parametrize("case,splits", _k128_split_cases(), ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_deep_k_kernel_general_form_with_k_ranges(gpu, oracle, case, splits):
+    """The 128 x 128 form of the kernel with 128-deep blocks on ragged, unpadded operands, k in
+    one to many ranges (1000: one block each) that meet in C through atomics; an overwriting
+    call twice over different garbage."""
+    import torch
+    name = gpu.mipgemm_variant_name
+    with VariantEnv("dma128k128split", splits):
+        assert name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB, case.ldc,
+                    case.orderC, case.a_unsigned, case.b_unsigned, True) == "mfma_dma128_k128_split"
+    check_case(gpu, oracle, case, "dma128k128split", splits)
+    if case.mode == W.OVERWRITE:
+        ops = W.materialize(case)
+        want = oracle_result(oracle, case, ops)
+        rows, cols = (case.n, case.m) if case.orderC else (case.m, case.n)
+        inside = np.zeros((rows, case.ldc), dtype=bool)
+        inside[:, :cols] = True
+        C = np.where(inside.reshape(-1), np.int32(0x5a5a5a5a), ops.C[:rows * case.ldc])
+        C = np.concatenate([C, ops.C[rows * case.ldc:]]).astype(np.int32)
+        got = gpu_gemm(gpu, case, ops.A, ops.B, C, "dma128k128split", splits)
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("spec", [(272, 1008, 8192, 0, 0, W.OVERWRITE, 1), (256, 1024, 6144, 0, 1, W.ACCUMULATE, 0),
+                                  (640, 400, 8320, 1, 0, W.OVERWRITE, 2), (384, 1536, 16384, 0, 0, W.ACCUMULATE, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_deep_k_over_few_tiles_as_dispatched(gpu, oracle, spec):
+    """A very long k over few tiles of C: the dispatcher itself takes the general 128 x 128 form
+    with k ranges (the name is asserted), ragged edges and an unsigned operand included."""
+    m, n, k, oa, ob, mode, uns = spec
+    case = W.Case("deepfew_%dx%dx%d_%d%d_m%d_u%d" % (m, n, k, oa, ob, mode, uns), 8, 0, m, n, k,
+                  a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob, pad=16, mode=mode,
+                  a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+                  b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+                  c_dist=("uniform", -1000, 1000), seed=12)
+    assert gpu.mipgemm_variant_name_for_mode(m, n, k, case.lda, oa, case.ldb, ob, case.ldc, 0, uns == 1,
+                                             uns == 2, True, mode) == "mfma_dma128_k128_split"
+    check_case(gpu, oracle, case, "auto")
 
 
 # ---------------------------------------------------------------------------
