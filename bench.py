@@ -339,6 +339,31 @@ def run_deep_k_table(M):
                 cells[2]), flush=True)
 
 
+def run_ragged_table(M):
+    """Aligned operands whose m or n is no multiple of the tile: the dispatcher's choice (the
+    general forms of the kernel with 128-deep blocks) against the 64-deep tile kernels with
+    masked edges (HIP graph replay, warm)."""
+    print()
+    print("Aligned operands, m or n no multiple of the tile, row-major, overwrite, us per call warm:")
+    print()
+    print("| m | n | k | entry | as dispatched | us | TOPS | 64-deep tiles | us | TOPS |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for (m, n, k) in ((4000, 4000, 1024), (4000, 4000, 4096), (4000, 4000, 8192), (8000, 8000, 4096),
+                      (6000, 4000, 8192), (3000, 2000, 4096), (1000, 3072, 768)):
+        for b_unsigned in (False, True):
+            case = W.Case("ragged_%dx%dx%d_u%d" % (m, n, k, b_unsigned), 8, 0, m, n, k, b_unsigned=b_unsigned,
+                          b_dist=("uniform", 0, 255) if b_unsigned else ("uniform", -128, 127), seed=3)
+            calls = 4 if case.ops > 1e11 else 24
+            cells = []
+            for variant in (None, "dma256" if m * n >= 192 * 65536 and k >= 1024 else "dma128"):
+                with M.tuning(MIPGEMM_VARIANT=variant):
+                    name = M.mipgemm_variant_name(m, n, k, case.lda, 0, case.ldb, 0, case.ldc, 0, False,
+                                                  b_unsigned, True)
+                    us = time_case_graph(M, case, calls=calls)
+                cells.append("%s | %.1f | %.0f" % (name, us, case.ops / us / 1e6))
+            print("| %d | %d | %d | %s | %s | %s |" % (m, n, k, case.entry, cells[0], cells[1]), flush=True)
+
+
 def run_conv_table(M):
     """The convolutions of the conv-as-GEMM workload, timed as convolutions (HIP graph
     replay, warm): the GEMM alone on a ready-made augmented matrix, the lowering written
@@ -776,6 +801,7 @@ def main():
         run_suite(M, args)
         run_packed_table(M)
         run_deep_k_table(M)
+        run_ragged_table(M)
         run_conv_table(M)
         run_network_table(M)
         run_pack_table(M)

@@ -54,14 +54,14 @@ const char *plan_name(const Plan &plan) {
     case KIND_STAGED: return staged[plan.shape];
     case KIND_DMA: return dma[plan.shape];
     case KIND_DMA_K128: return plan.shape == SHAPE_128 ? "mfma_dma128_k128" : "mfma_dma256_k128";
-    case KIND_DMA_K128_SPLIT: return "mfma_dma128_k128_split";
+    case KIND_DMA_K128_SPLIT: return plan.shape == SHAPE_256 ? "mfma_dma256_k128_ragged" : "mfma_dma128_k128_split";
     case KIND_SLAB: return plan.splits == 4 ? "mfma_slab64" : (plan.splits == 2 ? "mfma_slab32" : "mfma_slab16");
     default: return "?";
   }
 }
 
 // The tuning value MIPGEMM_VARIANT pins the kernel (tuning and tests): "simple", "dma256k128",
-// "dma128k128" (the same kernel on 128 x 128 tiles), "dma128k128split" (its general form with k ranges),
+// "dma128k128" (the same kernel on 128 x 128 tiles), "dma128k128split" (its general form with k ranges), "dma256k128ragged" (the general form on 256 x 256 tiles),
 // "slab16" / "slab32" (the skinny-m kernel with that slab width),
 // "tile<shape>" (register-staged) or "dma<shape>" (direct-to-LDS) with <shape> one of
 // 256, 128, 64, 64x256, 256x64, 64x128, 128x64.  A dma variant only applies to problems it is
@@ -100,6 +100,11 @@ static bool forced_plan(const Problem &p, Plan *plan) {
   if (!std::strcmp(e, "dma128k128split")) {
     if (!dma_k128_split_eligible(p)) return false;
     *plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
+    return true;
+  }
+  if (!std::strcmp(e, "dma256k128ragged")) {
+    if (!dma_k128_split_eligible(p, true)) return false;
+    *plan = {KIND_DMA_K128_SPLIT, SHAPE_256, 1};
     return true;
   }
   if (!std::strcmp(e, "slab16") || !std::strcmp(e, "slab32") || !std::strcmp(e, "slab64")) {
@@ -255,6 +260,7 @@ Plan choose_plan(const Problem &p) {
     // rows on: (1, 4096, 1024) 2.9/3.5 against 3.4/4.1, (16, 8192, 1024) 4.2/5.7 against 3.9/4.7;
     // with fewer rows from k = 1536: (8, 4096, 1536) 4.0/5.1 against 3.5/4.3,
     // (4, 16384, 1536) 6.2/8.4 against 4.6/8.2.)
+    const bool uns_acc = (p.a_unsigned || p.b_unsigned) && p.accumulate;
     const bool adds_in_place = p.accumulate && !p.out_float && p.k >= (p.m >= 16 ? 1024 : 1536);
     const bool slab_ok = p.m <= 64 && !adds_in_place && slab_eligible(p, 1);
     // Slabs of 32 columns re-read A half as often and need half the workgroups; they win
@@ -305,12 +311,39 @@ Plan choose_plan(const Problem &p) {
     else if (p.m > 64 && p.n > 64 && p.k >= (p.accumulate ? 6144 : 8192) && tile_count(p, SHAPE_128) >= 16 &&
              tile_count(p, SHAPE_128) <= 3 * kComputeUnits / 8 && dma_k128_split_eligible(p))
       plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
+    // (An accumulating call with an unsigned operand pays more for the large tile's write-back,
+    // which then carries the old words and the corrections through the registers together:
+    // up to k = 4096 the 128 x 128 form is the faster one there; 4096^2 x 1024, B unsigned:
+    // 61 us against 45.)
+    else if (sh == SHAPE_256 && uns_acc && p.k >= 1024 && p.k < 4096 && dma_k128_eligible(p, true))
+      plan = {KIND_DMA_K128, SHAPE_128, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     // (the same kernel on 128 x 128 tiles, where that is the shape and m, n, k are whole tiles
     // and blocks: 5 to 15 % over the 64-deep kernel of that shape; measured warm/cold, us:
     // 2048^3 14.6/15.1 -> 13.0/14.1, (1024, 3072, 3072) 17.1/23.2 -> 15.6/20.2,
     // (768, 4096, 2048) 12.3/12.9 -> 10.8/12.3, (256, 12544, 1152) 9.1/11.2 -> 8.3/10.4)
     else if (sh == SHAPE_128 && p.k >= 512 && dma_k128_eligible(p, true)) plan = {KIND_DMA_K128, sh, 1};
+    // Aligned operands whose m or n is no multiple of the tile: the general forms of the same
+    // kernel (loads redirected at the edges instead of padded operands), where the 64-deep
+    // kernels with their masked edges used to serve.  On 256 x 256 tiles from k = 2048 on;
+    // measured warm, us, overwriting: 4000^2 x 4096 105 -> 60, 4000^2 x 8192 193 -> 112,
+    // 8000^2 x 4096 402 -> 254, (6000, 4000, 8192) 325 -> 198, (5008, 3008, 2048) 69 -> 42.
+    // (Not for an unsigned operand in an accumulating call below k = 4096, as above.)
+    else if (sh == SHAPE_256 && p.k >= 2048 && !(uns_acc && p.k < 4096) && dma_k128_split_eligible(p, true))
+      plan = {KIND_DMA_K128_SPLIT, SHAPE_256, 1};
+    // On 128 x 128 tiles otherwise, from k = 768 on: 4000^2 x 1024 48 -> 30 (with an unsigned
+    // operand 88 -> 33), 8000^2 x 1024 162 -> 93, (3000, 2000, 1024) 15.8 -> 14.0,
+    // (3000, 2000, 4096) 45 -> 38, (1000, 3072, 768) 8.2 -> 6.7, (1000, 3072, 4096) 23 -> 21;
+    // accumulating calls tie warm and gain cold ((3000, 2000, 1024) 19.7/25.7 -> 20.8/21.9).
+    // Not at k = 512: (2048, 1568, 512) 6.6 -> 7.7.
+    else if ((sh == SHAPE_256 || sh == SHAPE_128) && p.k >= 768 && dma_k128_split_eligible(p))
+      plan = {KIND_DMA_K128_SPLIT, SHAPE_128, 1};
+    // The same tiles one step below the count that makes 128 x 128 the shape above, on
+    // problems with at least 1024 rows and columns and k from 2048: (1520, 1520, 2048)
+    // 16.0/17.6 -> 13.3/14.3 us warm/cold, (1520, 1520, 8192) 56.5/56.0 -> 36.9/47.1.
+    else if (p.k >= 2048 && p.m >= 1024 && p.n >= 1024 && tile_count(p, SHAPE_128) >= kComputeUnits / 2 &&
+             tile_count(p, SHAPE_128) < 192 && dma_k128_split_eligible(p))
+      plan = {KIND_DMA_K128_SPLIT, SHAPE_128, 1};
     else if (dma_eligible(p, sh)) plan = {KIND_DMA, sh, 1};
     // the register-staged kernel keeps its operands in flight in VGPRs, which a
     // 256 x 256 tile's accumulators leave no room for: it runs faster on 128 x 128

@@ -168,11 +168,11 @@ struct Stage16 {
 // accumulated from the fragments in the loop, which costs four dot-product instructions per
 // fragment of the signed operand between the matrix instructions.
 //
-// GENERAL (with RAGGED, on 128 x 128 tiles): m and n need not be whole tiles and the operands
-// need no padding (loads that would leave an operand are redirected inside it), and k may be
-// cut into ranges whose partial sums meet in C through atomics: the form for problems with
-// too few tiles to occupy the device and a long k.  A strided operand's extent must be a
-// multiple of 16.
+// GENERAL (with RAGGED): m and n need not be whole tiles and the operands need no padding
+// (loads that would leave an operand are redirected inside it); a strided operand's extent
+// must be a multiple of 16.  On 128 x 128 tiles k may also be cut into ranges whose partial
+// sums meet in C through atomics: the form for problems with too few tiles to occupy the
+// device and a long k.
 template <int BM, int BN, bool A_KC, bool B_KC, int UNS, bool RAGGED = false, bool GENERAL = false>
 __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   constexpr bool FLIP_A = UNS == 1 || UNS == 3, FLIP_B = UNS == 2 || UNS == 4;
@@ -409,7 +409,7 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   void *C = P.out_float == 2 ? static_cast<void *>(reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw)
                              : static_cast<void *>(P.C + mw * P.ldc + nw);
   bool added = false;
-  if constexpr (GENERAL) {
+  if constexpr (GENERAL && BM == 128 && BN == 128) {  // (k ranges exist on the small tile only)
     if (P.atomic) {
       if (mw < P.m && nw < P.n)
         add_blocks16_atomic<FM, FN, UNS != 0>(acc, P.C + mw * P.ldc + nw, P.ldc, P.m - mw, P.n - nw, lane, patch, corr);

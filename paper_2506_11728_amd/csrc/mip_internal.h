@@ -68,7 +68,7 @@ enum Kind {
   KIND_STAGED,    // MFMA tiles, operands staged through registers: any alignment, any size
   KIND_DMA,       // MFMA tiles, operands streamed global -> LDS directly (aligned, k % 64 == 0)
   KIND_DMA_K128,  // 256 x 256 (or, shape SHAPE_128, 128 x 128) tiles, 128-deep k blocks: large aligned problems
-  KIND_DMA_K128_SPLIT,  // the same kernel on 128 x 128 tiles, ragged edges allowed, k cut into `splits` ranges
+  KIND_DMA_K128_SPLIT,  // the same kernel, ragged edges allowed: 128 x 128 tiles with k cut into `splits` ranges, or (shape SHAPE_256) 256 x 256 tiles
   KIND_SLAB       // m <= 64: one workgroup per 16- or 32-column slab of B, all of k (splits = 1 or 2: slab width / 16)
 };
 
@@ -99,8 +99,9 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
 
 // The general 128 x 128 form of that kernel: any m and n (a strided operand's extent a multiple
 // of 16), int32 output, k in `splits` ranges that add into C (an overwriting call zeroes C first).
-bool dma_k128_split_eligible(const Problem &p);
-hipError_t launch_dma_k128_split(const Problem &p, int splits, hipStream_t s);
+// large: on 256 x 256 tiles (one k range).
+bool dma_k128_split_eligible(const Problem &p, bool large = false);
+hipError_t launch_dma_k128_split(const Problem &p, int splits, hipStream_t s, bool large = false);
 
 bool slab_eligible(const Problem &p, int nt);  // nt: slab width in blocks of 16 columns, 1 or 2
 hipError_t launch_slab(const Problem &p, int nt, hipStream_t s);

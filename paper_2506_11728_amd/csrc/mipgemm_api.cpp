@@ -163,7 +163,7 @@ hipError_t launch_plan(const Problem &p, const Plan &plan, hipStream_t s) {
     case KIND_STAGED: return launch_staged(p, plan.shape, plan.splits, s);
     case KIND_DMA: return launch_dma(p, plan.shape, plan.splits, s);
     case KIND_DMA_K128: return launch_dma_k128(p, s, nullptr, plan.shape == SHAPE_128);
-    case KIND_DMA_K128_SPLIT: return launch_dma_k128_split(p, plan.splits, s);
+    case KIND_DMA_K128_SPLIT: return launch_dma_k128_split(p, plan.splits, s, plan.shape == SHAPE_256);
     case KIND_SLAB: return launch_slab(p, plan.splits, s);
   }
   return hipErrorInvalidValue;
@@ -546,8 +546,9 @@ const char *mipgemm_variant_name_with_workspace(int64_t m, int64_t n, int64_t k,
   static const char *const names[][2] = {
       MIP_NAME("mfma_dma256"), MIP_NAME("mfma_dma128"), MIP_NAME("mfma_dma64"),
       MIP_NAME("mfma_dma64x256"), MIP_NAME("mfma_dma256x64"), MIP_NAME("mfma_dma64x128"),
-      MIP_NAME("mfma_dma128x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_slab16"),
-      MIP_NAME("mfma_slab32")};
+      MIP_NAME("mfma_dma128x64"), MIP_NAME("mfma_dma256_k128"), MIP_NAME("mfma_dma128_k128"),
+      MIP_NAME("mfma_dma128_k128_split"), MIP_NAME("mfma_dma256_k128_ragged"), MIP_NAME("mfma_slab16"),
+      MIP_NAME("mfma_slab32"), MIP_NAME("mfma_slab64")};
 #undef MIP_NAME
   const char *base = mip::plan_name(mip::choose_plan(p));
   for (const auto &nm : names)

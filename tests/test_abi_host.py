@@ -121,8 +121,9 @@ def test_variant_choice(M):
     assert name(4608, 4608, 4096, 4096, 0, 4608, 0, 4608, 0) == "mfma_dma256_k128"
     # unaligned operands cannot use the direct-to-LDS kernels
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, aligned16=False) == "mfma_tile128x64"
-    # a ragged row edge can, but not with the deep-k kernel; an unsigned operand can
-    assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256"
+    # a ragged row edge can, with the general form of the deep-k kernel; an unsigned operand can
+    assert name(8191, 8192, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_dma256_k128_ragged"
+    assert name(8192, 8192, 8256, 8256, 0, 8192, 0, 8192, 0) == "mfma_dma256"        # k % 128 != 0
     assert name(8192, 8192, 8192, 8192, 0, 8192, 0, 8192, 0, a_unsigned=True) == "mfma_dma256_k128"
     # a row-major B with n not a multiple of 16 cannot
     assert name(8192, 8191, 8192, 8192, 0, 8192, 0, 8192, 0) == "mfma_tile128x64"
@@ -140,8 +141,16 @@ def test_variant_choice(M):
     assert name(100000, 3, 2049, 2049, 0, 3, 0, 3, 0) == "mfma_tile256x64"
     # column-major C swaps the operand roles
     assert name(64, 100352, 576, 576, 0, 100352, 0, 64, 1) == "mfma_dma256x64"
-    # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels
-    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    # unsigned operands and ragged m / n edges stay on the direct-to-LDS kernels: with 128-deep
+    # blocks from k = 768 on (k a multiple of 128), the 64-deep kernel below and otherwise
+    assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128_k128_split"
+    assert name(1000, 3072, 512, 512, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    assert name(1000, 3072, 832, 832, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
+    # an accumulating call with an unsigned operand leaves the large tile below k = 4096
+    assert M.mipgemm_variant_name_for_mode(4096, 4096, 2048, 2048, 0, 4096, 0, 4096, 0, True, False, True,
+                                           1) == "mfma_dma128_k128"
+    assert M.mipgemm_variant_name_for_mode(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0, True, False, True,
+                                           1) == "mfma_dma256_k128"
     # whole 128 x 128 tiles and 128-deep k blocks: the kernel for large problems on that tile shape
     assert name(1024, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128_k128"
     assert name(2048, 2048, 2048, 2048, 0, 2048, 0, 2048, 0) == "mfma_dma128_k128"

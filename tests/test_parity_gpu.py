@@ -87,6 +87,8 @@ def kernel_that_runs(M, case, variant):
         assert name == "mfma_" + variant
     elif variant == "dma128k128split":
         assert name == "mfma_dma128_k128_split" or not case.m * case.n * case.k
+    elif variant == "dma256k128ragged":
+        assert name == "mfma_dma256_k128_ragged" or not case.m * case.n * case.k
     elif variant.startswith("dma") and not variant.endswith("k128"):
         assert name in ("mfma_" + variant, "mfma_tile" + variant[3:])
     _ran.setdefault(variant, set()).add(name)
@@ -471,6 +473,36 @@ def test_deep_k_kernel_general_form_with_k_ranges(gpu, oracle, case, splits):
         assert np.array_equal(got, want)
 
 
+def _k128_ragged_cases():
+    out = []
+    idx = 0
+    for (m, n, k) in ((400, 528, 384), (256, 256, 128), (272, 1040, 256), (1008, 304, 640), (300, 530, 256)):
+        for uns in (0, 1, 2):
+            for mode in (W.OVERWRITE, W.ACCUMULATE):
+                orders = ((0, 1, 0), (0, 1, 1)) if m % 16 or n % 16 else ((0, 0, 0), (0, 1, 0), (1, 0, 1), (1, 1, 0))
+                for (oa, ob, oc) in orders:
+                    out.append(W.Case(
+                        "k128ragged_%dx%dx%d_u%d_m%d_%d%d%d" % (m, n, k, uns, mode, oa, ob, oc), 8, idx,
+                        m, n, k, a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob,
+                        orderC=oc, pad=16 * (idx % 3), mode=mode,
+                        a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+                        b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+                        c_dist=("uniform", -1000, 1000), seed=11))
+                    idx += 1
+    return out
+
+
+@pytest.mark.parametrize("case", _k128_ragged_cases(), ids=lambda c: c.name)
+def test_deep_k_kernel_general_form_on_large_tiles(gpu, oracle, case):
+    """The 256 x 256 form of the kernel with 128-deep blocks on ragged, unpadded operands: loads
+    that would leave an operand are redirected inside it, the write-back stops at the edge."""
+    name = gpu.mipgemm_variant_name
+    with VariantEnv("dma256k128ragged"):
+        assert name(case.m, case.n, case.k, case.lda, case.orderA, case.ldb, case.orderB, case.ldc,
+                    case.orderC, case.a_unsigned, case.b_unsigned, True) == "mfma_dma256_k128_ragged"
+    check_case(gpu, oracle, case, "dma256k128ragged")
+
+
 @pytest.mark.parametrize("spec", [(272, 1008, 8192, 0, 0, W.OVERWRITE, 1), (256, 1024, 6144, 0, 1, W.ACCUMULATE, 0),
                                   (640, 400, 8320, 1, 0, W.OVERWRITE, 2), (384, 1536, 16384, 0, 0, W.ACCUMULATE, 0)],
                          ids=lambda s: "x".join(map(str, s)))
@@ -485,6 +517,27 @@ def test_deep_k_over_few_tiles_as_dispatched(gpu, oracle, spec):
                   c_dist=("uniform", -1000, 1000), seed=12)
     assert gpu.mipgemm_variant_name_for_mode(m, n, k, case.lda, oa, case.ldb, ob, case.ldc, 0, uns == 1,
                                              uns == 2, True, mode) == "mfma_dma128_k128_split"
+    check_case(gpu, oracle, case, "auto")
+
+
+@pytest.mark.parametrize("spec", [
+    (3600, 3632, 2048, 0, 0, W.OVERWRITE, 0, "mfma_dma256_k128_ragged"),
+    (3600, 3600, 2048, 0, 1, W.ACCUMULATE, 0, "mfma_dma256_k128_ragged"),
+    (3600, 3600, 2176, 1, 0, W.OVERWRITE, 2, "mfma_dma256_k128_ragged"),
+    (3600, 3600, 2048, 0, 0, W.ACCUMULATE, 1, "mfma_dma128_k128_split"),
+    (1000, 3072, 768, 0, 0, W.OVERWRITE, 1, "mfma_dma128_k128_split"),
+    (1520, 1520, 2048, 0, 0, W.ACCUMULATE, 2, "mfma_dma128_k128_split")], ids=lambda s: "x".join(map(str, s)))
+def test_aligned_ragged_shapes_as_dispatched(gpu, oracle, spec):
+    """Aligned operands whose m or n is no multiple of the tile: the dispatcher itself takes the
+    general forms of the kernel with 128-deep blocks (the name is asserted)."""
+    m, n, k, oa, ob, mode, uns, want = spec
+    case = W.Case("ragged_%dx%dx%d_%d%d_m%d_u%d" % (m, n, k, oa, ob, mode, uns), 8, 0, m, n, k,
+                  a_unsigned=uns == 1, b_unsigned=uns == 2, orderA=oa, orderB=ob, pad=16, mode=mode,
+                  a_dist=("uniform", 0, 255) if uns == 1 else ("uniform", -128, 127),
+                  b_dist=("uniform", 0, 255) if uns == 2 else ("uniform", -128, 127),
+                  c_dist=("uniform", -1000, 1000), seed=13)
+    assert gpu.mipgemm_variant_name_for_mode(m, n, k, case.lda, oa, case.ldb, ob, case.ldc, 0, uns == 1,
+                                             uns == 2, True, mode) == want
     check_case(gpu, oracle, case, "auto")
 
 
