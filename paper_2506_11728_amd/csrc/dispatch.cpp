@@ -308,7 +308,8 @@ Plan choose_plan(const Problem &p) {
     // k = 6144: (768, 768, 6144) 18.1/18.5 -> 14.7/17.0, (512, 1568, 6144) 20.1/26.8 -> 16.9/19.8.
     // Not below: at k = 4608 the atomics cost what the ranges save, (1024, 1024, 4608)
     // 13.2/15.4 against 19.8/22.0, (512, 1568, 4608) 14.7/16.7 against 16.7/20.0.
-    else if (p.m > 64 && p.n > 64 && p.k >= (p.accumulate ? 6144 : 8192) && tile_count(p, SHAPE_128) >= 16 &&
+    else if (!p.out_float && p.m > 64 && p.n > 64 && p.k >= (p.accumulate ? 6144 : 8192) &&
+             tile_count(p, SHAPE_128) >= 16 &&
              tile_count(p, SHAPE_128) <= 3 * kComputeUnits / 8 && dma_k128_split_eligible(p))
       plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
     // (An accumulating call with an unsigned operand pays more for the large tile's write-back,

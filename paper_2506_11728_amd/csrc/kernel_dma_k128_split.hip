@@ -8,7 +8,7 @@
 namespace mip {
 
 bool dma_k128_split_eligible(const Problem &p, bool large) {
-  if (p.conv || p.batch != 1 || p.out_float || p.k % KD2 || p.k < KD2) return false;
+  if (p.conv || p.batch != 1 || p.k % KD2 || p.k < KD2) return false;
   const bool a_kc = p.a_sk == 1, b_kc = p.b_sk == 1;
   if (!a_kc && (p.a_sm != 1 || p.m % 16)) return false;  // a strided operand comes in 16-byte chunks
   if (!b_kc && (p.b_sn != 1 || p.n % 16)) return false;
@@ -39,14 +39,16 @@ hipError_t launch_general(const Problem &p, int splits, hipStream_t s) {
   P.tiles_m = (int)((p.m + BM - 1) / BM);
   P.tiles_n = (int)((p.n + BN - 1) / BN);
   P.nkt = (int)(p.k / KD2);
-  if (splits < 1 || BM != 128) splits = 1;  // k ranges on the small tile only
+  // k ranges on the small tile only, and only into an int32 C (float sums must not be combined
+  // in arbitrary order, and an int8 C holds no partial sums)
+  if (splits < 1 || BM != 128 || p.out_float) splits = 1;
   if (splits > P.nkt) splits = P.nkt;       // every range holds at least one block
   if (splits > 65535) splits = 65535;
   P.splits = splits;
   P.atomic = splits > 1;
   P.accumulate = p.accumulate;
-  P.out_float = 0;
-  P.scale = 1.0f;
+  P.out_float = p.out_float;
+  P.scale = p.scale;
   P.ksum = nullptr;
   const int ntiles = P.tiles_m * P.tiles_n;
   P.first_round = (int)compute_units();

@@ -98,7 +98,8 @@ hipError_t launch_dma_k128(const Problem &p, hipStream_t s, unsigned long long *
                            bool small = false);
 
 // The general 128 x 128 form of that kernel: any m and n (a strided operand's extent a multiple
-// of 16), int32 output, k in `splits` ranges that add into C (an overwriting call zeroes C first).
+// of 16), k in `splits` ranges that add into an int32 C (an overwriting call zeroes C first; a
+// float or int8 output takes one range).
 // large: on 256 x 256 tiles (one k range).
 bool dma_k128_split_eligible(const Problem &p, bool large = false);
 hipError_t launch_dma_k128_split(const Problem &p, int splits, hipStream_t s, bool large = false);

@@ -48,7 +48,8 @@ def _cases():
     return out
 
 
-VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128", "dma128k128", "slab16", "slab32"]
+VARIANTS = ["auto", "simple", "tile64", "dma128", "dma256k128", "dma128k128", "dma128k128split", "dma256k128ragged",
+            "slab16", "slab32"]
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

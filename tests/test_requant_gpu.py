@@ -76,7 +76,7 @@ def _cases():
 
 
 @pytest.mark.parametrize("variant", ["auto", "simple", "tile64", "tile128x64", "dma64", "dma128", "dma64x256",
-                                     "dma256", "dma256k128", "dma128k128"])
+                                     "dma256", "dma256k128", "dma128k128", "dma128k128split", "dma256k128ragged"])
 @pytest.mark.parametrize("case,scale", _cases(), ids=lambda x: x.name if hasattr(x, "name") else None)
 def test_requant_against_oracle(gpu, oracle, case, scale, variant):
     print("case", case.name, "scale", scale, "variant", variant, flush=True)
