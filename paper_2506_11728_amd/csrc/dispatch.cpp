@@ -260,7 +260,6 @@ Plan choose_plan(const Problem &p) {
     // rows on: (1, 4096, 1024) 2.9/3.5 against 3.4/4.1, (16, 8192, 1024) 4.2/5.7 against 3.9/4.7;
     // with fewer rows from k = 1536: (8, 4096, 1536) 4.0/5.1 against 3.5/4.3,
     // (4, 16384, 1536) 6.2/8.4 against 4.6/8.2.)
-    const bool uns_acc = (p.a_unsigned || p.b_unsigned) && p.accumulate;
     const bool adds_in_place = p.accumulate && !p.out_float && p.k >= (p.m >= 16 ? 1024 : 1536);
     const bool slab_ok = p.m <= 64 && !adds_in_place && slab_eligible(p, 1);
     // Slabs of 32 columns re-read A half as often and need half the workgroups; they win
@@ -312,12 +311,6 @@ Plan choose_plan(const Problem &p) {
              tile_count(p, SHAPE_128) >= 16 &&
              tile_count(p, SHAPE_128) <= 3 * kComputeUnits / 8 && dma_k128_split_eligible(p))
       plan = {KIND_DMA_K128_SPLIT, SHAPE_128, k128_ranges(p)};
-    // (An accumulating call with an unsigned operand pays more for the large tile's write-back,
-    // which then carries the old words and the corrections through the registers together:
-    // up to k = 4096 the 128 x 128 form is the faster one there; 4096^2 x 1024, B unsigned:
-    // 61 us against 45.)
-    else if (sh == SHAPE_256 && uns_acc && p.k >= 1024 && p.k < 4096 && dma_k128_eligible(p, true))
-      plan = {KIND_DMA_K128, SHAPE_128, 1};
     else if (sh == SHAPE_256 && p.k >= 1024 && dma_k128_eligible(p)) plan = {KIND_DMA_K128, sh, 1};
     // (the same kernel on 128 x 128 tiles, where that is the shape and m, n, k are whole tiles
     // and blocks: 5 to 15 % over the 64-deep kernel of that shape; measured warm/cold, us:
@@ -329,8 +322,7 @@ Plan choose_plan(const Problem &p) {
     // kernels with their masked edges used to serve.  On 256 x 256 tiles from k = 2048 on;
     // measured warm, us, overwriting: 4000^2 x 4096 105 -> 60, 4000^2 x 8192 193 -> 112,
     // 8000^2 x 4096 402 -> 254, (6000, 4000, 8192) 325 -> 198, (5008, 3008, 2048) 69 -> 42.
-    // (Not for an unsigned operand in an accumulating call below k = 4096, as above.)
-    else if (sh == SHAPE_256 && p.k >= 2048 && !(uns_acc && p.k < 4096) && dma_k128_split_eligible(p, true))
+    else if (sh == SHAPE_256 && p.k >= 2048 && dma_k128_split_eligible(p, true))
       plan = {KIND_DMA_K128_SPLIT, SHAPE_256, 1};
     // On 128 x 128 tiles otherwise, from k = 768 on: 4000^2 x 1024 48 -> 30 (with an unsigned
     // operand 88 -> 33), 8000^2 x 1024 162 -> 93, (3000, 2000, 1024) 15.8 -> 14.0,

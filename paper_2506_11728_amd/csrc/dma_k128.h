@@ -402,9 +402,12 @@ __global__ __launch_bounds__(NTHREADS) void dma128_kernel(DmaParams P) {
   // compiler does not know that the statements above write them late); the last step has no
   // barrier of its own: wait until no wave reads the stages any more.
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  const Correction16<FM, FN> corr = unsigned_correction16<FM, FN>(sumA, sumB, FLIP_A, FLIP_B, lane);
-  const int64_t mw = m0 + wm * WM, nw = n0 + wn * WN;  // the wave's sub-tile
   int32_t *patch = reinterpret_cast<int32_t *>(smem) + wave * Patch16<FN>::WORDS;
+  // (the corrections of an unsigned operand: behind the four patches, one area per wave)
+  const Correction16<FM, FN> corr = unsigned_correction16<FM, FN>(
+      sumA, sumB, FLIP_A, FLIP_B, lane,
+      reinterpret_cast<int32_t *>(smem) + 4 * Patch16<FN>::WORDS + wave * Correction16<FM, FN>::WORDS);
+  const int64_t mw = m0 + wm * WM, nw = n0 + wn * WN;  // the wave's sub-tile
   // an int8 output is a matrix of bytes, ldc counted in bytes
   void *C = P.out_float == 2 ? static_cast<void *>(reinterpret_cast<int8_t *>(P.C) + mw * P.ldc + nw)
                              : static_cast<void *>(P.C + mw * P.ldc + nw);

@@ -11,43 +11,48 @@
 namespace mip {
 
 // Unsigned-operand correction (exact modulo 2^32): what has to be added to every element of
-// block row i (row_corr[i], the same in all four registers) and to the four registers of
-// every block in block column j (col_corr[j]).  sumA[i]: this lane's partial sum over k of
-// row (16 i + l % 16) of the staged A, the four lane groups l / 16 holding four quarters of
-// every 64 k; sumB[j]: the same for column (16 j + l % 16) of B.  The write-back adds them on
-// the way to LDS, so that the accumulators are never all in ordinary registers at once.
+// row r of the wave's sub-tile (rows[r]) and of column c (cols[c]).  Kept in LDS, in an area of
+// 16 * (FM + FN) words private to the wave, and added after the blocks have been turned into
+// rows of C (one four-word read per lane for its columns, one word per row piece): adding it
+// on the way into LDS instead takes every accumulator through the ordinary registers together
+// with 5 * FN correction registers, which an accumulating call, with the old words of C in
+// flight as well, has no room for.
+// sumA[i]: this lane's partial sum over k of row (16 i + l % 16) of the staged A, the four lane
+// groups l / 16 holding four quarters of every 64 k; sumB[j]: the same for column
+// (16 j + l % 16) of B.
 template <int FM, int FN>
 struct Correction16 {
-  int row_corr[FM];
-  v4i col_corr[FN];
+  const int32_t *rows;  // 16 * FM words
+  const int32_t *cols;  // 16 * FN words
+  static constexpr int WORDS = 16 * (FM + FN);
 };
 
+// area: Correction16<FM, FN>::WORDS words of LDS that no wave reads as operand stages any more.
 template <int FM, int FN>
 __device__ __forceinline__ Correction16<FM, FN> unsigned_correction16(const int (&sumA)[FM],
                                                                       const int (&sumB)[FN],
                                                                       bool a_unsigned, bool b_unsigned,
-                                                                      int lane) {
-  Correction16<FM, FN> c;
-#pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    c.col_corr[j] = v4i{0, 0, 0, 0};
-    if (a_unsigned) {  // sum_p (a - 128) b + 128 sum_p b: needs B's column sums
-      int total = sumB[j] + __shfl_xor(sumB[j], 16);
-      total += __shfl_xor(total, 32);  // every lane: column l % 16 of block column j
-#pragma unroll
-      for (int v = 0; v < 4; ++v) c.col_corr[j][v] = 128 * __shfl(total, 4 * (lane >> 4) + v);
-    }
-  }
+                                                                      int lane, int32_t *area) {
+  if (!a_unsigned && !b_unsigned) return Correction16<FM, FN>{area, area + 16 * FM};  // never read
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-    c.row_corr[i] = 0;
-    if (b_unsigned) {  // needs A's row sums, which end up in the lanes that own the row
-      int total = sumA[i] + __shfl_xor(sumA[i], 16);
-      total += __shfl_xor(total, 32);
-      c.row_corr[i] = 128 * total;
+    int total = 0;
+    if (b_unsigned) {  // sum_p a (b - 128) + 128 sum_p a: needs A's row sums
+      total = sumA[i] + __shfl_xor(sumA[i], 16);
+      total += __shfl_xor(total, 32);  // every lane: row l % 16 of block row i
     }
+    if (lane < 16) area[16 * i + lane] = 128 * total;
   }
-  return c;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    int total = 0;
+    if (a_unsigned) {  // sum_p (a - 128) b + 128 sum_p b: needs B's column sums
+      total = sumB[j] + __shfl_xor(sumB[j], 16);
+      total += __shfl_xor(total, 32);  // every lane: column l % 16 of block column j
+    }
+    if (lane < 16) area[16 * (FM + j) + lane] = 128 * total;
+  }
+  return Correction16<FM, FN>{area, area + 16 * FM};
 }
 
 // The wave's patch of LDS for the write-back: 16 rows of 16 * FN words, rows 4 words further
@@ -90,10 +95,10 @@ __device__ __forceinline__ void store_blocks16_as(const v4i (&acc)[FM][FN], void
   int8_t *Q = static_cast<int8_t *>(Cv);
   // An accumulating call reads the old words of a strip of sixteen rows one strip ahead: the
   // loads of strip i + 1 are in flight while strip i is turned and stored, so that only the
-  // first strip's load latency is exposed (4096^3 accumulating 79 -> 74 us).  Not with an
-  // unsigned operand's corrections live as well: there the second set of old words costs more
-  // in registers than it saves (A unsigned: 98 -> 107 us), and each strip fetches its own.
-  constexpr bool AHEAD = ACCUMULATE && !CORRECT;
+  // first strip's load latency is exposed (4096^3 accumulating 79 -> 74 us).
+  constexpr bool AHEAD = ACCUMULATE;
+  // (same wave wrote the corrections: LDS operations of a wave complete in order)
+  const v4i colc = CORRECT ? *reinterpret_cast<const v4i *>(corr.cols + c0) : v4i{0, 0, 0, 0};
   v4i old[2][PASSES];
   auto fetch_old = [&](int i, v4i (&into)[PASSES]) {
 #pragma unroll
@@ -109,22 +114,21 @@ __device__ __forceinline__ void store_blocks16_as(const v4i (&acc)[FM][FN], void
   for (int i = 0; i < FM; ++i) {
     if (!FULL && i * 16 >= rows) break;  // wave-uniform
     if (ACCUMULATE) {
-      if (!AHEAD) fetch_old(i, old[i & 1]);
-      else if (i + 1 < FM) fetch_old(i + 1, old[(i + 1) & 1]);
-      // keep the loads up here, in flight during the turn: under register pressure (an
-      // unsigned operand's corrections) the scheduler otherwise sinks each load to its use
-      // and the wave waits for them one by one
+      if (i + 1 < FM) fetch_old(i + 1, old[(i + 1) & 1]);
+      // keep the loads up here, in flight during the turn: under register pressure the
+      // scheduler otherwise sinks each load to its use and the wave waits for them one by one
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int j = 0; j < FN; ++j)
-      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) =
-          CORRECT ? acc[i][j] + corr.col_corr[j] + corr.row_corr[i] : acc[i][j];
+      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) = acc[i][j];
     // same wave wrote and reads: LDS operations of a wave complete in order
     v4i val[PASSES];
 #pragma unroll
-    for (int t = 0; t < PASSES; ++t)
+    for (int t = 0; t < PASSES; ++t) {
       val[t] = *reinterpret_cast<const v4i *>(patch + (t * ROWS_PER_PASS + r0) * PITCH + c0);
+      if (CORRECT) val[t] += colc + corr.rows[i * 16 + t * ROWS_PER_PASS + r0];
+    }
 #pragma unroll
     for (int t = 0; t < PASSES; ++t) {
       const int row = i * 16 + t * ROWS_PER_PASS + r0;
@@ -173,12 +177,12 @@ __device__ __forceinline__ void add_blocks16_atomic(const v4i (&acc)[FM][FN], in
     if (i * 16 >= rows) break;  // wave-uniform
 #pragma unroll
     for (int j = 0; j < FN; ++j)
-      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) =
-          CORRECT ? acc[i][j] + corr.col_corr[j] + corr.row_corr[i] : acc[i][j];
+      *reinterpret_cast<v4i *>(patch + (lane & 15) * PITCH + 16 * j + 4 * (lane >> 4)) = acc[i][j];
     // same wave wrote and reads: LDS operations of a wave complete in order
     int val[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) val[r] = patch[r * PITCH + lane];
+    for (int r = 0; r < 16; ++r)
+      val[r] = patch[r * PITCH + lane] + (CORRECT ? corr.cols[lane] + corr.rows[i * 16 + r] : 0);
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (i * 16 + r < rows && lane < cols)

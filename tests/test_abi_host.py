@@ -146,11 +146,11 @@ def test_variant_choice(M):
     assert name(1000, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128_k128_split"
     assert name(1000, 3072, 512, 512, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
     assert name(1000, 3072, 832, 832, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128"
-    # an accumulating call with an unsigned operand leaves the large tile below k = 4096
+    # an accumulating call with an unsigned operand stays on the large tile
     assert M.mipgemm_variant_name_for_mode(4096, 4096, 2048, 2048, 0, 4096, 0, 4096, 0, True, False, True,
-                                           1) == "mfma_dma128_k128"
-    assert M.mipgemm_variant_name_for_mode(4096, 4096, 4096, 4096, 0, 4096, 0, 4096, 0, True, False, True,
                                            1) == "mfma_dma256_k128"
+    assert M.mipgemm_variant_name_for_mode(4000, 4000, 2048, 2048, 0, 4000, 0, 4000, 0, True, False, True,
+                                           1) == "mfma_dma256_k128_ragged"
     # whole 128 x 128 tiles and 128-deep k blocks: the kernel for large problems on that tile shape
     assert name(1024, 3072, 768, 768, 0, 3072, 0, 3072, 0, a_unsigned=True) == "mfma_dma128_k128"
     assert name(2048, 2048, 2048, 2048, 0, 2048, 0, 2048, 0) == "mfma_dma128_k128"

@@ -524,7 +524,8 @@ def test_deep_k_over_few_tiles_as_dispatched(gpu, oracle, spec):
     (3600, 3632, 2048, 0, 0, W.OVERWRITE, 0, "mfma_dma256_k128_ragged"),
     (3600, 3600, 2048, 0, 1, W.ACCUMULATE, 0, "mfma_dma256_k128_ragged"),
     (3600, 3600, 2176, 1, 0, W.OVERWRITE, 2, "mfma_dma256_k128_ragged"),
-    (3600, 3600, 2048, 0, 0, W.ACCUMULATE, 1, "mfma_dma128_k128_split"),
+    (3600, 3600, 2048, 0, 0, W.ACCUMULATE, 1, "mfma_dma256_k128_ragged"),
+    (3600, 3600, 1024, 0, 0, W.ACCUMULATE, 2, "mfma_dma128_k128_split"),
     (1000, 3072, 768, 0, 0, W.OVERWRITE, 1, "mfma_dma128_k128_split"),
     (1520, 1520, 2048, 0, 0, W.ACCUMULATE, 2, "mfma_dma128_k128_split")], ids=lambda s: "x".join(map(str, s)))
 def test_aligned_ragged_shapes_as_dispatched(gpu, oracle, spec):
