@@ -10,7 +10,8 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 
 VARIANTS = [None, None, None, "dma64", "dma128", "dma64x128", "dma128x64", "dma64x256", "dma256x64", "tile64",
-            "tile128x64", "dma128k128", "dma256k128", "slab16", "slab32", "slab64", "dma256"]
+            "tile128x64", "dma128k128", "dma256k128", "slab16", "slab32", "slab64", "dma256", "dma128k128split",
+            "dma256k128ragged"]
 ENTRIES = ["s8s8s32", "u8s8s32", "s8u8s32", "s8s8f32", "u8s8s8", "u8s8s32_packed", "s16"]
 
 
